@@ -1,0 +1,227 @@
+"""Pins for the oracle's training and inference against plaintext references."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import plain_cart
+from oracle import Oracle, X_T, X_F, X_M, X_C, X_GAMMA, X_SD, X_L, X_SCORE, X_C_PAPER
+from paper_2305_00645_amd import workloads as wl
+
+M64 = (1 << 64) - 1
+
+
+def run_oracle_train(seed, w, tau=16, H=None, check_levels=True):
+    H = w["H"] if H is None else H
+    N, d, K = w["N"], w["d"], w["K"]
+    o = Oracle(seed, tau=tau, K=K)
+    sx, sy = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
+    o.train_create(sx, sy, N, d, H)
+    ref = plain_cart.train(w["X"], w["y"], K, H, tau)
+    CW = d * K + K
+    for h in range(H):
+        o.train_level(h)
+        if not check_levels:
+            continue
+        nh = 1 << h
+        L = ref["levels"][h]
+        assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), L["M"])
+        C = Oracle.rec(o.train_export(X_C)).astype(np.int64).reshape(nh, CW)
+        for r in range(nh):
+            assert np.array_equal(C[r, :d * K].reshape(d, K), L["n1"][r]), (h, r)
+            assert np.array_equal(C[r, d * K:], L["tot"][r]), (h, r)
+        S = Oracle.rec(o.train_export(X_SCORE)).astype(np.int64).reshape(nh, d)
+        assert np.array_equal(S, np.array(L["score"]))
+        assert np.array_equal(Oracle.rec(o.train_export(X_SD)).astype(np.int64), np.array(L["SD"]))
+        G = Oracle.rec(o.train_export(X_GAMMA)).astype(np.int64).reshape(nh, d)
+        assert np.array_equal(G, np.array(L["gamma"]))
+        # per-sample leaf one-hot: 1 exactly at the sample's node when that node is a real leaf
+        LT = Oracle.rec(o.train_export(X_L)).astype(np.int64).reshape(nh, -1)[:, :N]
+        Fbefore = np.array([1 if (L["split"][r] or _was_leaf(ref, h, r)) else 0 for r in range(nh)])
+        want = ((L["M"][None, :] - (nh - 1)) == np.arange(nh)[:, None]) & (Fbefore[:, None] == 1)
+        assert np.array_equal(LT, want.astype(np.int64))
+    feat, leaf = o.train_finish()
+    T = Oracle.rec(o.train_export(X_T)).astype(np.int64)
+    F = Oracle.rec(o.train_export(X_F)).astype(np.int64)
+    assert np.array_equal(T, ref["T"])
+    assert np.array_equal(F, ref["F"])
+    assert np.array_equal(Oracle.rec(feat).astype(np.int64), ref["T"][:(1 << H) - 1])
+    assert np.array_equal(Oracle.rec(leaf).astype(np.int64), ref["T"][(1 << H) - 1:])
+    assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), ref["levels"][H]["M"])
+    return o, ref, (feat, leaf)
+
+
+def _was_leaf(ref, h, r):
+    """Node type before this level's update: a node is a real leaf iff it is the
+    root or its parent was split."""
+    if h == 0:
+        return True
+    return bool(ref["levels"][h - 1]["split"][r // 2])
+
+
+def check_tree_encoding(F, H):
+    """Every root-to-bottom path reads 0..0, then at most one 1, then 2..2 (Sec. IV)."""
+    for leafpos in range(1 << H):
+        node = (1 << H) - 1 + leafpos
+        path = []
+        while True:
+            path.append(int(F[node]))
+            if node == 0:
+                break
+            node = (node - 1) // 2
+        path = path[::-1]
+        s = "".join(map(str, path))
+        assert s.lstrip("0").lstrip("1").strip("2") == "" and s.count("1") <= 1, s
+        assert set(path) <= {0, 1, 2}
+
+
+def test_c1_full_training_matches_plaintext_cart(seed):
+    w = wl.c1_train()
+    o, ref, _ = run_oracle_train(seed, w)
+    check_tree_encoding(ref["F"], w["H"])
+    # the learned tree fits the (noisy) training labels far better than chance
+    acc = (plain_cart.predict(ref["T"], w["H"], w["X"]) == w["y"]).mean()
+    assert acc > 0.85
+
+
+@pytest.mark.parametrize("H", [1, 4])
+def test_c2_training_matches_plaintext_cart(seed, H):
+    w = wl.c2_train()
+    run_oracle_train(seed, w, H=H)
+
+
+def test_c2_depth7_tree_and_structure(seed):
+    w = wl.c2_train()
+    o, ref, _ = run_oracle_train(seed, w, H=7, check_levels=False)
+    check_tree_encoding(ref["F"], 7)
+    assert (ref["F"] == 2).sum() > 0 and (ref["F"] == 0).sum() > 5
+
+
+def test_multiclass_and_other_tau(seed):
+    rng = np.random.default_rng(77)
+    N, d, K = 150, 9, 4
+    X = (rng.random((N, d)) < 0.4).astype(np.uint64)
+    y = (X[:, 0].astype(np.int64) * 2 + X[:, 3].astype(np.int64) + (rng.random(N) < 0.1)) % K
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    w = dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3)
+    run_oracle_train(seed, w, tau=10)
+
+
+def test_small_c3_shape_matches_plaintext_cart(seed):
+    w = wl.c3_train(N=600, H=3, n_thr=4)
+    assert w["d"] == 6 * 4 + 102
+    run_oracle_train(seed, w, check_levels=False)
+
+
+def test_degenerate_inputs(seed):
+    # one class only: the root is pure, everything below is a dummy, all labels equal
+    X = np.array([[0, 1], [1, 1], [1, 0], [0, 0], [1, 1]], dtype=np.uint64)
+    y = np.ones(5, dtype=np.int64)
+    Y = np.zeros((5, 2), dtype=np.uint64); Y[:, 1] = 1
+    o, ref, (feat, leaf) = run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=2))
+    assert list(ref["F"]) == [1, 2, 2, 2, 2, 2, 2]
+    assert set(Oracle.rec(leaf).tolist()) == {1}
+    # depth 0: only a label
+    o, ref, (feat, leaf) = run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=0))
+    assert feat.shape[1] == 0 and Oracle.rec(leaf).tolist() == [1]
+    # a single candidate column, more levels than candidates
+    X1 = np.array([[0], [1], [1], [0]], dtype=np.uint64)
+    y1 = np.array([0, 1, 1, 0])
+    Y1 = np.zeros((4, 2), dtype=np.uint64); Y1[np.arange(4), y1] = 1
+    run_oracle_train(seed, dict(X=X1, Y=Y1, y=y1, N=4, d=1, K=2, H=2))
+
+
+def test_counter_array_paper_layout(seed):
+    """Row/column relations of the counter array (Sec. V-B, statistics counting)."""
+    w = wl.c1_train()
+    N, d, K = w["N"], w["d"], w["K"]
+    o = Oracle(seed, K=K)
+    o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, 2)
+    o.train_level(0)
+    C = Oracle.rec(o.train_export(X_C_PAPER)).astype(np.int64).reshape(1 + K, 2 * d)
+    X, y = w["X"].astype(np.int64), w["y"]
+    for k in range(d):
+        for v in (0, 1):
+            assert C[0, 2 * k + v] == (X[:, k] == v).sum()
+            for c in range(K):
+                assert C[c + 1, 2 * k + v] == ((X[:, k] == v) & (y == c)).sum()
+    assert np.array_equal(C[0], C[1:].sum(axis=0))
+
+
+def test_choice_close_to_real_valued_gini_and_exact_rational(seed):
+    """The chosen candidate's Gini index (definition of Sec. II-A) is within 2^(2-tau)
+    of the minimum over unused candidates, and by exact rational comparison
+    (cross-multiplication, valid here since N <= 8192) it is within two floor errors."""
+    for w, H, tau in ((wl.c1_train(), 3, 16), (wl.c2_train(), 5, 16), (wl.c2_train(), 3, 6)):
+        ref = plain_cart.train(w["X"], w["y"], w["K"], H, tau)
+        N, d, K = w["N"], w["d"], w["K"]
+        o = Oracle(seed, tau=tau, K=K)
+        o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, H)
+        gam = {0: np.ones(d, dtype=np.int64)}
+        for h in range(H):
+            o.train_level(h)
+            SD = Oracle.rec(o.train_export(X_SD)).astype(np.int64)
+            L = ref["levels"][h]
+            ngam = {}
+            for r in range(1 << h):
+                g = gam[r]
+                if L["split"][r] and g.sum() > 0:
+                    gr = plain_cart.gini_real(L["n1"][r], L["tot"][r])
+                    ex = plain_cart.scores_exact(L["n1"][r], L["tot"][r])
+                    free = [k for k in range(d) if g[k]]
+                    k = int(SD[r])
+                    assert g[k] == 1
+                    assert gr[k] <= min(gr[q] for q in free) + 2.0 ** (2 - tau)
+                    assert ex[k] >= max(ex[q] for q in free) - Fraction(2, 1 << tau)
+                g2 = g.copy(); g2[int(SD[r])] = 0
+                ngam[2 * r] = ngam[2 * r + 1] = g2
+            gam = ngam
+
+
+def test_wire_and_rounds_do_not_depend_on_data(seed):
+    """Only sizes and depth may show in the message pattern (Sec. I, goals)."""
+    res = []
+    for s in (11, 12):
+        w = wl.c1_train(N=64, d=6, depth=2, seed=s)
+        o = Oracle(seed, K=2)
+        o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), 64, 6, 2)
+        o.train_level(0); o.train_level(1); o.train_finish()
+        res.append((o.stats()[0], o.stats()[1].tolist(), o.op_counter()))
+    assert res[0] == res[1]
+
+
+# ---------------------------------------------------------------- inference
+@pytest.mark.parametrize("binary", [False, True])
+def test_inference_matches_plaintext_traversal(seed, binary):
+    w = wl.c4_infer(NI=300, H=5, binary=binary)
+    o = Oracle(seed)
+    sf, sl = o.share(w["feat"]), o.share(w["leaf"])
+    st = None if w["thr"] is None else o.share(w["thr"])
+    sI = o.share(w["I"].reshape(-1))
+    o.stats_reset()
+    R = o.infer(sf, st, sl, w["H"], sI, w["NI"], w["d"])
+    T = np.concatenate([w["feat"], w["leaf"]]).astype(np.int64)
+    thr = None if w["thr"] is None else np.concatenate([w["thr"], np.zeros(1 << w["H"], dtype=np.uint64)])
+    want = plain_cart.predict(T, w["H"], w["I"], thr)
+    assert np.array_equal(Oracle.rec(R).astype(np.int64), want)
+    rounds, _ = o.stats()
+    per_level = 9 + 9 + (0 if binary else 8)
+    assert rounds == w["H"] * per_level + 9
+
+
+def test_inference_on_trained_tree_equals_plaintext_prediction(seed):
+    w = wl.c1_train()
+    o, ref, (feat, leaf) = run_oracle_train(seed, w, check_levels=False)
+    rng = np.random.default_rng(5)
+    I = (rng.random((200, w["d"])) < 0.5).astype(np.uint64)
+    R = o.infer(feat, None, leaf, w["H"], o.share(I.reshape(-1)), 200, w["d"])
+    assert np.array_equal(Oracle.rec(R).astype(np.int64), plain_cart.predict(ref["T"], w["H"], I))
+
+
+def test_inference_depth0_and_single_instance(seed):
+    o = Oracle(seed)
+    leaf = o.share(np.array([3], dtype=np.uint64))
+    feat = np.zeros((3, 0), dtype=np.uint64)
+    I = o.share(np.array([1, 0], dtype=np.uint64))
+    R = o.infer(feat, None, leaf, 0, I, 1, 2)
+    assert Oracle.rec(R).tolist() == [3]
