@@ -1,0 +1,150 @@
+/*
+ * gtree.h — C ABI of the MI355X (gfx950) library for the hot path of GTree
+ * (arXiv 2305.00645): three-party semi-honest decision-tree training and
+ * inference on 2-out-of-3 replicated secret shares over Z_2^64.
+ *
+ * All three computing parties are simulated on ONE GPU.  Each party has its own
+ * share buffers and keys; a message between parties is a store into a device
+ * buffer that the receiving party's wavefront loads after a barrier; rounds and
+ * wire bytes are counted.  Offline material (edaBits, daBits) is derived from a
+ * dealer key inside the kernels, because the paper times only the online phase
+ * (Sec. VI).  This is a performance simulation, not a deployable secure system.
+ *
+ * Conventions
+ *  - Every pointer in a gt_shares is DEVICE memory, 8-byte aligned, owned by the
+ *    caller, of `n` 64-bit words.  party[p].own holds component p, party[p].next
+ *    component p+1 mod 3 (Sec. II-B: P_i holds (x_i, x_{i+1})).
+ *  - `plain` buffers are device memory too.
+ *  - Calls are enqueued on the context's HIP stream; gt_stats_get and the
+ *    destroy calls synchronise with it.  Calls on one context must not overlap.
+ *  - Return value 0 = success, negative = error; nothing is thrown or aborted.
+ *    After an error the output buffers are unspecified; the context stays usable
+ *    unless the error is GT_EHIP.
+ *  - Every protocol invocation consumes operation ids from the context's
+ *    counter; shares are a pure function of (keys, operation id, element index),
+ *    so results do not depend on launch shapes.  Two contexts created with the
+ *    same parameters and driven with the same calls produce identical shares.
+ *  - Public values (leaked by design, Sec. I): all sizes, depths, tau, K.
+ */
+#ifndef GTREE_H
+#define GTREE_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GT_OK 0
+#define GT_EINVAL (-1) /* null pointer, zero/oversized dimension, bad selector */
+#define GT_ENOMEM (-2) /* device allocation failed */
+#define GT_ESTATE (-3) /* level called out of order, object used after finish */
+#define GT_EHIP (-4)   /* a HIP runtime call or kernel launch failed */
+
+#define GT_MAX_DEPTH 16u       /* decision levels of a tree */
+#define GT_MAX_N (1u << 20)    /* training samples: keeps Gini terms below 2^40 */
+#define GT_MAX_K 16u           /* classes */
+#define GT_MAX_TAU 20u         /* fractional bits of the Gini quotients */
+
+typedef struct gt_ctx gt_ctx;     /* keys, operation counter, stream, message buffers */
+typedef struct gt_train gt_train; /* per-party shares of T, F, M, C, gamma and the data */
+typedef struct gt_tree gt_tree;   /* per-party shares of feature ids [, thresholds], labels */
+
+typedef struct { uint64_t *own, *next; } gt_plane2;
+typedef struct { gt_plane2 party[3]; size_t n; } gt_shares;
+
+/* rounds: protocol rounds; wire_bytes[a][b]: bytes party a sent to party b, each
+ * message of n elements of w bits counted as ceil(n*w/8); kernel_ms: GPU time of
+ * the calls, from HIP events on the context's stream. */
+typedef struct { uint64_t rounds; uint64_t wire_bytes[3][3]; double kernel_ms; } gt_stats;
+
+/* tau: fractional bits of the fixed-point Gini quotients (Sec. V-B); K: classes;
+ * seed[0..2]: pairwise keys k1..k3 (party p uses seed[p], seed[p+1 mod 3], Sec. III),
+ * seed[3]: dealer key for offline material, seed[4]: data owner / query user key;
+ * hip_stream: a hipStream_t or NULL for the default stream. */
+typedef struct {
+    uint32_t tau, K;
+    uint64_t seed[5][4];
+    uint32_t flags; /* reserved, 0 */
+    void *hip_stream;
+} gt_params;
+
+int gt_ctx_create(gt_ctx **out, const gt_params *params);
+int gt_ctx_destroy(gt_ctx *ctx);
+/* accumulated counters since creation or the last reset; synchronises the stream */
+int gt_stats_get(gt_ctx *ctx, gt_stats *out);
+int gt_stats_reset(gt_ctx *ctx);
+uint32_t gt_op_counter(const gt_ctx *ctx);
+const char *gt_strerror(int code);
+
+/* ---- sharing (Sec. II-B, Share^A / Rec^A; the data owner's and query user's role) */
+/* out.party[p] receive components (p, p+1) of a fresh sharing of plain[0..n). */
+int gt_share_a(gt_ctx *ctx, const uint64_t *plain_dev, size_t n, const gt_shares *out);
+/* plain[e] = x1 + x2 + x3, read as party 0's two components plus party 2's first. */
+int gt_reconstruct_a(gt_ctx *ctx, const gt_shares *in, uint64_t *plain_dev, size_t n);
+
+/* ---- building blocks (Sec. II-B multiplication; Sec. V-A equality test and
+ *      oblivious array access); each consumes one operation id (gt_div: tau+1) */
+int gt_mult(gt_ctx *ctx, const gt_shares *x, const gt_shares *y, size_t n, const gt_shares *z);
+/* z = arithmetic 0/1 sharing of [x == y]; y_pub_dev: public operand or NULL for 0 */
+int gt_eq_a(gt_ctx *ctx, const gt_shares *x, const uint64_t *y_pub_dev, size_t n, const gt_shares *z);
+/* z = arithmetic 0/1 sharing of [x >= y]; requires |x - y| < 2^63 as signed numbers */
+int gt_ge_a(gt_ctx *ctx, const gt_shares *x, const gt_shares *y, size_t n, const gt_shares *z);
+/* z[i] = W[u[i]], 0 when u[i] is outside [0, w); linear scan over all w entries */
+int gt_oaa(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z);
+/* q = floor(S * 2^tau / Q) for 0 <= S <= Q < 2^40, Q > 0 (restoring division) */
+int gt_div(gt_ctx *ctx, const gt_shares *S, const gt_shares *Q, size_t n, const gt_shares *q);
+
+/* ---- training (Sec. V-B: learning, heuristic computation, node split) ---- */
+/* X: N x dcols row-major 0/1 candidate columns, Y: N x K one-hot class indicators.
+ * Copies the data into the library's sample-contiguous layout and computes the
+ * one-time products X[i][k]*Y[i][c].  max_depth = H decision levels; level H holds
+ * labels.  N <= GT_MAX_N, 1 <= dcols, H <= GT_MAX_DEPTH. */
+int gt_train_create(gt_ctx *ctx, const gt_shares *X, const gt_shares *Y, size_t N,
+                    uint32_t dcols, uint32_t max_depth, gt_train **out);
+/* one level h (0 <= h < H, in order): data partition (h > 0), per-sample leaf
+ * flags, class counts for every (node, candidate), Gini scores by exact
+ * fixed-point division, first arg-max, updates of gamma, F, C, T. */
+int gt_train_level(gt_ctx *ctx, gt_train *tr, uint32_t h);
+/* level H: partition, class totals, majority label per node.  The tree's shares
+ * are copied into a new gt_tree (binary mode). */
+int gt_train_finish(gt_ctx *ctx, gt_train *tr, gt_tree **out);
+int gt_train_destroy(gt_train *tr);
+
+enum {
+    GT_X_T = 0,      /* 2^(H+1)-1 words */
+    GT_X_F = 1,      /* 2^(H+1)-1 */
+    GT_X_M = 2,      /* N */
+    GT_X_C = 3,      /* statistics of the level last processed: n_h x (d*K+K),
+                        [k*K+c] = count(column k = 1, class c), [d*K+c] = count(class c) */
+    GT_X_GAMMA = 4,  /* n_h x d, after the update */
+    GT_X_SD = 5,     /* n_h */
+    GT_X_L = 6,      /* n_h x N8 (N padded to a multiple of 8), node-major */
+    GT_X_SCORE = 7,  /* n_h x d masked scores */
+    GT_X_C_PAPER = 8 /* the statistics in the (1+K) x 2d counter-array layout of Sec. V-B */
+};
+size_t gt_train_export_size(const gt_train *tr, int what);
+int gt_train_export(gt_ctx *ctx, const gt_train *tr, int what, const gt_shares *out);
+/* Overwrite the state so that level h can be run next: M (N words), the tree entries
+ * of level h-1 (2^(h-1) words, ignored for h = 0), F, C and gamma of level h
+ * (2^h, 2^h*(d*K+K), 2^h*d words). */
+int gt_train_import(gt_ctx *ctx, gt_train *tr, uint32_t h, const gt_shares *M,
+                    const gt_shares *Tprev, const gt_shares *Flevel, const gt_shares *C,
+                    const gt_shares *gamma);
+
+/* ---- inference (Sec. V-C) ------------------------------------------------ */
+/* feat: 2^H-1 feature ids, thr: 2^H-1 thresholds or NULL (binary features),
+ * leaf: 2^H labels.  The shares are copied. */
+int gt_tree_import(gt_ctx *ctx, const gt_shares *feat, const gt_shares *thr,
+                   const gt_shares *leaf, uint32_t depth, gt_tree **out);
+int gt_tree_export(gt_ctx *ctx, const gt_tree *tree, const gt_shares *feat, const gt_shares *leaf);
+int gt_tree_destroy(gt_tree *tree);
+/* I: N_I x d row-major.  Binary mode: the fetched feature value is the branch bit.
+ * Threshold mode: branch bit = [value > threshold], values and thresholds in
+ * [0, 2^62).  R: N_I labels. */
+int gt_infer_batch(gt_ctx *ctx, const gt_tree *tree, const gt_shares *I, size_t N_I,
+                   uint32_t d, const gt_shares *R_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,286 @@
+// Device-side toolkit: PRF, per-party share arithmetic, message exchange and the
+// per-element protocol steps (Sec. II-B and Sec. V-A of the GTree paper), for gfx950.
+//
+// Execution model.  A workgroup is 3 wavefronts of 64 lanes: wavefront p IS party p
+// (threadIdx.y = p).  Lane l of each of the three wavefronts works on the same
+// element(s), each on its own party's two components.  A protocol message is a
+// store into the workgroup's region of the device-resident wire buffer; the
+// receiving wavefront loads it after a workgroup barrier.  A party's lanes never
+// read another party's shares or keys, only the words sent to it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint64_t u64;
+typedef uint32_t u32;
+
+#define GT_LANES 64
+#define GT_XW 8                                   // max words per lane per message
+#define GT_SLOT_WORDS (3 * GT_XW * GT_LANES)      // one message slot: 3 senders
+#define GT_WIRE_WORDS_PER_BLOCK (2 * GT_SLOT_WORDS)
+#define GT_KEY_DEALER 3
+#define GT_KEY_OWNER 4
+
+// ---------------------------------------------------------------------------------
+// ChaCha block function, 8 rounds, as a counter-based PRF.  State words 12..15 are
+// (block lo, block hi, op, stream); output word w (64 bit) is the little-endian pair
+// (2w, 2w+1).  The key is wave-uniform and lives in scalar registers.
+struct Key { u32 k[8]; };
+
+__device__ __forceinline__ u32 rotl32(u32 x, int r) { return __builtin_rotateleft32(x, r); }
+
+#define GT_QR(a, b, c, d)                                                                     \
+    a += b; d ^= a; d = rotl32(d, 16); c += d; b ^= c; b = rotl32(b, 12);                     \
+    a += b; d ^= a; d = rotl32(d, 8);  c += d; b ^= c; b = rotl32(b, 7);
+
+__device__ __forceinline__ void chacha8(const Key &key, u64 blk, u32 op, u32 stream, u64 (&out)[8])
+{
+    const u32 i0 = 0x61707865u, i1 = 0x3320646eu, i2 = 0x79622d32u, i3 = 0x6b206574u;
+    const u32 c12 = (u32)blk, c13 = (u32)(blk >> 32);
+    u32 x0 = i0, x1 = i1, x2 = i2, x3 = i3;
+    u32 x4 = key.k[0], x5 = key.k[1], x6 = key.k[2], x7 = key.k[3];
+    u32 x8 = key.k[4], x9 = key.k[5], x10 = key.k[6], x11 = key.k[7];
+    u32 x12 = c12, x13 = c13, x14 = op, x15 = stream;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        GT_QR(x0, x4, x8, x12) GT_QR(x1, x5, x9, x13) GT_QR(x2, x6, x10, x14) GT_QR(x3, x7, x11, x15)
+        GT_QR(x0, x5, x10, x15) GT_QR(x1, x6, x11, x12) GT_QR(x2, x7, x8, x13) GT_QR(x3, x4, x9, x14)
+    }
+    x0 += i0; x1 += i1; x2 += i2; x3 += i3;
+    x4 += key.k[0]; x5 += key.k[1]; x6 += key.k[2]; x7 += key.k[3];
+    x8 += key.k[4]; x9 += key.k[5]; x10 += key.k[6]; x11 += key.k[7];
+    x12 += c12; x13 += c13; x14 += op; x15 += stream;
+    out[0] = (u64)x0 | ((u64)x1 << 32);   out[1] = (u64)x2 | ((u64)x3 << 32);
+    out[2] = (u64)x4 | ((u64)x5 << 32);   out[3] = (u64)x6 | ((u64)x7 << 32);
+    out[4] = (u64)x8 | ((u64)x9 << 32);   out[5] = (u64)x10 | ((u64)x11 << 32);
+    out[6] = (u64)x12 | ((u64)x13 << 32); out[7] = (u64)x14 | ((u64)x15 << 32);
+}
+
+__device__ __forceinline__ u64 sel8(const u64 (&w)[8], u32 i)
+{
+    u64 a = (i & 1) ? w[1] : w[0], b = (i & 1) ? w[3] : w[2];
+    u64 c = (i & 1) ? w[5] : w[4], d = (i & 1) ? w[7] : w[6];
+    u64 ab = (i & 2) ? b : a, cd = (i & 2) ? d : c;
+    return (i & 4) ? cd : ab;
+}
+
+__device__ __forceinline__ Key load_key(const u32 *keys, int idx)
+{
+    Key k;
+#pragma unroll
+    for (int i = 0; i < 8; i++) k.k[i] = __builtin_amdgcn_readfirstlane(keys[idx * 8 + i]);
+    return k;
+}
+
+// The keys one party may use: its two pairwise keys (Sec. III) and, in this
+// simulation, the dealer key from which the offline material is derived.
+struct PartyKeys { Key own, nxt, dlr; };
+
+__device__ __forceinline__ PartyKeys load_party_keys(const u32 *keys, int p)
+{
+    PartyKeys K;
+    K.own = load_key(keys, p);
+    K.nxt = load_key(keys, p == 2 ? 0 : p + 1);
+    K.dlr = load_key(keys, GT_KEY_DEALER);
+    return K;
+}
+
+// word j of stream (op, stream) under one key
+__device__ __forceinline__ u64 prf_word(const Key &k, u32 op, u32 stream, u64 j)
+{
+    u64 w[8];
+    chacha8(k, j >> 3, op, stream, w);
+    return sel8(w, (u32)j & 7);
+}
+
+// party p's component of the zero sharing of element e: arithmetic / Boolean
+__device__ __forceinline__ u64 zero_a(const PartyKeys &K, u32 op, u32 stream, u64 e)
+{
+    return prf_word(K.own, op, stream, e) - prf_word(K.nxt, op, stream, e);
+}
+__device__ __forceinline__ u64 zero_b(const PartyKeys &K, u32 op, u32 stream, u64 e)
+{
+    return prf_word(K.own, op, stream, e) ^ prf_word(K.nxt, op, stream, e);
+}
+
+// ---------------------------------------------------------------------------------
+// A party's view of one shared element: components p (own) and p+1 (next).
+struct Sh { u64 o, n; };
+
+// kernel-argument view of a shared vector: six planes
+struct P6 { u64 *o[3]; u64 *n[3]; };
+
+__device__ __forceinline__ u64 *own_of(const P6 &a, int p) { return p == 0 ? a.o[0] : (p == 1 ? a.o[1] : a.o[2]); }
+__device__ __forceinline__ u64 *nxt_of(const P6 &a, int p) { return p == 0 ? a.n[0] : (p == 1 ? a.n[1] : a.n[2]); }
+__device__ __forceinline__ Sh ld(const P6 &a, int p, size_t e) { Sh v; v.o = own_of(a, p)[e]; v.n = nxt_of(a, p)[e]; return v; }
+__device__ __forceinline__ void st(const P6 &a, int p, size_t e, Sh v) { own_of(a, p)[e] = v.o; nxt_of(a, p)[e] = v.n; }
+
+// public constant c as the sharing (c, 0, 0): component 1 is party 0's own and party 2's next
+__device__ __forceinline__ Sh pub(int p, u64 c) { Sh v; v.o = p == 0 ? c : 0; v.n = p == 2 ? c : 0; return v; }
+__device__ __forceinline__ Sh operator+(Sh a, Sh b) { Sh v; v.o = a.o + b.o; v.n = a.n + b.n; return v; }
+__device__ __forceinline__ Sh operator-(Sh a, Sh b) { Sh v; v.o = a.o - b.o; v.n = a.n - b.n; return v; }
+__device__ __forceinline__ Sh operator^(Sh a, Sh b) { Sh v; v.o = a.o ^ b.o; v.n = a.n ^ b.n; return v; }
+__device__ __forceinline__ Sh scale(Sh a, u64 c) { Sh v; v.o = a.o * c; v.n = a.n * c; return v; }
+
+// party-local part of a product: z_p = x_p y_p + x_{p+1} y_p + x_p y_{p+1}
+__device__ __forceinline__ u64 prod3(Sh x, Sh y) { return x.o * (y.o + y.n) + x.n * y.o; }
+__device__ __forceinline__ u64 and3(Sh x, Sh y) { return (x.o & (y.o ^ y.n)) ^ (x.n & y.o); }
+
+// ---------------------------------------------------------------------------------
+// Message exchange inside the workgroup.  `reshare`: every party sends to its
+// predecessor (after a product, so that the receiver then holds (z_p, z_{p+1}));
+// `open`: every party sends to its successor (it hands over its first component).
+// Two slots alternate so that one barrier per message suffices.
+struct Wire {
+    u64 *base;   // this workgroup's region
+    int slot, p, lane;
+    __device__ __forceinline__ void init(u64 *wire)
+    {
+        base = wire + (size_t)blockIdx.x * GT_WIRE_WORDS_PER_BLOCK;
+        slot = 0; p = threadIdx.y; lane = threadIdx.x;
+    }
+    template <int NW>
+    __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
+    {
+        static_assert(NW <= GT_XW, "message too wide");
+        u64 *buf = base + slot * GT_SLOT_WORDS;
+        slot ^= 1;
+#pragma unroll
+        for (int j = 0; j < NW; j++) buf[(p * GT_XW + j) * GT_LANES + lane] = snd[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NW; j++) rcv[j] = buf[(from * GT_XW + j) * GT_LANES + lane];
+    }
+    template <int NW>
+    __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }
+    template <int NW>
+    __device__ __forceinline__ void open(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 0 ? 2 : p - 1); }
+    __device__ __forceinline__ u64 reshare1(u64 v) { u64 s[1] = { v }, r[1]; reshare<1>(s, r); return r[0]; }
+    __device__ __forceinline__ u64 open1(u64 v) { u64 s[1] = { v }, r[1]; open<1>(s, r); return r[0]; }
+};
+
+// ---------------------------------------------------------------------------------
+// Offline material of one element, party p's components (dealer stream 0, block e).
+struct Dealer { Sh rA, rho, bA; u32 bBo, bBn; };
+
+__device__ __forceinline__ Dealer dealer_from_block(const u64 (&D)[8], int p)
+{
+    const u64 r = D[0], beta = D[5] & 1;
+    const u64 rA2 = r - D[1] - D[2], rho2 = r ^ D[3] ^ D[4], bA2 = beta - D[6] - D[7];
+    const u32 b0 = (u32)(D[5] >> 1) & 1, b1 = (u32)(D[5] >> 2) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
+    Dealer d;
+    d.rA.o = p == 0 ? D[1] : (p == 1 ? D[2] : rA2);   d.rA.n = p == 0 ? D[2] : (p == 1 ? rA2 : D[1]);
+    d.rho.o = p == 0 ? D[3] : (p == 1 ? D[4] : rho2); d.rho.n = p == 0 ? D[4] : (p == 1 ? rho2 : D[3]);
+    d.bA.o = p == 0 ? D[6] : (p == 1 ? D[7] : bA2);   d.bA.n = p == 0 ? D[7] : (p == 1 ? bA2 : D[6]);
+    d.bBo = p == 0 ? b0 : (p == 1 ? b1 : b2);         d.bBn = p == 0 ? b1 : (p == 1 ? b2 : b0);
+    return d;
+}
+
+__device__ __forceinline__ Dealer dealer_of(const PartyKeys &K, int p, u32 op, u64 e)
+{
+    u64 D[8];
+    chacha8(K.dlr, e, op, 0, D);
+    return dealer_from_block(D, p);
+}
+
+// ---------------------------------------------------------------------------------
+// Per-element protocols, one element per lane.  Every lane of the workgroup must
+// call them together (they contain barriers); inactive lanes pass zeros.
+
+// product with reshare: returns (z_p, z_{p+1})
+__device__ __forceinline__ Sh mult_sh(Wire &W, Sh x, Sh y, u64 alpha)
+{
+    Sh z;
+    z.o = prod3(x, y) + alpha;
+    z.n = W.reshare1(z.o);
+    return z;
+}
+
+// Equality test [v == 0] -> Boolean bit sharing.  A receives the Boolean
+// zero-sharing word of stream 1 (bits 0..62 used here, bit 63 free for a following AND).
+__device__ __forceinline__ Sh eq_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D, u64 &A)
+{
+    Sh m = v + D.rA;
+    const u64 c = m.o + m.n + W.open1(m.o);
+    Sh t = D.rho;
+    if (p == 0) t.o ^= ~c;
+    if (p == 2) t.n ^= ~c;
+    A = zero_b(K, op, 1, e);
+    u32 off = 0;
+#pragma unroll
+    for (int k = 0; k < 6; k++) {
+        const u32 w = 32u >> k;
+        const u64 mask = (w == 32) ? 0xffffffffull : ((1ull << w) - 1);
+        Sh a, b;
+        a.o = t.o & mask; a.n = t.n & mask;
+        b.o = (t.o >> w) & mask; b.n = (t.n >> w) & mask;
+        t.o = (and3(a, b) ^ (A >> off)) & mask;
+        t.n = W.reshare1(t.o);
+        off += w;
+    }
+    return t;
+}
+
+// one-bit AND with reshare; alpha is the mask bit
+__device__ __forceinline__ Sh and_bit(Wire &W, Sh x, Sh y, u64 alpha)
+{
+    Sh z;
+    z.o = (and3(x, y) ^ alpha) & 1;
+    z.n = W.reshare1(z.o);
+    return z;
+}
+
+// Comparison [v >= 0] (v signed, |v| < 2^63) -> Boolean bit sharing.
+__device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D)
+{
+    const u64 LOW63 = 0x7fffffffffffffffull, TOP = 0x8000000000000000ull;
+    Sh m = v + D.rA;
+    const u64 c = m.o + m.n + W.open1(m.o);
+    const u64 nc = ~c;
+    Sh G, E;
+    G.o = nc & D.rho.o & LOW63; G.n = nc & D.rho.n & LOW63;
+    E.o = D.rho.o & LOW63;      E.n = D.rho.n & LOW63;
+    if (p == 0) E.o = ((D.rho.o ^ nc) & LOW63) | TOP;
+    if (p == 2) E.n = ((D.rho.n ^ nc) & LOW63) | TOP;
+    const u64 AG = zero_b(K, op, 1, e), AE = zero_b(K, op, 2, e);
+#pragma unroll
+    for (int k = 0; k < 6; k++) {
+        const int s = 1 << k;
+        // positions that start a block of 2s bits
+        const u64 sm = k == 0 ? 0x5555555555555555ull : k == 1 ? 0x1111111111111111ull
+                     : k == 2 ? 0x0101010101010101ull : k == 3 ? 0x0001000100010001ull
+                     : k == 4 ? 0x0000000100000001ull : 0x1ull;
+        Sh Eh, Gh;
+        Eh.o = E.o >> s; Eh.n = E.n >> s; Gh.o = G.o >> s; Gh.n = G.n >> s;
+        const u64 zg = (and3(Eh, G) ^ (AG >> (s - 1))) & sm;
+        if (k < 5) {
+            const u64 ze = (and3(Eh, E) ^ (AE >> (s - 1))) & sm;
+            u64 snd[2] = { zg, ze }, rcv[2];
+            W.reshare<2>(snd, rcv);
+            G.o = (Gh.o & sm) ^ zg; G.n = (Gh.n & sm) ^ rcv[0];
+            E.o = ze; E.n = rcv[1];
+        } else {
+            const u64 r = W.reshare1(zg);
+            G.o = (Gh.o & sm) ^ zg; G.n = (Gh.n & sm) ^ r;
+        }
+    }
+    Sh ge;
+    ge.o = ((D.rho.o >> 63) ^ G.o) & 1;
+    ge.n = ((D.rho.n >> 63) ^ G.n) & 1;
+    if (p == 0) ge.o ^= (c >> 63) ^ 1;
+    if (p == 2) ge.n ^= (c >> 63) ^ 1;
+    return ge;
+}
+
+// bit -> arithmetic: open f = s xor beta; s = beta if f = 0 else 1 - beta
+__device__ __forceinline__ Sh b2a(Wire &W, int p, Sh s, const Dealer &D)
+{
+    const u64 fo = (s.o ^ D.bBo) & 1, fn = (s.n ^ D.bBn) & 1;
+    const u64 f = (fo ^ fn ^ W.open1(fo)) & 1;
+    Sh one = pub(p, 1), out;
+    out.o = f ? one.o - D.bA.o : D.bA.o;
+    out.n = f ? one.n - D.bA.n : D.bA.n;
+    return out;
+}
+
+__device__ __forceinline__ Sh not_bit(int p, Sh b) { if (p == 0) b.o ^= 1; if (p == 2) b.n ^= 1; return b; }

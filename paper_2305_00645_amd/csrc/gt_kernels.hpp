@@ -1,0 +1,675 @@
+// Kernels of the GTree hot path for gfx950.  See gt_device.hpp for the execution
+// model (workgroup = 3 wavefronts = 3 parties; messages through the wire buffer).
+#pragma once
+#include "gt_device.hpp"
+
+#define GT_BLOCK dim3(GT_LANES, 3, 1)
+
+// grid-stride loop over tiles of 64 elements; every lane of the workgroup runs the
+// same number of iterations, so the barriers inside the protocols stay uniform
+#define GT_FOR_TILES(n)                                                                    \
+    for (u64 tile_ = blockIdx.x, ntiles_ = ((u64)(n) + GT_LANES - 1) / GT_LANES; tile_ < ntiles_; tile_ += gridDim.x)
+#define GT_ELEM() (tile_ * GT_LANES + threadIdx.x)
+
+struct KCommon { const u32 *keys; u64 *wire; u32 op; };
+
+__device__ __forceinline__ P6 p6_off(P6 a, size_t off)
+{
+    for (int j = 0; j < 3; j++) { a.o[j] += off; a.n[j] += off; }
+    return a;
+}
+
+// ---------------------------------------------------------------------------------
+// Share^A (Sec. II-B): x1, x2 from the owner's key (streams 0 and 1), x3 = x - x1 - x2.
+// One lane produces 8 consecutive elements (one PRF block per stream).
+__global__ __launch_bounds__(256) void k_share(const u32 *keys, u32 op, const u64 *plain, u64 n, P6 out)
+{
+    const Key ko = load_key(keys, GT_KEY_OWNER);
+    const u64 ngrp = (n + 7) / 8;
+    for (u64 g = (u64)blockIdx.x * blockDim.x + threadIdx.x; g < ngrp; g += (u64)gridDim.x * blockDim.x) {
+        u64 a[8], b[8];
+        chacha8(ko, g, op, 0, a);
+        chacha8(ko, g, op, 1, b);
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const u64 e = g * 8 + s;
+            if (e < n) {
+                const u64 x3 = plain[e] - a[s] - b[s];
+                out.o[0][e] = a[s]; out.n[0][e] = b[s];
+                out.o[1][e] = b[s]; out.n[1][e] = x3;
+                out.o[2][e] = x3;   out.n[2][e] = a[s];
+            }
+        }
+    }
+}
+
+// Rec^A: party 0 adds its two components and the one it receives from party 2.
+__global__ __launch_bounds__(256) void k_reconstruct(P6 in, u64 n, u64 *plain)
+{
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x)
+        plain[e] = in.o[0][e] + in.n[0][e] + in.o[2][e];
+}
+
+// local copy / strided gather of shares: dst[doff + e] = src[soff + e*sstride]
+__global__ __launch_bounds__(256) void k_copy(P6 dst, u64 doff, P6 src, u64 soff, u64 sstride, u64 n)
+{
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x)
+        for (int j = 0; j < 3; j++) {
+            dst.o[j][doff + e] = src.o[j][soff + e * sstride];
+            dst.n[j][doff + e] = src.n[j][soff + e * sstride];
+        }
+}
+
+// dst[r][i] (row stride N8) = src[i][r] (row stride w): sample-contiguous layout
+__global__ __launch_bounds__(256) void k_transpose(P6 dst, P6 src, u64 N, u64 N8, u32 w)
+{
+    const u64 total = N * w;
+    for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (u64)gridDim.x * blockDim.x) {
+        const u64 k = t / N, i = t % N;
+        for (int j = 0; j < 3; j++) {
+            dst.o[j][k * N8 + i] = src.o[j][i * w + k];
+            dst.n[j][k * N8 + i] = src.n[j][i * w + k];
+        }
+    }
+}
+
+// every element := public constant c
+__global__ __launch_bounds__(256) void k_fill_const(P6 dst, u64 off, u64 n, u64 c)
+{
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x)
+        for (int j = 0; j < 3; j++) {
+            dst.o[j][off + e] = j == 0 ? c : 0;
+            dst.n[j][off + e] = j == 2 ? c : 0;
+        }
+}
+
+// dst += src (local)
+__global__ __launch_bounds__(256) void k_add_inplace(P6 dst, P6 src, u64 n)
+{
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x)
+        for (int j = 0; j < 3; j++) { dst.o[j][e] += src.o[j][e]; dst.n[j][e] += src.n[j][e]; }
+}
+
+// rows of width d: dst[2r] = dst[2r+1] = src[r] (children inherit gamma, Sec. V-B)
+__global__ __launch_bounds__(256) void k_dup_rows(P6 dst, P6 src, u64 nh, u64 d)
+{
+    const u64 n = nh * d;
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x) {
+        const u64 r = e / d, k = e % d;
+        for (int j = 0; j < 3; j++) {
+            dst.o[j][(2 * r) * d + k] = dst.o[j][(2 * r + 1) * d + k] = src.o[j][e];
+            dst.n[j][(2 * r) * d + k] = dst.n[j][(2 * r + 1) * d + k] = src.n[j][e];
+        }
+    }
+}
+
+// idx[r*P2 + k] := k (public), val padding := 0
+__global__ __launch_bounds__(256) void k_iota(P6 idx, P6 val, u32 nh, u32 P2, u32 d)
+{
+    const u64 n = (u64)nh * P2;
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x) {
+        const u64 k = e % P2;
+        for (int j = 0; j < 3; j++) {
+            idx.o[j][e] = j == 0 ? k : 0;
+            idx.n[j][e] = j == 2 ? k : 0;
+            if (k >= d) { val.o[j][e] = 0; val.n[j][e] = 0; }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Elementwise product (Sec. II-B), 8 consecutive elements per lane.
+// MODE 0: z[e] = x[e]*y[e].
+// MODE 1 (one-time products of the learning protocol): e = (k*K+c)*N8 + i,
+//         z[e] = XT[k*N8+i] * YT[c*N8+i], defined for i < N.
+// MODE 2 (node split): e = r*CW + col, z = C[e] * (1 - split[r]), written to both
+//         children (2r, 2r+1) of the next level.
+struct MultArgs { KCommon c; P6 x, y, z; u64 n, N, N8; u32 K, CW; };
+
+template <int MODE>
+__global__ __launch_bounds__(192) void k_mult(MultArgs a)
+{
+    const int p = threadIdx.y, lane = threadIdx.x;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    const u64 ngrp = (a.n + 7) / 8;
+    for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
+        const u64 g = tile * GT_LANES + lane, e0 = g * 8;
+        u64 ao[8], an[8], snd[8], rcv[8];
+        chacha8(K.own, g, a.c.op, 0, ao);
+        chacha8(K.nxt, g, a.c.op, 0, an);
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const u64 e = e0 + s;
+            Sh x = { 0, 0 }, y = { 0, 0 };
+            if (e < a.n) {
+                if (MODE == 0) { x = ld(a.x, p, e); y = ld(a.y, p, e); }
+                if (MODE == 1) {
+                    const u64 col = e / a.N8, i = e % a.N8;
+                    if (i < a.N) { x = ld(a.x, p, (col / a.K) * a.N8 + i); y = ld(a.y, p, (col % a.K) * a.N8 + i); }
+                }
+                if (MODE == 2) { x = ld(a.x, p, e); y = pub(p, 1) - ld(a.y, p, e / a.CW); }
+            }
+            snd[s] = prod3(x, y) + (ao[s] - an[s]);
+        }
+        W.reshare<8>(snd, rcv);
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const u64 e = e0 + s;
+            if (e < a.n) {
+                Sh z = { snd[s], rcv[s] };
+                if (MODE == 0) st(a.z, p, e, z);
+                if (MODE == 1) { if (e % a.N8 < a.N) st(a.z, p, e, z); }
+                if (MODE == 2) {
+                    const u64 r = e / a.CW, col = e % a.CW;
+                    st(a.z, p, (2 * r) * a.CW + col, z);
+                    st(a.z, p, (2 * r + 1) * a.CW + col, z);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Equality grid (first lines of the array-access protocol, Sec. V-A; per-sample leaf
+// flags of the learning protocol, Sec. V-B).  Rows are samples i < N, columns k < w;
+// element (k, i) has index k*N8 + i.  A lane owns 8 consecutive samples and walks
+// over the columns, so that one PRF block yields the mask words of its 8 elements
+// and the inner products of the array access accumulate in registers.
+//   E[k][i] = [u[i] - base == k]  (and g[k] if HAS_G)  -> arithmetic sharing, then
+//   GM_STORE : out[k*N8+i] = E
+//   GM_COMMON: z[i] = sum_k E[k][i] * W1[w1off+k]   (NDOT = 2: also W2 -> out2)
+//   GM_ROWS  : z[i] = sum_k E[k][i] * XT[k*N8+i]
+//   epilogue 0: out[i] = z;  1: out[i] = 2*prev[i] + z + 1  (index update of the
+//   partition and inference protocols).
+enum { GM_STORE = 0, GM_COMMON = 1, GM_ROWS = 2 };
+struct GridArgs {
+    KCommon c;
+    P6 u; u64 base; u32 w; u64 N, N8;
+    P6 g, out, out2, W1, W2, XT, prev;
+    u64 w1off, w2off;
+    int epi;
+};
+
+template <int W2B>
+__device__ __forceinline__ void pack8(const u64 (&z)[8], u64 (&snd)[(W2B * 8 + 63) / 64])
+{
+    constexpr int NW = (W2B * 8 + 63) / 64;
+#pragma unroll
+    for (int j = 0; j < NW; j++) snd[j] = 0;
+#pragma unroll
+    for (int s = 0; s < 8; s++) snd[(s * W2B) >> 6] |= z[s] << ((s * W2B) & 63);
+}
+template <int W2B>
+__device__ __forceinline__ void unpack8(const u64 (&rcv)[(W2B * 8 + 63) / 64], u64 (&z)[8])
+{
+    constexpr u64 mask = W2B == 64 ? ~0ull : ((1ull << (W2B & 63)) - 1);
+#pragma unroll
+    for (int s = 0; s < 8; s++) z[s] = (rcv[(s * W2B) >> 6] >> ((s * W2B) & 63)) & mask;
+}
+
+template <int W2B>
+__device__ __forceinline__ void eq_round8(Wire &W, Sh (&t)[8], const u64 (&A)[8], u32 off)
+{
+    constexpr int NW = (W2B * 8 + 63) / 64;
+    constexpr u64 mask = (1ull << W2B) - 1;
+    u64 z[8], r[8], snd[NW], rcv[NW];
+#pragma unroll
+    for (int s = 0; s < 8; s++) {
+        Sh a, b;
+        a.o = t[s].o & mask; a.n = t[s].n & mask;
+        b.o = (t[s].o >> W2B) & mask; b.n = (t[s].n >> W2B) & mask;
+        z[s] = (and3(a, b) ^ (A[s] >> off)) & mask;
+    }
+    pack8<W2B>(z, snd);
+    W.reshare<NW>(snd, rcv);
+    unpack8<W2B>(rcv, r);
+#pragma unroll
+    for (int s = 0; s < 8; s++) { t[s].o = z[s]; t[s].n = r[s]; }
+}
+
+template <int MODE, bool HAS_G, int NDOT>
+__global__ __launch_bounds__(192) void k_eqgrid(GridArgs a)
+{
+    const int p = threadIdx.y, lane = threadIdx.x;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    const u32 op = a.c.op;
+    const u64 ngrp = a.N8 / 8;
+    const Sh one = pub(p, 1);
+    for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
+        const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
+        const bool act = grp < ngrp;
+        Sh v[8];
+        u64 acc[8], acc2[8];
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            v[s].o = 0; v[s].n = 0; acc[s] = 0; acc2[s] = 0;
+            if (act && i0 + s < a.N) v[s] = ld(a.u, p, i0 + s) - pub(p, a.base);
+        }
+        for (u32 k = 0; k < a.w; k++) {
+            const u64 e0 = (u64)k * a.N8 + i0;
+            u64 A[8];
+            {
+                u64 An[8];
+                chacha8(K.own, e0 >> 3, op, 1, A);
+                chacha8(K.nxt, e0 >> 3, op, 1, An);
+#pragma unroll
+                for (int s = 0; s < 8; s++) A[s] ^= An[s];
+            }
+            Sh t[8], bA[8];
+            u32 bBo = 0, bBn = 0;
+            u64 snd[8], rcv[8], mn[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const Dealer D = dealer_of(K, p, op, e0 + s);
+                const Sh m = v[s] - pub(p, k) + D.rA;
+                snd[s] = m.o; mn[s] = m.n;
+                t[s] = D.rho; bA[s] = D.bA;
+                bBo |= D.bBo << s; bBn |= D.bBn << s;
+            }
+            W.open<8>(snd, rcv);                       // masked values, 64 bits each
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const u64 c = snd[s] + mn[s] + rcv[s];
+                if (p == 0) t[s].o ^= ~c;
+                if (p == 2) t[s].n ^= ~c;
+            }
+            eq_round8<32>(W, t, A, 0);                 // six AND rounds, 63 bits
+            eq_round8<16>(W, t, A, 32);
+            eq_round8<8>(W, t, A, 48);
+            eq_round8<4>(W, t, A, 56);
+            eq_round8<2>(W, t, A, 60);
+            eq_round8<1>(W, t, A, 62);
+            if (HAS_G) {                               // and with the column's shared bit
+                const Sh gk = ld(a.g, p, k);
+                u64 z[8], r[8], s1[1], r1[1];
+#pragma unroll
+                for (int s = 0; s < 8; s++) z[s] = (and3(t[s], gk) ^ (A[s] >> 63)) & 1;
+                pack8<1>(z, s1);
+                W.reshare<1>(s1, r1);
+                unpack8<1>(r1, r);
+#pragma unroll
+                for (int s = 0; s < 8; s++) { t[s].o = z[s]; t[s].n = r[s]; }
+            }
+            u32 f;
+            {                                          // bit -> arithmetic: open s xor beta
+                u32 fo = 0, fn = 0;
+#pragma unroll
+                for (int s = 0; s < 8; s++) { fo |= ((u32)t[s].o & 1) << s; fn |= ((u32)t[s].n & 1) << s; }
+                fo ^= bBo; fn ^= bBn;
+                f = fo ^ fn ^ (u32)W.open1((u64)fo);
+            }
+            Sh Wk = { 0, 0 }, Wk2 = { 0, 0 };
+            if (MODE == GM_COMMON) {
+                Wk = ld(a.W1, p, a.w1off + k);
+                if (NDOT == 2) Wk2 = ld(a.W2, p, a.w2off + k);
+            }
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                Sh E;
+                E.o = ((f >> s) & 1) ? one.o - bA[s].o : bA[s].o;
+                E.n = ((f >> s) & 1) ? one.n - bA[s].n : bA[s].n;
+                const bool live = act && i0 + s < a.N;
+                if (MODE == GM_STORE) { if (live) st(a.out, p, e0 + s, E); }
+                if (MODE == GM_COMMON) { acc[s] += prod3(E, Wk); if (NDOT == 2) acc2[s] += prod3(E, Wk2); }
+                if (MODE == GM_ROWS) { if (live) acc[s] += prod3(E, ld(a.XT, p, e0 + s)); }
+            }
+        }
+        if (MODE != GM_STORE) {
+            u64 ao[8], an[8], snd[8], rcv[8];
+            chacha8(K.own, grp, op, 2, ao);
+            chacha8(K.nxt, grp, op, 2, an);
+#pragma unroll
+            for (int s = 0; s < 8; s++) snd[s] = acc[s] + (ao[s] - an[s]);
+            W.reshare<8>(snd, rcv);
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                if (act && i0 + s < a.N) {
+                    Sh z = { snd[s], rcv[s] };
+                    if (a.epi == 1) z = scale(ld(a.prev, p, i0 + s), 2) + z + one;
+                    st(a.out, p, i0 + s, z);
+                }
+            }
+            if (NDOT == 2) {
+                chacha8(K.own, grp, op, 3, ao);
+                chacha8(K.nxt, grp, op, 3, an);
+#pragma unroll
+                for (int s = 0; s < 8; s++) snd[s] = acc2[s] + (ao[s] - an[s]);
+                W.reshare<8>(snd, rcv);
+#pragma unroll
+                for (int s = 0; s < 8; s++)
+                    if (act && i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.out2, p, i0 + s, z); }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Small per-element protocols, one element per lane.
+
+// z = B2A([x - y_pub == 0]) or the Boolean bit (BOOL_OUT)
+struct EqArgs { KCommon c; P6 x; const u64 *ypub; u64 ysub; P6 z; u64 n, xoff; };
+template <bool BOOL_OUT>
+__global__ __launch_bounds__(192) void k_eq(EqArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh v = { 0, 0 };
+        if (act) v = ld(a.x, p, a.xoff + e) - pub(p, a.ysub + (a.ypub ? a.ypub[e] : 0));
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        u64 A;
+        Sh b = eq_bit(W, K, p, a.c.op, e, v, D, A);
+        if (!BOOL_OUT) b = b2a(W, p, b, D);
+        if (act) st(a.z, p, e, b);
+    }
+}
+
+// z = B2A([x >= y])
+struct GeArgs { KCommon c; P6 x, y, z; u64 n; };
+__global__ __launch_bounds__(192) void k_ge(GeArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh v = { 0, 0 };
+        if (act) v = ld(a.x, p, e) - ld(a.y, p, e);
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        Sh b = b2a(W, p, ge_bit(W, K, p, a.c.op, e, v, D), D);
+        if (act) st(a.z, p, e, b);
+    }
+}
+
+// Inference, threshold mode: bit = [x > theta]; Tidx <- 2 Tidx + bit + 1.
+struct CmpArgs { KCommon c; P6 th, x, tidx; u64 n; };
+__global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh v = { 0, 0 };
+        if (act) v = ld(a.th, p, e) - ld(a.x, p, e);
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, v, D)), D);
+        if (act) st(a.tidx, p, e, scale(ld(a.tidx, p, e), 2) + b + pub(p, 1));
+    }
+}
+
+// One step of restoring division: b = [r >= Q]; r <- r - b Q; quo <- 2 quo + b.
+// first: r starts as S and quo as 0; otherwise r is doubled first.
+struct DivArgs { KCommon c; P6 S, Q, r, quo; u64 n; int first; };
+__global__ __launch_bounds__(192) void k_div_step(DivArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh r = { 0, 0 }, Q = { 0, 0 }, quo = { 0, 0 };
+        if (act) {
+            Q = ld(a.Q, p, e);
+            if (a.first) r = ld(a.S, p, e);
+            else { r = scale(ld(a.r, p, e), 2); quo = ld(a.quo, p, e); }
+        }
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        const Sh b = b2a(W, p, ge_bit(W, K, p, a.c.op, e, r - Q, D), D);
+        const Sh bq = mult_sh(W, b, Q, zero_a(K, a.c.op, 3, e));
+        if (act) { st(a.r, p, e, r - bq); st(a.quo, p, e, scale(quo, 2) + b); }
+    }
+}
+
+// Gini numerator/denominator terms (Sec. V-B, Eq. (1)): element q = (r*d+k)*2 + j,
+// S = sum_c n_jc^2, Q = n_j * n with n_1c = C[r][k*K+c], n_0c = tot_c - n_1c.
+struct PrepArgs { KCommon c; P6 C, S, Q; u64 n; u32 d, K, CW; };
+__global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    const u64 dK = (u64)a.d * a.K;
+    GT_FOR_TILES(a.n) {
+        const u64 q = GT_ELEM();
+        const bool act = q < a.n;
+        Sh nj = { 0, 0 }, n = { 0, 0 };
+        u64 s = 0;
+        if (act) {
+            const u64 r = q / (2 * a.d), k = (q / 2) % a.d, br = q & 1;
+            for (u32 cl = 0; cl < a.K; cl++) {
+                const Sh n1 = ld(a.C, p, r * a.CW + k * a.K + cl), tot = ld(a.C, p, r * a.CW + dK + cl);
+                const Sh njc = br ? n1 : tot - n1;
+                nj = nj + njc; n = n + tot;
+                s += prod3(njc, njc);
+            }
+        }
+        u64 snd[2] = { s + zero_a(K, a.c.op, 0, q), prod3(nj, n) + zero_a(K, a.c.op, 1, q) }, rcv[2];
+        W.reshare<2>(snd, rcv);
+        if (act) { Sh S = { snd[0], rcv[0] }, Q = { snd[1], rcv[1] }; st(a.S, p, q, S); st(a.Q, p, q, Q); }
+    }
+}
+
+// score = quo[2e] + quo[2e+1]; masked = score * gamma[e]; written to the export copy
+// and into the tournament array val[r*P2 + k].
+struct MaskArgs { KCommon c; P6 quo, gamma, score, val; u64 n; u32 d, P2; };
+__global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh s = { 0, 0 }, g = { 0, 0 };
+        if (act) { s = ld(a.quo, p, 2 * e) + ld(a.quo, p, 2 * e + 1); g = ld(a.gamma, p, e); }
+        const Sh z = mult_sh(W, s, g, zero_a(K, a.c.op, 0, e));
+        if (act) { st(a.score, p, e, z); st(a.val, p, (e / a.d) * a.P2 + e % a.d, z); }
+    }
+}
+
+// Compare-and-select: b = [right > left]; val = left + b (right-left); idx likewise.
+// mode 0 (tournament level over arrays of length len per node): e = r*half + m,
+//        left = in[r*len+2m], right = in[r*len+2m+1], out[e].
+// mode 1 (label chain): left = val_in[e] / idx_in[e], right = C[e*CW + coff], index
+//        constant cidx; in place.
+struct SelArgs { KCommon c; P6 vin, iin, vout, iout, C; u64 n; u32 len, CW; u64 coff, cidx; int mode; };
+__global__ __launch_bounds__(192) void k_select_max(SelArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh L = { 0, 0 }, R = { 0, 0 }, IL = { 0, 0 }, IR = { 0, 0 };
+        if (act) {
+            if (a.mode == 0) {
+                const u64 half = a.len / 2, r = e / half, m = e % half, l = r * a.len + 2 * m;
+                L = ld(a.vin, p, l); R = ld(a.vin, p, l + 1); IL = ld(a.iin, p, l); IR = ld(a.iin, p, l + 1);
+            } else {
+                L = ld(a.vin, p, e); IL = ld(a.iin, p, e);
+                R = ld(a.C, p, e * a.CW + a.coff); IR = pub(p, a.cidx);
+            }
+        }
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        const Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, L - R, D)), D);
+        u64 snd[2] = { prod3(b, R - L) + zero_a(K, a.c.op, 3, e), prod3(b, IR - IL) + zero_a(K, a.c.op, 4, e) }, rcv[2];
+        W.reshare<2>(snd, rcv);
+        if (act) {
+            Sh dv = { snd[0], rcv[0] }, di = { snd[1], rcv[1] };
+            st(a.vout, p, e, L + dv); st(a.iout, p, e, IL + di);
+        }
+    }
+}
+
+// gamma[r][k] <- gamma[r][k] * (1 - [SD[r] == k])
+struct GammaArgs { KCommon c; P6 SD, gamma; u64 n; u32 d; };
+__global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 e = GT_ELEM();
+        const bool act = e < a.n;
+        Sh v = { 0, 0 }, g = { 0, 0 };
+        if (act) { v = ld(a.SD, p, e / a.d) - pub(p, e % a.d); g = ld(a.gamma, p, e); }
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        u64 A;
+        const Sh oh = b2a(W, p, eq_bit(W, K, p, a.c.op, e, v, D, A), D);
+        const Sh z = mult_sh(W, g, pub(p, 1) - oh, zero_a(K, a.c.op, 2, e));
+        if (act) st(a.gamma, p, e, z);
+    }
+}
+
+// Node r: pure = [n^2 - sum_c tot_c^2 == 0]; split = isLeaf and not pure;
+// F[base+r] <- F (1 - split); children F <- 2 - split.
+struct SplitArgs { KCommon c; P6 C, isLeaf, F, split; u64 n, base; u32 K, CW; u64 dK; };
+__global__ __launch_bounds__(192) void k_split(SplitArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 r = GT_ELEM();
+        const bool act = r < a.n;
+        Sh n = { 0, 0 }, leaf = { 0, 0 }, f = { 0, 0 };
+        u64 dv = 0;
+        if (act) {
+            for (u32 cl = 0; cl < a.K; cl++) {
+                const Sh tc = ld(a.C, p, r * a.CW + a.dK + cl);
+                n = n + tc;
+                dv -= prod3(tc, tc);
+            }
+            dv += prod3(n, n);
+            leaf = ld(a.isLeaf, p, r);
+            f = ld(a.F, p, a.base + r);
+        }
+        Sh d;
+        d.o = dv + zero_a(K, a.c.op, 2, r);
+        d.n = W.reshare1(d.o);
+        const Dealer D = dealer_of(K, p, a.c.op, r);
+        u64 A;
+        const Sh npure = not_bit(p, eq_bit(W, K, p, a.c.op, r, d, D, A));
+        const Sh sA = b2a(W, p, and_bit(W, leaf, npure, A >> 63), D);
+        const Sh keep = pub(p, 1) - sA;
+        const Sh fz = mult_sh(W, f, keep, zero_a(K, a.c.op, 3, r));
+        if (act) {
+            st(a.split, p, r, sA);
+            st(a.F, p, a.base + r, fz);
+            const Sh ch = keep + pub(p, 1);
+            st(a.F, p, 2 * (a.base + r) + 1, ch);
+            st(a.F, p, 2 * (a.base + r) + 2, ch);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Statistics counting as a contraction in Z_2^64 (Sec. V-B):
+//   Z_p[r][col] = sum_i (L_p + L_{p+1})[r][i] * B_p[col][i] + L_p[r][i] * B_{p+1}[col][i]
+// with L the per-sample leaf one-hot (n_h x N8) and B the sample-contiguous columns
+// (XY products, then the K class indicators).  64 x 64 output tile per workgroup,
+// 4 x 4 per lane, 16-sample slices staged through LDS; the sample range is split
+// over workgroups and partial sums meet by 64-bit atomic adds, which are exact and
+// order-independent in the ring.
+#define CT_T 64
+#define CT_K 16
+struct CountArgs { P6 LT, BT; u64 N8; u32 nh, ncol; u64 colbase; u64 *Zacc; u64 kchunk; u32 nchunk; };
+
+__global__ __launch_bounds__(256) void k_count(CountArgs a)
+{
+    __shared__ u64 As[CT_K][CT_T + 1], Ao[CT_K][CT_T + 1], Bo[CT_K][CT_T + 1], Bn[CT_K][CT_T + 1];
+    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    const int p = blockIdx.z / a.nchunk;
+    const u64 chunk = blockIdx.z % a.nchunk;
+    const u64 r0 = (u64)blockIdx.y * CT_T, c0 = (u64)blockIdx.x * CT_T;
+    const u64 kbeg = chunk * a.kchunk, kend = kbeg + a.kchunk < a.N8 ? kbeg + a.kchunk : a.N8;
+    const u64 *Lo = own_of(a.LT, p), *Ln = nxt_of(a.LT, p), *Xo = own_of(a.BT, p), *Xn = nxt_of(a.BT, p);
+    u64 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = 0;
+    const int lrow = tid / 4, lk = (tid % 4) * 4;      // loader: 64 rows x 16 samples, 4 samples per lane
+    for (u64 k0 = kbeg; k0 < kend; k0 += CT_K) {
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const u64 i = k0 + lk + q;
+            u64 lo = 0, ln = 0, xo = 0, xn = 0;
+            if (i < kend) {
+                if (r0 + lrow < a.nh) { lo = Lo[(r0 + lrow) * a.N8 + i]; ln = Ln[(r0 + lrow) * a.N8 + i]; }
+                if (c0 + lrow < a.ncol) { xo = Xo[(a.colbase + c0 + lrow) * a.N8 + i]; xn = Xn[(a.colbase + c0 + lrow) * a.N8 + i]; }
+            }
+            As[lk + q][lrow] = lo + ln; Ao[lk + q][lrow] = lo;
+            Bo[lk + q][lrow] = xo; Bn[lk + q][lrow] = xn;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < CT_K; kk++) {
+            u64 as[4], ao[4], bo[4], bn[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) { as[i] = As[kk][ty * 4 + i]; ao[i] = Ao[kk][ty * 4 + i]; bo[i] = Bo[kk][tx * 4 + i]; bn[i] = Bn[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) acc[i][j] += as[i] * bo[j] + ao[i] * bn[j];
+        }
+        __syncthreads();
+    }
+    u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const u64 r = r0 + ty * 4 + i, c = c0 + tx * 4 + j;
+            if (r < a.nh && c < a.ncol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)acc[i][j]);
+        }
+}
+
+// add the zero sharing, reshare, accumulate into the node statistics
+struct CountFinArgs { KCommon c; u64 *Zacc; P6 C; u64 n; u32 ncol, CW; u64 colbase; };
+__global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
+{
+    const int p = threadIdx.y;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    GT_FOR_TILES(a.n) {
+        const u64 o = GT_ELEM();
+        const bool act = o < a.n;
+        Sh z;
+        z.o = (act ? a.Zacc[(u64)p * a.n + o] : 0) + zero_a(K, a.c.op, 0, o);
+        z.n = W.reshare1(z.o);
+        if (act) {
+            const u64 idx = (o / a.ncol) * a.CW + a.colbase + o % a.ncol;
+            st(a.C, p, idx, ld(a.C, p, idx) + z);
+        }
+    }
+}
+
+// counter-array layout of Sec. V-B for export: per node (1+K) x 2d, local linear ops
+__global__ __launch_bounds__(256) void k_c_paper(P6 C, P6 out, u32 nh, u32 d, u32 K, u32 CW)
+{
+    const u64 per = (u64)(1 + K) * 2 * d, n = (u64)nh * per;
+    for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (u64)gridDim.x * blockDim.x) {
+        const u64 r = t / per, q = t % per, row = q / (2 * d), col = q % (2 * d), k = col / 2, v = col & 1;
+        for (int j = 0; j < 3; j++)
+            for (int pl = 0; pl < 2; pl++) {
+                const u64 *src = pl ? C.n[j] : C.o[j];
+                u64 val = 0;
+                for (u32 cl = (row ? row - 1 : 0); cl < (row ? row : K); cl++) {
+                    const u64 n1 = src[r * CW + k * K + cl], tot = src[r * CW + (u64)d * K + cl];
+                    val += v ? n1 : tot - n1;
+                }
+                (pl ? out.n[j] : out.o[j])[t] = val;
+            }
+    }
+}

@@ -1,0 +1,689 @@
+// Host side of the C ABI declared in include/gtree.h: argument checks, device
+// state, the operation schedule of each protocol, message accounting, launches.
+#include "gtree.h"
+#include "gt_kernels.hpp"
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#define GT_MAX_BLOCKS 4096u
+
+#define HIPCHK(x)                                                                             \
+    do { hipError_t e_ = (x); if (e_ != hipSuccess) {                                         \
+        fprintf(stderr, "gtree: %s failed: %s (%s:%d)\n", #x, hipGetErrorString(e_), __FILE__, __LINE__); \
+        return GT_EHIP; } } while (0)
+#define GTCHK(x) do { int r_ = (x); if (r_ != GT_OK) return r_; } while (0)
+
+// ---------------------------------------------------------------------------------
+struct DSh {                 // a shared vector in device memory: six planes in one allocation
+    u64 *base = nullptr;
+    size_t n = 0;
+    P6 v{};
+};
+
+struct gt_ctx {
+    u32 tau, K;
+    u32 op;
+    hipStream_t stream;
+    u32 *keys_d;
+    u64 *wire;
+    gt_stats acc;
+    hipEvent_t ev0, ev1;
+    bool timing;
+};
+
+struct gt_tree {
+    u32 H;
+    bool has_thr;
+    DSh feat, thr, leaf;
+};
+
+struct gt_train {
+    size_t N, N8;
+    u32 d, K, H, CW, level, last, P2;
+    bool finished;
+    DSh XT, BT;                      // [k][i]; [(k*K+c) | d*K+c][i]
+    DSh M, T, F, C, Cn, gamma, Gn, isLeaf, LT, SD, split;
+    DSh S, Q, quo, rem, val[2], idx[2], tval, best, lab;
+    DSh Clast, Glast, Slast;
+    u64 *Zacc;
+};
+
+static size_t pad8(size_t n) { return (n + 7) & ~(size_t)7; }
+
+static int dsh_alloc(DSh &s, size_t n, hipStream_t st)
+{
+    s.n = n;
+    size_t words = 6 * (n ? n : 1);
+    if (hipMalloc(&s.base, words * 8) != hipSuccess) { s.base = nullptr; return GT_ENOMEM; }
+    HIPCHK(hipMemsetAsync(s.base, 0, words * 8, st));
+    for (int p = 0; p < 3; p++) { s.v.o[p] = s.base + (size_t)(2 * p) * n; s.v.n[p] = s.base + (size_t)(2 * p + 1) * n; }
+    return GT_OK;
+}
+static void dsh_free(DSh &s) { if (s.base) (void)hipFree(s.base); s.base = nullptr; s.n = 0; }
+
+static P6 off6(P6 a, size_t off) { for (int j = 0; j < 3; j++) { a.o[j] += off; a.n[j] += off; } return a; }
+
+static bool shares_ok(const gt_shares *s, size_t n)
+{
+    if (!s) return false;
+    if (n == 0) return true;
+    if (s->n < n) return false;
+    for (int p = 0; p < 3; p++) if (!s->party[p].own || !s->party[p].next) return false;
+    return true;
+}
+static P6 to_p6(const gt_shares *s)
+{
+    P6 a;
+    for (int p = 0; p < 3; p++) { a.o[p] = s->party[p].own; a.n[p] = s->party[p].next; }
+    return a;
+}
+
+static unsigned blocks_for(u64 n, unsigned per)
+{
+    u64 b = (n + per - 1) / per;
+    if (b < 1) b = 1;
+    return (unsigned)std::min<u64>(b, GT_MAX_BLOCKS);
+}
+static unsigned tiles(u64 n) { return blocks_for(n, GT_LANES); }          // one element per lane
+static unsigned tiles8(u64 n) { return blocks_for((n + 7) / 8, GT_LANES); } // eight per lane
+
+// ---- message accounting: one message of n elements of `bits` bits is ceil(n*bits/8)
+// bytes; dir = +1 to the successor (opening), -1 to the predecessor (resharing).
+static void wire_add(gt_ctx *c, int dir, u64 n, u64 bits)
+{
+    u64 bytes = (n * bits + 7) / 8;
+    for (int p = 0; p < 3; p++) c->acc.wire_bytes[p][(p + dir + 3) % 3] += bytes;
+}
+static void acct_eq(gt_ctx *c, u64 n)
+{
+    wire_add(c, +1, n, 64);
+    for (int k = 0; k < 6; k++) wire_add(c, -1, n, 32u >> k);
+    c->acc.rounds += 7;
+}
+static void acct_ge(gt_ctx *c, u64 n)
+{
+    wire_add(c, +1, n, 64);
+    for (int k = 0; k < 5; k++) wire_add(c, -1, n, 2 * (32u >> k));
+    wire_add(c, -1, n, 1);
+    c->acc.rounds += 7;
+}
+static void acct_b2a(gt_ctx *c, u64 n) { wire_add(c, +1, n, 1); c->acc.rounds += 1; }
+static void acct_and1(gt_ctx *c, u64 n) { wire_add(c, -1, n, 1); c->acc.rounds += 1; }
+static void acct_reshare(gt_ctx *c, u64 n, u64 words) { wire_add(c, -1, n, 64 * words); c->acc.rounds += 1; }
+
+struct Timed {                // times one API call with events on the context's stream
+    gt_ctx *c; bool on;
+    explicit Timed(gt_ctx *ctx) : c(ctx), on(!ctx->timing)
+    {
+        if (on) { c->timing = true; (void)hipEventRecord(c->ev0, c->stream); }
+    }
+    int finish(int rc)
+    {
+        if (!on) return rc;
+        on = false; c->timing = false;
+        if (hipEventRecord(c->ev1, c->stream) != hipSuccess) return rc ? rc : GT_EHIP;
+        if (hipEventSynchronize(c->ev1) != hipSuccess) return rc ? rc : GT_EHIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->acc.kernel_ms += ms;
+        if (rc == GT_OK && hipGetLastError() != hipSuccess) return GT_EHIP;
+        return rc;
+    }
+    ~Timed() { if (on) { c->timing = false; } }
+};
+
+static KCommon kc(gt_ctx *c, u32 op) { KCommon k; k.keys = c->keys_d; k.wire = c->wire; k.op = op; return k; }
+#define LAUNCH_OK() do { if (hipGetLastError() != hipSuccess) return GT_EHIP; } while (0)
+
+// ---------------------------------------------------------------------------------
+extern "C" const char *gt_strerror(int code)
+{
+    switch (code) {
+    case GT_OK: return "ok";
+    case GT_EINVAL: return "invalid argument";
+    case GT_ENOMEM: return "device allocation failed";
+    case GT_ESTATE: return "call out of order";
+    case GT_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+    }
+}
+
+extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
+{
+    if (!out || !prm) return GT_EINVAL;
+    if (prm->K < 1 || prm->K > GT_MAX_K || prm->tau < 1 || prm->tau > GT_MAX_TAU) return GT_EINVAL;
+    gt_ctx *c = new (std::nothrow) gt_ctx();
+    if (!c) return GT_ENOMEM;
+    memset(c, 0, sizeof *c);
+    c->tau = prm->tau; c->K = prm->K; c->stream = (hipStream_t)prm->hip_stream;
+    u32 keys[5][8];
+    for (int k = 0; k < 5; k++)
+        for (int i = 0; i < 4; i++) { keys[k][2 * i] = (u32)prm->seed[k][i]; keys[k][2 * i + 1] = (u32)(prm->seed[k][i] >> 32); }
+    if (hipMalloc(&c->keys_d, sizeof keys) != hipSuccess) { delete c; return GT_ENOMEM; }
+    if (hipMalloc(&c->wire, (size_t)GT_MAX_BLOCKS * GT_WIRE_WORDS_PER_BLOCK * 8) != hipSuccess) { (void)hipFree(c->keys_d); delete c; return GT_ENOMEM; }
+    if (hipMemcpy(c->keys_d, keys, sizeof keys, hipMemcpyHostToDevice) != hipSuccess ||
+        hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) {
+        (void)hipFree(c->keys_d); (void)hipFree(c->wire); delete c; return GT_EHIP;
+    }
+    *out = c;
+    return GT_OK;
+}
+
+extern "C" int gt_ctx_destroy(gt_ctx *c)
+{
+    if (!c) return GT_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipEventDestroy(c->ev0); (void)hipEventDestroy(c->ev1);
+    (void)hipFree(c->keys_d); (void)hipFree(c->wire);
+    delete c;
+    return GT_OK;
+}
+
+extern "C" int gt_stats_get(gt_ctx *c, gt_stats *out)
+{
+    if (!c || !out) return GT_EINVAL;
+    HIPCHK(hipStreamSynchronize(c->stream));
+    *out = c->acc;
+    return GT_OK;
+}
+extern "C" int gt_stats_reset(gt_ctx *c) { if (!c) return GT_EINVAL; memset(&c->acc, 0, sizeof c->acc); return GT_OK; }
+extern "C" uint32_t gt_op_counter(const gt_ctx *c) { return c ? c->op : 0; }
+
+// ---------------------------------------------------------------------------------
+extern "C" int gt_share_a(gt_ctx *c, const uint64_t *plain, size_t n, const gt_shares *out)
+{
+    if (!c || !shares_ok(out, n) || (n && !plain)) return GT_EINVAL;
+    Timed T(c);
+    u32 op = c->op++;
+    if (n) { hipLaunchKernelGGL(k_share, dim3(blocks_for((n + 7) / 8, 256)), dim3(256), 0, c->stream, c->keys_d, op, plain, (u64)n, to_p6(out)); LAUNCH_OK(); }
+    return T.finish(GT_OK);
+}
+
+extern "C" int gt_reconstruct_a(gt_ctx *c, const gt_shares *in, uint64_t *plain, size_t n)
+{
+    if (!c || !shares_ok(in, n) || (n && !plain)) return GT_EINVAL;
+    Timed T(c);
+    if (n) { hipLaunchKernelGGL(k_reconstruct, dim3(blocks_for(n, 256)), dim3(256), 0, c->stream, to_p6(in), (u64)n, plain); LAUNCH_OK(); }
+    return T.finish(GT_OK);
+}
+
+static int copy6(gt_ctx *c, P6 dst, u64 doff, P6 src, u64 soff, u64 sstride, u64 n)
+{
+    if (!n) return GT_OK;
+    hipLaunchKernelGGL(k_copy, dim3(blocks_for(n, 256)), dim3(256), 0, c->stream, dst, doff, src, soff, sstride, n);
+    LAUNCH_OK();
+    return GT_OK;
+}
+
+// ---- building blocks ---------------------------------------------------------------
+static int do_mult(gt_ctx *c, int mode, MultArgs a)
+{
+    a.c = kc(c, c->op++);
+    if (a.n) {
+        dim3 g(tiles8(a.n));
+        if (mode == 0) hipLaunchKernelGGL(k_mult<0>, g, GT_BLOCK, 0, c->stream, a);
+        else if (mode == 1) hipLaunchKernelGGL(k_mult<1>, g, GT_BLOCK, 0, c->stream, a);
+        else hipLaunchKernelGGL(k_mult<2>, g, GT_BLOCK, 0, c->stream, a);
+        LAUNCH_OK();
+    }
+    return GT_OK;
+}
+
+extern "C" int gt_mult(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t n, const gt_shares *z)
+{
+    if (!c || !shares_ok(x, n) || !shares_ok(y, n) || !shares_ok(z, n)) return GT_EINVAL;
+    Timed T(c);
+    MultArgs a{}; a.x = to_p6(x); a.y = to_p6(y); a.z = to_p6(z); a.n = n;
+    int rc = do_mult(c, 0, a);
+    acct_reshare(c, n, 1);
+    return T.finish(rc);
+}
+
+static int do_eq(gt_ctx *c, bool bool_out, P6 x, u64 xoff, const u64 *ypub, u64 ysub, P6 z, u64 n)
+{
+    EqArgs a{}; a.c = kc(c, c->op++); a.x = x; a.xoff = xoff; a.ypub = ypub; a.ysub = ysub; a.z = z; a.n = n;
+    if (n) {
+        if (bool_out) hipLaunchKernelGGL(k_eq<true>, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a);
+        else hipLaunchKernelGGL(k_eq<false>, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a);
+        LAUNCH_OK();
+    }
+    acct_eq(c, n);
+    if (!bool_out) acct_b2a(c, n);
+    return GT_OK;
+}
+
+extern "C" int gt_eq_a(gt_ctx *c, const gt_shares *x, const uint64_t *ypub, size_t n, const gt_shares *z)
+{
+    if (!c || !shares_ok(x, n) || !shares_ok(z, n)) return GT_EINVAL;
+    Timed T(c);
+    return T.finish(do_eq(c, false, to_p6(x), 0, ypub, 0, to_p6(z), n));
+}
+
+extern "C" int gt_ge_a(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t n, const gt_shares *z)
+{
+    if (!c || !shares_ok(x, n) || !shares_ok(y, n) || !shares_ok(z, n)) return GT_EINVAL;
+    Timed T(c);
+    GeArgs a{}; a.c = kc(c, c->op++); a.x = to_p6(x); a.y = to_p6(y); a.z = to_p6(z); a.n = n;
+    if (n) { hipLaunchKernelGGL(k_ge, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a); LAUNCH_OK(); }
+    acct_ge(c, n); acct_b2a(c, n);
+    return T.finish(GT_OK);
+}
+
+// the equality grid with its accounting
+static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
+{
+    a.c = kc(c, c->op++);
+    const u64 nel = (u64)a.w * a.N;
+    if (a.N && a.w) {
+        dim3 g(tiles8(a.N8));
+        if (mode == GM_STORE && has_g) hipLaunchKernelGGL((k_eqgrid<GM_STORE, true, 1>), g, GT_BLOCK, 0, c->stream, a);
+        else if (mode == GM_STORE) hipLaunchKernelGGL((k_eqgrid<GM_STORE, false, 1>), g, GT_BLOCK, 0, c->stream, a);
+        else if (mode == GM_COMMON && ndot == 2) hipLaunchKernelGGL((k_eqgrid<GM_COMMON, false, 2>), g, GT_BLOCK, 0, c->stream, a);
+        else if (mode == GM_COMMON) hipLaunchKernelGGL((k_eqgrid<GM_COMMON, false, 1>), g, GT_BLOCK, 0, c->stream, a);
+        else hipLaunchKernelGGL((k_eqgrid<GM_ROWS, false, 1>), g, GT_BLOCK, 0, c->stream, a);
+        LAUNCH_OK();
+    }
+    acct_eq(c, nel);
+    if (has_g) acct_and1(c, nel);
+    acct_b2a(c, nel);
+    if (mode != GM_STORE) acct_reshare(c, a.N, ndot);
+    return GT_OK;
+}
+
+extern "C" int gt_oaa(gt_ctx *c, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z)
+{
+    if (!c || !shares_ok(W, w) || !shares_ok(u, n) || !shares_ok(z, n) || w == 0 || w > 0xffffffffu) return GT_EINVAL;
+    Timed T(c);
+    GridArgs a{}; a.u = to_p6(u); a.base = 0; a.w = (u32)w; a.N = n; a.N8 = pad8(n);
+    a.W1 = to_p6(W); a.w1off = 0; a.out = to_p6(z); a.epi = 0;
+    return T.finish(do_grid(c, GM_COMMON, false, 1, a));
+}
+
+static int div_steps(gt_ctx *c, P6 S, P6 Q, P6 rem, P6 quo, u64 n)
+{
+    for (u32 t = 0; t <= c->tau; t++) {
+        DivArgs a{}; a.c = kc(c, c->op++); a.S = S; a.Q = Q; a.r = rem; a.quo = quo; a.n = n; a.first = t == 0;
+        if (n) { hipLaunchKernelGGL(k_div_step, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a); LAUNCH_OK(); }
+        acct_ge(c, n); acct_b2a(c, n); acct_reshare(c, n, 1);
+    }
+    return GT_OK;
+}
+
+extern "C" int gt_div(gt_ctx *c, const gt_shares *S, const gt_shares *Q, size_t n, const gt_shares *q)
+{
+    if (!c || !shares_ok(S, n) || !shares_ok(Q, n) || !shares_ok(q, n)) return GT_EINVAL;
+    Timed T(c);
+    DSh rem;
+    int rc = dsh_alloc(rem, n, c->stream);
+    if (rc == GT_OK) rc = div_steps(c, to_p6(S), to_p6(Q), rem.v, to_p6(q), n);
+    rc = T.finish(rc);
+    dsh_free(rem);
+    return rc;
+}
+
+// ---- training -------------------------------------------------------------------------
+static void train_free(gt_train *t)
+{
+    DSh *all[] = { &t->XT, &t->BT, &t->M, &t->T, &t->F, &t->C, &t->Cn, &t->gamma, &t->Gn, &t->isLeaf, &t->LT, &t->SD,
+                   &t->split, &t->S, &t->Q, &t->quo, &t->rem, &t->val[0], &t->val[1], &t->idx[0], &t->idx[1],
+                   &t->tval, &t->best, &t->lab, &t->Clast, &t->Glast, &t->Slast };
+    for (DSh *s : all) dsh_free(*s);
+    if (t->Zacc) (void)hipFree(t->Zacc);
+    delete t;
+}
+
+extern "C" int gt_train_destroy(gt_train *t) { if (!t) return GT_EINVAL; (void)hipDeviceSynchronize(); train_free(t); return GT_OK; }
+
+extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y, size_t N, uint32_t d,
+                               uint32_t H, gt_train **out)
+{
+    if (!c || !out || N == 0 || N > GT_MAX_N || d == 0 || d > 65536 || H > GT_MAX_DEPTH) return GT_EINVAL;
+    if (!shares_ok(X, N * d) || !shares_ok(Y, N * c->K)) return GT_EINVAL;
+    Timed T(c);
+    gt_train *t = new (std::nothrow) gt_train();
+    if (!t) return T.finish(GT_ENOMEM);
+    const u32 K = c->K;
+    const size_t N8 = pad8(N), nmax = (size_t)1 << H, nodes = ((size_t)2 << H) - 1, CW = (size_t)d * K + K;
+    size_t P2 = 1; while (P2 < d) P2 *= 2;
+    t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
+    t->finished = false; t->Zacc = nullptr;
+    hipStream_t s = c->stream;
+    int rc = GT_OK;
+    struct { DSh *v; size_t n; } plan[] = {
+        { &t->XT, d * N8 }, { &t->BT, CW * N8 }, { &t->M, N }, { &t->T, nodes }, { &t->F, nodes },
+        { &t->C, nmax * CW }, { &t->Cn, nmax * CW }, { &t->gamma, nmax * d }, { &t->Gn, nmax * d }, { &t->isLeaf, nmax },
+        { &t->LT, nmax * N8 }, { &t->SD, nmax }, { &t->split, nmax }, { &t->S, nmax * d * 2 }, { &t->Q, nmax * d * 2 },
+        { &t->quo, nmax * d * 2 }, { &t->rem, nmax * d * 2 }, { &t->val[0], nmax * P2 }, { &t->val[1], nmax * P2 },
+        { &t->idx[0], nmax * P2 }, { &t->idx[1], nmax * P2 }, { &t->tval, N }, { &t->best, nmax }, { &t->lab, nmax },
+        { &t->Clast, nmax * CW }, { &t->Glast, nmax * d }, { &t->Slast, nmax * d },
+    };
+    for (auto &pl : plan) { rc = dsh_alloc(*pl.v, pl.n, s); if (rc != GT_OK) break; }
+    if (rc == GT_OK && hipMalloc(&t->Zacc, 3 * nmax * CW * 8) != hipSuccess) rc = GT_ENOMEM;
+    if (rc != GT_OK) { (void)hipStreamSynchronize(s); train_free(t); return T.finish(rc); }
+    // sample-contiguous copies of X and Y (Y goes behind the d*K product columns)
+    hipLaunchKernelGGL(k_transpose, dim3(blocks_for(N * d, 256)), dim3(256), 0, s, t->XT.v, to_p6(X), (u64)N, (u64)N8, d);
+    hipLaunchKernelGGL(k_transpose, dim3(blocks_for(N * K, 256)), dim3(256), 0, s, off6(t->BT.v, (size_t)d * K * N8), to_p6(Y), (u64)N, (u64)N8, K);
+    // one-time products X[i][k] * Y[i][c]
+    MultArgs a{}; a.x = t->XT.v; a.y = off6(t->BT.v, (size_t)d * K * N8); a.z = t->BT.v;
+    a.n = (u64)d * K * N8; a.N = N; a.N8 = N8; a.K = K;
+    rc = do_mult(c, 1, a);
+    acct_reshare(c, (u64)N * d * K, 1);
+    // M = 0, the root is a leaf, no candidate used yet
+    hipLaunchKernelGGL(k_fill_const, dim3(1), dim3(256), 0, s, t->F.v, (u64)0, (u64)1, (u64)1);
+    hipLaunchKernelGGL(k_fill_const, dim3(blocks_for(d, 256)), dim3(256), 0, s, t->gamma.v, (u64)0, (u64)d, (u64)1);
+    if (rc == GT_OK && hipGetLastError() != hipSuccess) rc = GT_EHIP;
+    rc = T.finish(rc);
+    if (rc != GT_OK) { train_free(t); return rc; }
+    *out = t;
+    return GT_OK;
+}
+
+// data partition: Tval = T_level(h-1)[M - base], Dval = X[i][Tval], M <- 2M + Dval + 1
+static int partition(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 wprev = (u64)1 << (h - 1), base = wprev - 1;
+    GridArgs a{}; a.u = t->M.v; a.base = base; a.w = (u32)wprev; a.N = t->N; a.N8 = t->N8;
+    a.W1 = t->T.v; a.w1off = base; a.out = t->tval.v; a.epi = 0;
+    GTCHK(do_grid(c, GM_COMMON, false, 1, a));
+    GridArgs b{}; b.u = t->tval.v; b.base = 0; b.w = t->d; b.N = t->N; b.N8 = t->N8;
+    b.XT = t->XT.v; b.out = t->M.v; b.prev = t->M.v; b.epi = 1;
+    return do_grid(c, GM_ROWS, false, 1, b);
+}
+
+static int leaf_onehot(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 nh = (u64)1 << h, base = nh - 1;
+    GTCHK(do_eq(c, true, t->F.v, base, nullptr, 1, t->isLeaf.v, nh));
+    GridArgs a{}; a.u = t->M.v; a.base = base; a.w = (u32)nh; a.N = t->N; a.N8 = t->N8;
+    a.g = t->isLeaf.v; a.out = t->LT.v;
+    return do_grid(c, GM_STORE, true, 1, a);
+}
+
+static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
+{
+    const u64 nh = (u64)1 << h, dK = (u64)t->d * t->K;
+    const u32 ncol = totals_only ? t->K : t->CW;
+    const u64 colbase = totals_only ? dK : 0;
+    const u32 op = c->op++;
+    HIPCHK(hipMemsetAsync(t->Zacc, 0, 3 * nh * ncol * 8, c->stream));
+    CountArgs a{}; a.LT = t->LT.v; a.BT = t->BT.v; a.N8 = t->N8; a.nh = (u32)nh; a.ncol = ncol; a.colbase = colbase;
+    a.Zacc = t->Zacc; a.kchunk = 2048;
+    a.nchunk = (u32)((t->N8 + a.kchunk - 1) / a.kchunk);
+    dim3 g((ncol + CT_T - 1) / CT_T, (unsigned)((nh + CT_T - 1) / CT_T), 3 * a.nchunk);
+    hipLaunchKernelGGL(k_count, g, dim3(256), 0, c->stream, a);
+    LAUNCH_OK();
+    CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
+    hipLaunchKernelGGL(k_count_fin, dim3(tiles(f.n)), GT_BLOCK, 0, c->stream, f);
+    LAUNCH_OK();
+    acct_reshare(c, nh * ncol, 1);
+    return GT_OK;
+}
+
+static int select_max(gt_ctx *c, SelArgs a)
+{
+    a.c = kc(c, c->op++);
+    if (a.n) { hipLaunchKernelGGL(k_select_max, dim3(tiles(a.n)), GT_BLOCK, 0, c->stream, a); LAUNCH_OK(); }
+    acct_ge(c, a.n); acct_b2a(c, a.n); acct_reshare(c, a.n, 2);
+    return GT_OK;
+}
+
+static int heuristic(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 nh = (u64)1 << h, d = t->d, nq = nh * d * 2, ns = nh * d;
+    PrepArgs pa{}; pa.c = kc(c, c->op++); pa.C = t->C.v; pa.S = t->S.v; pa.Q = t->Q.v; pa.n = nq; pa.d = t->d; pa.K = t->K; pa.CW = t->CW;
+    hipLaunchKernelGGL(k_score_prep, dim3(tiles(nq)), GT_BLOCK, 0, c->stream, pa); LAUNCH_OK();
+    acct_reshare(c, nq, 2);
+    // empty branch: make the divisor 1
+    DSh &z = t->rem;    // scratch for the 0/1 sharing of [Q == 0]
+    GTCHK(do_eq(c, false, t->Q.v, 0, nullptr, 0, z.v, nq));
+    hipLaunchKernelGGL(k_add_inplace, dim3(blocks_for(nq, 256)), dim3(256), 0, c->stream, t->Q.v, z.v, nq); LAUNCH_OK();
+    GTCHK(div_steps(c, t->S.v, t->Q.v, t->rem.v, t->quo.v, nq));
+    hipLaunchKernelGGL(k_iota, dim3(blocks_for(nh * t->P2, 256)), dim3(256), 0, c->stream, t->idx[0].v, t->val[0].v, (u32)nh, t->P2, t->d); LAUNCH_OK();
+    MaskArgs ma{}; ma.c = kc(c, c->op++); ma.quo = t->quo.v; ma.gamma = t->gamma.v; ma.score = t->Slast.v; ma.val = t->val[0].v; ma.n = ns; ma.d = t->d; ma.P2 = t->P2;
+    hipLaunchKernelGGL(k_mask_score, dim3(tiles(ns)), GT_BLOCK, 0, c->stream, ma); LAUNCH_OK();
+    acct_reshare(c, ns, 1);
+    int cur = 0;
+    for (u64 len = t->P2; len > 1; len /= 2) {
+        SelArgs sa{}; sa.vin = t->val[cur].v; sa.iin = t->idx[cur].v; sa.vout = t->val[cur ^ 1].v; sa.iout = t->idx[cur ^ 1].v;
+        sa.n = nh * (len / 2); sa.len = (u32)len; sa.mode = 0;
+        GTCHK(select_max(c, sa));
+        cur ^= 1;
+    }
+    return copy6(c, t->SD.v, 0, t->idx[cur].v, 0, 1, nh);
+}
+
+static int update(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 nh = (u64)1 << h, base = nh - 1, d = t->d, CW = t->CW;
+    GammaArgs ga{}; ga.c = kc(c, c->op++); ga.SD = t->SD.v; ga.gamma = t->gamma.v; ga.n = nh * d; ga.d = t->d;
+    hipLaunchKernelGGL(k_gamma, dim3(tiles(ga.n)), GT_BLOCK, 0, c->stream, ga); LAUNCH_OK();
+    acct_eq(c, nh * d); acct_b2a(c, nh * d); acct_reshare(c, nh * d, 1);
+    SplitArgs sa{}; sa.c = kc(c, c->op++); sa.C = t->C.v; sa.isLeaf = t->isLeaf.v; sa.F = t->F.v; sa.split = t->split.v;
+    sa.n = nh; sa.base = base; sa.K = t->K; sa.CW = t->CW; sa.dK = (u64)t->d * t->K;
+    hipLaunchKernelGGL(k_split, dim3(tiles(nh)), GT_BLOCK, 0, c->stream, sa); LAUNCH_OK();
+    acct_reshare(c, nh, 1); acct_eq(c, nh); acct_and1(c, nh); acct_b2a(c, nh); acct_reshare(c, nh, 1);
+    // keep this level's statistics and flags for export; T takes the split decisions
+    GTCHK(copy6(c, t->Clast.v, 0, t->C.v, 0, 1, nh * CW));
+    GTCHK(copy6(c, t->Glast.v, 0, t->gamma.v, 0, 1, nh * d));
+    GTCHK(copy6(c, t->T.v, base, t->SD.v, 0, 1, nh));
+    t->last = h;
+    // children: statistics inherited unless the node was split; gamma always inherited
+    MultArgs m{}; m.x = t->C.v; m.y = t->split.v; m.z = t->Cn.v; m.n = nh * CW; m.CW = t->CW;
+    GTCHK(do_mult(c, 2, m));
+    acct_reshare(c, nh * CW, 1);
+    std::swap(t->C, t->Cn);
+    if (h + 1 <= t->H && 2 * nh <= ((u64)1 << t->H)) {
+        hipLaunchKernelGGL(k_dup_rows, dim3(blocks_for(nh * d, 256)), dim3(256), 0, c->stream, t->Gn.v, t->gamma.v, nh, d); LAUNCH_OK();
+        std::swap(t->gamma, t->Gn);
+    }
+    return GT_OK;
+}
+
+extern "C" int gt_train_level(gt_ctx *c, gt_train *t, uint32_t h)
+{
+    if (!c || !t) return GT_EINVAL;
+    if (t->finished || h != t->level || h >= t->H) return GT_ESTATE;
+    Timed T(c);
+    int rc = GT_OK;
+    if (h > 0) rc = partition(c, t, h);
+    if (rc == GT_OK) rc = leaf_onehot(c, t, h);
+    if (rc == GT_OK) rc = count(c, t, h, false);
+    if (rc == GT_OK) rc = heuristic(c, t, h);
+    if (rc == GT_OK) rc = update(c, t, h);
+    if (rc == GT_OK) t->level = h + 1;
+    return T.finish(rc);
+}
+
+static int tree_alloc(gt_ctx *c, u32 H, bool thr, gt_tree **out)
+{
+    gt_tree *tr = new (std::nothrow) gt_tree();
+    if (!tr) return GT_ENOMEM;
+    tr->H = H; tr->has_thr = thr;
+    const size_t nint = ((size_t)1 << H) - 1, nleaf = (size_t)1 << H;
+    int rc = dsh_alloc(tr->feat, nint, c->stream);
+    if (rc == GT_OK) rc = dsh_alloc(tr->leaf, nleaf, c->stream);
+    if (rc == GT_OK && thr) rc = dsh_alloc(tr->thr, nint, c->stream);
+    if (rc != GT_OK) { (void)hipStreamSynchronize(c->stream); dsh_free(tr->feat); dsh_free(tr->leaf); dsh_free(tr->thr); delete tr; return rc; }
+    *out = tr;
+    return GT_OK;
+}
+
+extern "C" int gt_train_finish(gt_ctx *c, gt_train *t, gt_tree **out)
+{
+    if (!c || !t || !out) return GT_EINVAL;
+    if (t->finished || t->level != t->H) return GT_ESTATE;
+    Timed T(c);
+    const u32 H = t->H;
+    const u64 nh = (u64)1 << H, base = nh - 1, dK = (u64)t->d * t->K;
+    int rc = GT_OK;
+    if (H > 0) rc = partition(c, t, H);
+    if (rc == GT_OK) rc = leaf_onehot(c, t, H);
+    if (rc == GT_OK) rc = count(c, t, H, true);
+    // label = first maximum of the class totals
+    if (rc == GT_OK) rc = copy6(c, t->best.v, 0, t->C.v, dK, t->CW, nh);
+    if (rc == GT_OK) { hipLaunchKernelGGL(k_fill_const, dim3(blocks_for(nh, 256)), dim3(256), 0, c->stream, t->lab.v, (u64)0, nh, (u64)0); if (hipGetLastError() != hipSuccess) rc = GT_EHIP; }
+    for (u32 cl = 1; cl < t->K && rc == GT_OK; cl++) {
+        SelArgs sa{}; sa.vin = t->best.v; sa.iin = t->lab.v; sa.vout = t->best.v; sa.iout = t->lab.v; sa.C = t->C.v;
+        sa.n = nh; sa.CW = t->CW; sa.coff = dK + cl; sa.cidx = cl; sa.mode = 1;
+        rc = select_max(c, sa);
+    }
+    if (rc == GT_OK) rc = copy6(c, t->T.v, base, t->lab.v, 0, 1, nh);
+    if (rc == GT_OK) rc = copy6(c, t->Clast.v, 0, t->C.v, 0, 1, nh * t->CW);
+    gt_tree *tr = nullptr;
+    if (rc == GT_OK) rc = tree_alloc(c, H, false, &tr);
+    if (rc == GT_OK) rc = copy6(c, tr->feat.v, 0, t->T.v, 0, 1, base);
+    if (rc == GT_OK) rc = copy6(c, tr->leaf.v, 0, t->T.v, base, 1, nh);
+    if (rc == GT_OK) { t->last = H; t->level = H + 1; t->finished = true; }
+    rc = T.finish(rc);
+    if (rc != GT_OK) { if (tr) gt_tree_destroy(tr); return rc; }
+    *out = tr;
+    return GT_OK;
+}
+
+extern "C" size_t gt_train_export_size(const gt_train *t, int what)
+{
+    if (!t) return 0;
+    const size_t nh = (size_t)1 << t->last;
+    switch (what) {
+    case GT_X_T: case GT_X_F: return ((size_t)2 << t->H) - 1;
+    case GT_X_M: return t->N;
+    case GT_X_C: return nh * t->CW;
+    case GT_X_GAMMA: case GT_X_SCORE: return nh * t->d;
+    case GT_X_SD: return nh;
+    case GT_X_L: return nh * t->N8;
+    case GT_X_C_PAPER: return nh * (1 + t->K) * 2 * t->d;
+    default: return 0;
+    }
+}
+
+extern "C" int gt_train_export(gt_ctx *c, const gt_train *t, int what, const gt_shares *out)
+{
+    if (!c || !t) return GT_EINVAL;
+    const size_t n = gt_train_export_size(t, what);
+    if (what < GT_X_T || what > GT_X_C_PAPER || !shares_ok(out, n)) return GT_EINVAL;
+    Timed T(c);
+    const DSh *src = nullptr;
+    switch (what) {
+    case GT_X_T: src = &t->T; break;
+    case GT_X_F: src = &t->F; break;
+    case GT_X_M: src = &t->M; break;
+    case GT_X_C: src = &t->Clast; break;
+    case GT_X_GAMMA: src = &t->Glast; break;
+    case GT_X_SD: src = &t->SD; break;
+    case GT_X_L: src = &t->LT; break;
+    case GT_X_SCORE: src = &t->Slast; break;
+    default: break;
+    }
+    int rc = GT_OK;
+    if (src) rc = copy6(c, to_p6(out), 0, src->v, 0, 1, n);
+    else {
+        const u32 nh = 1u << t->last;
+        hipLaunchKernelGGL(k_c_paper, dim3(blocks_for(n, 256)), dim3(256), 0, c->stream, t->Clast.v, to_p6(out), nh, t->d, t->K, t->CW);
+        if (hipGetLastError() != hipSuccess) rc = GT_EHIP;
+    }
+    return T.finish(rc);
+}
+
+extern "C" int gt_train_import(gt_ctx *c, gt_train *t, uint32_t h, const gt_shares *M, const gt_shares *Tprev,
+                               const gt_shares *Fl, const gt_shares *Cc, const gt_shares *gm)
+{
+    if (!c || !t || h > t->H) return GT_EINVAL;
+    const size_t nh = (size_t)1 << h, base = nh - 1;
+    if (!shares_ok(M, t->N) || !shares_ok(Fl, nh) || !shares_ok(Cc, nh * t->CW) || !shares_ok(gm, nh * t->d)) return GT_EINVAL;
+    if (h > 0 && !shares_ok(Tprev, nh / 2)) return GT_EINVAL;
+    Timed T(c);
+    int rc = copy6(c, t->M.v, 0, to_p6(M), 0, 1, t->N);
+    if (rc == GT_OK && h > 0) rc = copy6(c, t->T.v, base - nh / 2, to_p6(Tprev), 0, 1, nh / 2);
+    if (rc == GT_OK) rc = copy6(c, t->F.v, base, to_p6(Fl), 0, 1, nh);
+    if (rc == GT_OK) rc = copy6(c, t->C.v, 0, to_p6(Cc), 0, 1, nh * t->CW);
+    if (rc == GT_OK) rc = copy6(c, t->gamma.v, 0, to_p6(gm), 0, 1, nh * t->d);
+    if (rc == GT_OK) { t->level = h; t->finished = false; }
+    return T.finish(rc);
+}
+
+// ---- inference ------------------------------------------------------------------------
+extern "C" int gt_tree_import(gt_ctx *c, const gt_shares *feat, const gt_shares *thr, const gt_shares *leaf,
+                              uint32_t H, gt_tree **out)
+{
+    if (!c || !out || H > GT_MAX_DEPTH) return GT_EINVAL;
+    const size_t nint = ((size_t)1 << H) - 1, nleaf = (size_t)1 << H;
+    if (!shares_ok(feat, nint) || !shares_ok(leaf, nleaf) || (thr && !shares_ok(thr, nint))) return GT_EINVAL;
+    Timed T(c);
+    gt_tree *tr = nullptr;
+    int rc = tree_alloc(c, H, thr != nullptr, &tr);
+    if (rc == GT_OK) rc = copy6(c, tr->feat.v, 0, to_p6(feat), 0, 1, nint);
+    if (rc == GT_OK) rc = copy6(c, tr->leaf.v, 0, to_p6(leaf), 0, 1, nleaf);
+    if (rc == GT_OK && thr) rc = copy6(c, tr->thr.v, 0, to_p6(thr), 0, 1, nint);
+    rc = T.finish(rc);
+    if (rc != GT_OK) { if (tr) gt_tree_destroy(tr); return rc; }
+    *out = tr;
+    return GT_OK;
+}
+
+extern "C" int gt_tree_export(gt_ctx *c, const gt_tree *tr, const gt_shares *feat, const gt_shares *leaf)
+{
+    if (!c || !tr) return GT_EINVAL;
+    const size_t nint = ((size_t)1 << tr->H) - 1, nleaf = (size_t)1 << tr->H;
+    if (!shares_ok(feat, nint) || !shares_ok(leaf, nleaf)) return GT_EINVAL;
+    Timed T(c);
+    int rc = copy6(c, to_p6(feat), 0, tr->feat.v, 0, 1, nint);
+    if (rc == GT_OK) rc = copy6(c, to_p6(leaf), 0, tr->leaf.v, 0, 1, nleaf);
+    return T.finish(rc);
+}
+
+extern "C" int gt_tree_destroy(gt_tree *tr)
+{
+    if (!tr) return GT_EINVAL;
+    (void)hipDeviceSynchronize();
+    dsh_free(tr->feat); dsh_free(tr->thr); dsh_free(tr->leaf);
+    delete tr;
+    return GT_OK;
+}
+
+extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, size_t NI, uint32_t d, const gt_shares *R)
+{
+    if (!c || !tr || NI == 0 || d == 0 || d > 65536) return GT_EINVAL;
+    if (!shares_ok(I, NI * d) || !shares_ok(R, NI)) return GT_EINVAL;
+    Timed T(c);
+    const size_t N8 = pad8(NI);
+    const u32 H = tr->H;
+    DSh IT, tidx, f, th, x;
+    int rc = dsh_alloc(IT, (size_t)d * N8, c->stream);
+    if (rc == GT_OK) rc = dsh_alloc(tidx, NI, c->stream);
+    if (rc == GT_OK) rc = dsh_alloc(f, NI, c->stream);
+    if (rc == GT_OK && tr->has_thr) rc = dsh_alloc(th, NI, c->stream);
+    if (rc == GT_OK && tr->has_thr) rc = dsh_alloc(x, NI, c->stream);
+    if (rc == GT_OK) {
+        hipLaunchKernelGGL(k_transpose, dim3(blocks_for(NI * d, 256)), dim3(256), 0, c->stream, IT.v, to_p6(I), (u64)NI, (u64)N8, d);
+        if (hipGetLastError() != hipSuccess) rc = GT_EHIP;
+    }
+    for (u32 n = 0; n < H && rc == GT_OK; n++) {
+        const u64 w = (u64)1 << n, base = w - 1;
+        GridArgs a{}; a.u = tidx.v; a.base = base; a.w = (u32)w; a.N = NI; a.N8 = N8;
+        a.W1 = tr->feat.v; a.w1off = base; a.out = f.v; a.epi = 0;
+        if (tr->has_thr) { a.W2 = tr->thr.v; a.w2off = base; a.out2 = th.v; }
+        rc = do_grid(c, GM_COMMON, false, tr->has_thr ? 2 : 1, a);
+        if (rc != GT_OK) break;
+        GridArgs b{}; b.u = f.v; b.base = 0; b.w = d; b.N = NI; b.N8 = N8; b.XT = IT.v;
+        if (tr->has_thr) { b.out = x.v; b.epi = 0; } else { b.out = tidx.v; b.prev = tidx.v; b.epi = 1; }
+        rc = do_grid(c, GM_ROWS, false, 1, b);
+        if (rc != GT_OK) break;
+        if (tr->has_thr) {
+            CmpArgs ca{}; ca.c = kc(c, c->op++); ca.th = th.v; ca.x = x.v; ca.tidx = tidx.v; ca.n = NI;
+            hipLaunchKernelGGL(k_cmp_step, dim3(tiles(NI)), GT_BLOCK, 0, c->stream, ca);
+            if (hipGetLastError() != hipSuccess) rc = GT_EHIP;
+            acct_ge(c, NI); acct_b2a(c, NI);
+        }
+    }
+    if (rc == GT_OK) {
+        const u64 nleaf = (u64)1 << H;
+        GridArgs a{}; a.u = tidx.v; a.base = nleaf - 1; a.w = (u32)nleaf; a.N = NI; a.N8 = N8;
+        a.W1 = tr->leaf.v; a.w1off = 0; a.out = to_p6(R); a.epi = 0;
+        rc = do_grid(c, GM_COMMON, false, 1, a);
+    }
+    rc = T.finish(rc);
+    dsh_free(IT); dsh_free(tidx); dsh_free(f); dsh_free(th); dsh_free(x);
+    return rc;
+}

@@ -1,0 +1,319 @@
+"""GPU library against the CPU oracle: every share plane bit for bit, plus the
+round and wire-byte counters.  All calls go through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+M64 = (1 << 64) - 1
+
+
+def u64(vals):
+    return np.array([int(v) & M64 for v in vals], dtype=np.uint64)
+
+
+@pytest.fixture(scope="module")
+def mods():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from oracle import Oracle
+    from paper_2305_00645_amd import gtree
+    gtree.load()
+    return Oracle, gtree
+
+
+def pair(mods, seed, tau=16, K=2):
+    Oracle, gtree = mods
+    return Oracle(seed, tau=tau, K=K), gtree.GTree(seed, tau=tau, K=K)
+
+
+def same(gs, oc, what=""):
+    """gs: gtree.Shares, oc: oracle components (3, n)."""
+    comp = gs.components()
+    assert comp.shape == oc.shape, (what, comp.shape, oc.shape)
+    if not np.array_equal(comp, oc):
+        bad = np.argwhere(comp != oc)
+        raise AssertionError("%s: %d of %d words differ, first at %s" % (what, len(bad), comp.size, bad[0]))
+
+
+def same_stats(o, g):
+    ro, wo = o.stats()
+    rg, wg, _ = g.stats()
+    assert ro == rg and np.array_equal(wo, wg), (ro, rg, wo.tolist(), wg.tolist())
+    assert o.op_counter() == g.op_counter()
+
+
+@pytest.mark.parametrize("n", [1, 7, 8, 63, 64, 65, 1000, 4099])
+def test_share_reconstruct(mods, seed, n):
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(n)
+    x = rng.integers(0, M64, size=n, dtype=np.uint64)
+    so, sg = o.share(x), g.share_a(x)
+    same(sg, so, "share")
+    assert np.array_equal(g.rec(sg), x)
+
+
+def test_empty_vectors(mods, seed):
+    o, g = pair(mods, seed)
+    sg = g.share_a(np.zeros(0, dtype=np.uint64))
+    o.share(np.zeros(0, dtype=np.uint64))
+    assert g.mult(sg, sg).n == 0
+    o.mult(np.zeros((3, 0), dtype=np.uint64), np.zeros((3, 0), dtype=np.uint64))
+    assert o.op_counter() == g.op_counter()
+
+
+@pytest.mark.parametrize("n", [1, 9, 512, 1531])
+def test_mult(mods, seed, n):
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(10 + n)
+    x = rng.integers(0, M64, size=n, dtype=np.uint64)
+    y = rng.integers(0, M64, size=n, dtype=np.uint64)
+    xo, yo = o.share(x), o.share(y)
+    xg, yg = g.share_a(x), g.share_a(y)
+    zo, zg = o.mult(xo, yo), g.mult(xg, yg)
+    same(zg, zo, "mult")
+    assert np.array_equal(g.rec(zg), x * y)
+    same_stats(o, g)
+
+
+def test_eq_public_and_shared(mods, seed):
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(3)
+    xs, ys = [], []
+    for b in range(64):
+        v = int(rng.integers(0, M64, dtype=np.uint64))
+        xs.append(v); ys.append(v ^ (1 << b))
+    for v in [0, 1, M64, 1 << 63, (1 << 63) - 1]:
+        xs += [v, v, v]; ys += [v, v + 1, v - 1]
+    for _ in range(150):
+        v = int(rng.integers(0, M64, dtype=np.uint64))
+        xs.append(v); ys.append(v if rng.random() < 0.5 else int(rng.integers(0, M64, dtype=np.uint64)))
+    x, y = u64(xs), u64(ys)
+    xo, xg = o.share(x), g.share_a(x)
+    eo, eg = o.eq_a(xo, y), g.eq_a(xg, y)
+    same(eg, eo, "eq_a public")
+    assert np.array_equal(g.rec(eg), (x == y).astype(np.uint64))
+    yo, yg = o.share(y), g.share_a(y)
+    do = xo - yo
+    dg = g.new(x.size); dg.t.copy_(xg.t - yg.t)
+    eo, eg = o.eq_a(do, None), g.eq_a(dg, None)
+    same(eg, eo, "eq_a shared")
+    same_stats(o, g)
+
+
+def test_ge(mods, seed):
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(4)
+    xs, ys = [], []
+    smalls = [0, 1, 2, 5, 1 << 16, (1 << 40) - 1, 1 << 40, 1 << 62, (1 << 63) - 1]
+    for a in smalls:
+        for b in smalls:
+            xs.append(a); ys.append(b)
+    for b in range(63):
+        v = int(rng.integers(0, 1 << 62))
+        xs.append(v | (1 << b)); ys.append(v & ~(1 << b))
+        xs.append(v & ~(1 << b)); ys.append(v | (1 << b))
+    for _ in range(300):
+        xs.append(int(rng.integers(0, 1 << 62))); ys.append(int(rng.integers(0, 1 << 62)))
+    for a, b in [(-5, 3), (3, -5), (-1, -1), (-7, -8)]:
+        xs.append(a); ys.append(b)
+    x, y = u64(xs), u64(ys)
+    zo = o.ge_a(o.share(x), o.share(y))
+    zg = g.ge_a(g.share_a(x), g.share_a(y))
+    same(zg, zo, "ge_a")
+    want = u64([1 if a >= b else 0 for a, b in zip(xs, ys)])
+    assert np.array_equal(g.rec(zg), want)
+    same_stats(o, g)
+
+
+@pytest.mark.parametrize("w,n", [(1, 5), (2, 64), (5, 100), (16, 513), (64, 1025), (37, 777)])
+def test_oaa(mods, seed, w, n):
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(w * 1000 + n)
+    Wp = rng.integers(0, M64, size=w, dtype=np.uint64)
+    u = rng.integers(0, w + 2, size=n).astype(np.uint64)
+    zo = o.oaa(o.share(Wp), o.share(u))
+    zg = g.oaa(g.share_a(Wp), g.share_a(u))
+    same(zg, zo, "oaa")
+    want = np.array([Wp[int(i)] if int(i) < w else 0 for i in u], dtype=np.uint64)
+    assert np.array_equal(g.rec(zg), want)
+    same_stats(o, g)
+
+
+@pytest.mark.parametrize("tau", [5, 16])
+def test_div(mods, seed, tau):
+    o, g = pair(mods, seed, tau=tau)
+    rng = np.random.default_rng(6)
+    Q = [1, 2, 3, 7, 1000, (1 << 40) - 1] + [int(rng.integers(1, 1 << 40)) for _ in range(200)]
+    S = [int(rng.integers(0, q + 1)) for q in Q]
+    S[0], S[1], S[2] = 1, 0, 3
+    qo = o.div(o.share(u64(S)), o.share(u64(Q)))
+    qg = g.div(g.share_a(u64(S)), g.share_a(u64(Q)))
+    same(qg, qo, "div")
+    assert np.array_equal(g.rec(qg), u64([(s << tau) // q for s, q in zip(S, Q)]))
+    same_stats(o, g)
+
+
+# ------------------------------------------------------------------ training
+def run_train_pair(mods, seed, w, tau=16, H=None, every_level=True):
+    from oracle import X_T, X_F, X_M, X_C, X_GAMMA, X_SD, X_L, X_SCORE, X_C_PAPER
+    H = w["H"] if H is None else H
+    N, d, K = w["N"], w["d"], w["K"]
+    o, g = pair(mods, seed, tau=tau, K=K)
+    xo, yo = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
+    xg, yg = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+    o.train_create(xo, yo, N, d, H)
+    g.train_create(xg, yg, N, d, H)
+    names = dict(M=X_M, L=X_L, C=X_C, SCORE=X_SCORE, SD=X_SD, GAMMA=X_GAMMA, F=X_F, T=X_T, CP=X_C_PAPER)
+    for h in range(H):
+        o.train_level(h)
+        g.train_level(h)
+        if every_level or h == H - 1:
+            for nm, what in names.items():
+                same(g.train_export(what), o.train_export(what), "level %d %s" % (h, nm))
+        same_stats(o, g)
+    fo, lo = o.train_finish()
+    tree = g.train_finish()
+    fg, lg = tree.export()
+    same(fg, fo, "tree features")
+    same(lg, lo, "tree labels")
+    for nm in ("M", "L", "C", "F", "T"):
+        same(g.train_export(names[nm]), o.train_export(names[nm]), "finish %s" % nm)
+    same_stats(o, g)
+    return o, g, tree, (fo, lo)
+
+
+def test_train_c1(mods, seed):
+    import plain_cart
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c1_train()
+    o, g, tree, (fo, lo) = run_train_pair(mods, seed, w)
+    ref = plain_cart.train(w["X"], w["y"], w["K"], w["H"], 16)
+    fg, lg = tree.export()
+    assert np.array_equal(g.rec(fg).astype(np.int64), ref["T"][:7])
+    assert np.array_equal(g.rec(lg).astype(np.int64), ref["T"][7:])
+    # inference with the trained tree, binary mode, against plaintext prediction
+    rng = np.random.default_rng(5)
+    I = (rng.random((333, w["d"])) < 0.5).astype(np.uint64)
+    Ro = o.infer(fo, None, lo, w["H"], o.share(I.reshape(-1)), 333, w["d"])
+    Rg = g.infer_batch(tree, g.share_a(I.reshape(-1)), 333, w["d"])
+    same(Rg, Ro, "inference on trained tree")
+    assert np.array_equal(g.rec(Rg).astype(np.int64), plain_cart.predict(ref["T"], w["H"], I))
+    same_stats(o, g)
+
+
+def test_train_c2_depth7(mods, seed):
+    from paper_2305_00645_amd import workloads as wl
+    run_train_pair(mods, seed, wl.c2_train(), H=7, every_level=False)
+
+
+def test_train_multiclass_ragged(mods, seed):
+    rng = np.random.default_rng(77)
+    N, d, K = 203, 9, 4
+    X = (rng.random((N, d)) < 0.4).astype(np.uint64)
+    y = (X[:, 0].astype(np.int64) * 2 + X[:, 3].astype(np.int64) + (rng.random(N) < 0.1)) % K
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), tau=10)
+
+
+def test_train_c3_shape_reduced(mods, seed):
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c3_train(N=3000, H=4, n_thr=8)
+    run_train_pair(mods, seed, w, every_level=False)
+
+
+def test_train_degenerate(mods, seed):
+    X = np.array([[0, 1], [1, 1], [1, 0], [0, 0], [1, 1]], dtype=np.uint64)
+    y = np.ones(5, dtype=np.int64)
+    Y = np.zeros((5, 2), dtype=np.uint64); Y[:, 1] = 1
+    run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=2))
+    run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=0))
+    X1 = np.array([[0], [1], [1], [0]], dtype=np.uint64)
+    y1 = np.array([0, 1, 1, 0])
+    Y1 = np.zeros((4, 2), dtype=np.uint64); Y1[np.arange(4), y1] = 1
+    run_train_pair(mods, seed, dict(X=X1, Y=Y1, y=y1, N=4, d=1, K=2, H=2))
+
+
+def test_train_errors(mods, seed):
+    Oracle, gtree = mods
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c1_train(N=32, d=4, depth=2)
+    g = gtree.GTree(seed)
+    xg, yg = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+    g.train_create(xg, yg, 32, 4, 2)
+    with pytest.raises(gtree.GtError) as e:
+        g.train_level(1)                       # out of order
+    assert e.value.code == gtree.GT_ESTATE
+    with pytest.raises(gtree.GtError) as e:
+        g.train_create(xg, yg, 33, 4, 2)       # buffers too small
+    assert e.value.code == gtree.GT_EINVAL
+    with pytest.raises(gtree.GtError):
+        g.train_create(xg, yg, 32, 4, 99)      # depth over the limit
+
+
+# ------------------------------------------------------------------ inference
+@pytest.mark.parametrize("binary,NI,H", [(False, 1000, 7), (True, 1000, 7), (False, 77, 3), (True, 1, 2)])
+def test_infer(mods, seed, binary, NI, H):
+    import plain_cart
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c4_infer(NI=NI, H=H, binary=binary)
+    o, g = pair(mods, seed)
+    fo, lo = o.share(w["feat"]), o.share(w["leaf"])
+    fg, lg = g.share_a(w["feat"]), g.share_a(w["leaf"])
+    to = tg = None
+    if not binary:
+        to, tg = o.share(w["thr"]), g.share_a(w["thr"])
+    Io, Ig = o.share(w["I"].reshape(-1)), g.share_a(w["I"].reshape(-1))
+    tree = g.tree_import(fg, tg, lg, H)
+    Ro = o.infer(fo, to, lo, H, Io, NI, w["d"])
+    Rg = g.infer_batch(tree, Ig, NI, w["d"])
+    same(Rg, Ro, "inference")
+    T = np.concatenate([w["feat"], w["leaf"]]).astype(np.int64)
+    thr = None if binary else np.concatenate([w["thr"], np.zeros(1 << H, dtype=np.uint64)])
+    assert np.array_equal(g.rec(Rg).astype(np.int64), plain_cart.predict(T, H, w["I"], thr))
+    same_stats(o, g)
+
+
+def test_infer_depth0(mods, seed):
+    o, g = pair(mods, seed)
+    lo, lg = o.share(u64([3])), g.share_a(u64([3]))
+    Io, Ig = o.share(u64([1, 0, 1, 1])), g.share_a(u64([1, 0, 1, 1]))
+    tree = g.tree_import(g.new(0), None, lg, 0)
+    Ro = o.infer(np.zeros((3, 0), dtype=np.uint64), None, lo, 0, Io, 2, 2)
+    Rg = g.infer_batch(tree, Ig, 2, 2)
+    same(Rg, Ro, "depth 0")
+    assert g.rec(Rg).tolist() == [3, 3]
+
+
+def test_single_level_from_imported_state(mods, seed):
+    """One split-scoring level started from a synthetic state (reduced C5 recipe)."""
+    from oracle import X_M, X_C, X_SD, X_SCORE, X_F
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c5_level(N=5000, d=12, K=4, h=3)
+    N, d, K, h = w["N"], w["d"], w["K"], w["h"]
+    o, g = pair(mods, seed, K=K)
+    xo, yo = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
+    xg, yg = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+    o.train_create(xo, yo, N, d, h + 1)
+    g.train_create(xg, yg, N, d, h + 1)
+    CW = d * K + K
+    st = [w["M"], w["Tprev"], w["F"], np.zeros((1 << h) * CW, dtype=np.uint64), w["gamma"].reshape(-1)]
+    so = [o.share(a) for a in st]
+    sg = [g.share_a(a) for a in st]
+    o.train_import(h, *so)
+    g.train_import(h, *sg)
+    o.train_level(h)
+    g.train_level(h)
+    for what in (X_M, X_C, X_SCORE, X_SD, X_F):
+        same(g.train_export(what), o.train_export(what), "import level, export %d" % what)
+    # counts equal the plaintext histogram of the routed samples
+    X, y = w["X"].astype(np.int64), w["y"]
+    M = 2 * w["M"].astype(np.int64) + 1 + X[np.arange(N), w["Tprev"].astype(np.int64)[w["M"].astype(np.int64) - ((1 << (h - 1)) - 1)]]
+    assert np.array_equal(g.rec(g.train_export(X_M)).astype(np.int64), M)
+    C = g.rec(g.train_export(X_C)).astype(np.int64).reshape(1 << h, CW)
+    for r in range(1 << h):
+        sel = M == (1 << h) - 1 + r
+        for c in range(K):
+            assert C[r, d * K + c] == (sel & (y == c)).sum()
+            assert np.array_equal(C[r, :d * K].reshape(d, K)[:, c], X[sel & (y == c)].sum(axis=0))
+    same_stats(o, g)
