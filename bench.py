@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the GTree hot path on one MI355X.
+
+A step is one pass of the whole hot path at the scale workload (C5 of the workload
+list): the one-time products (a0), one full split-scoring level over 128 nodes
+(a1-a7: partition, leaf one-hot, class counts, Gini division, arg-max, updates), the
+label level (a8) and a depth-10 inference batch (b1-b5), all three parties on one GPU,
+inputs resident in device memory.  `value` is split candidates scored per second of
+the split-scoring level; the other parts are reported beside it.  One JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--samples", type=int, default=1000000, help="training samples (C5: 10^6)")
+    ap.add_argument("--instances", type=int, default=1000000, help="inference batch (C5: 10^6)")
+    ap.add_argument("--cpu-samples", type=int, default=40000, help="oracle sample for cpu_baseline (0 = skip)")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build simulates the three parties on ONE GPU; --gpus %d is not supported "
+              "(no collectives, no second device)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2305_00645_amd import gtree, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    gtree.load()
+
+    N, NI, d, K, h, Hinf = args.samples, args.instances, 64, 4, 7, 10
+    H = h + 1
+    CW = d * K + K
+    w = wl.c5_level(N=N, d=d, K=K, h=h)
+    wi = wl.c5_infer(NI=NI, d=d, H=Hinf, K=K)
+
+    def setup(profile):
+        g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=K, profile=profile)
+        st = dict(
+            X=g.share_a(w["X"].reshape(-1)), Y=g.share_a(w["Y"].reshape(-1)),
+            M=g.share_a(w["M"]), Tprev=g.share_a(w["Tprev"]), F=g.share_a(w["F"]),
+            C=g.share_a(np.zeros((1 << h) * CW, dtype=np.uint64)), gamma=g.share_a(w["gamma"].reshape(-1)),
+            I=g.share_a(wi["I"].reshape(-1)),
+        )
+        st["tree"] = g.tree_import(g.share_a(wi["feat"]), None, g.share_a(wi["leaf"]), Hinf)
+        g.train_create(st["X"], st["Y"], N, d, H)
+        return g, st
+
+    def step(g, st, t):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.train_reset(st["X"], st["Y"])                                   # a0
+        torch.cuda.synchronize(); t1 = time.perf_counter()
+        g.train_import(h, st["M"], st["Tprev"], st["F"], st["C"], st["gamma"])
+        g.train_level(h)                                                  # a1-a7
+        torch.cuda.synchronize(); t2 = time.perf_counter()
+        tree = g.train_finish()                                           # a1, a2, a8 at level H
+        torch.cuda.synchronize(); t3 = time.perf_counter()
+        R = g.infer_batch(st["tree"], st["I"], NI, d)                     # b1-b5
+        torch.cuda.synchronize(); t4 = time.perf_counter()
+        tree.close()
+        if t is not None:
+            t["a0"] += t1 - t0; t["level"] += t2 - t1; t["finish"] += t3 - t2; t["infer"] += t4 - t3
+        return R
+
+    g, st = setup(False)
+    for _ in range(args.warmup):
+        step(g, st, None)
+    t = dict(a0=0.0, level=0.0, finish=0.0, infer=0.0)
+    torch.cuda.synchronize()
+    T0 = time.perf_counter()
+    for _ in range(args.steps):
+        R = step(g, st, t)
+    torch.cuda.synchronize()
+    total = time.perf_counter() - T0
+    k = args.steps
+    ms = {a: 1e3 * b / k for a, b in t.items()}
+    ncand = (1 << h) * d
+    value = ncand / (ms["level"] / 1e3)
+    # sanity: predictions equal plaintext traversal on a sample of instances
+    pred = g.rec(R)[:2000].astype(np.int64)
+    Tt = np.concatenate([wi["feat"], wi["leaf"]]).astype(np.int64)
+    idx = np.zeros(2000, dtype=np.int64)
+    for _ in range(Hinf):
+        idx = 2 * idx + 1 + wi["I"][np.arange(2000), Tt[idx]].astype(np.int64)
+    assert np.array_equal(pred, Tt[idx]), "inference result differs from plaintext traversal"
+    rounds, wire, _ = g.stats()
+    g.close(); del g, st
+    torch.cuda.empty_cache()
+
+    out = {
+        "metric": "secure split candidates scored/s per level", "value": value, "unit": "candidates/s",
+        "n_gpus": 1, "steps": k, "warmup": args.warmup, "ms_per_step": 1e3 * total / k,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "C5 scale: %d samples x %d binary columns, %d classes, one split-scoring level over %d "
+                               "nodes (%d candidates) + depth-%d inference on %d instances; 3 parties on 1 GPU, Z_2^64, tau=16"
+                               % (N, d, K, 1 << h, ncand, Hinf, NI),
+                   "value_from": "candidates / time of gt_train_level(h=%d)" % h},
+        "breakdown_ms": {"a0_products": ms["a0"], "a1_a7_level": ms["level"], "a1_a2_a8_label_level": ms["finish"],
+                         "b1_b5_inference": ms["infer"]},
+        "inference_instances_per_s": NI / (ms["infer"] / 1e3), "inference_depth": Hinf,
+    }
+
+    if not args.no_roofline:
+        # second timed region with a pair of HIP events around every kernel launch
+        g, st = setup(True)
+        step(g, st, None)
+        g.stats_reset()
+        for _ in range(k):
+            step(g, st, None)
+        prof = g.prof()
+        g.close(); del g, st
+        torch.cuda.empty_cache()
+        dom = max(prof, key=lambda c: prof[c][0])
+        # per step: equality tests of a1 (N x (2^(h-1) + d)), a2 (N x 2^h), label level (N x (2^h + d) + N x 2^(h+1)),
+        # inference (N_I x (2^Hinf - 1 + Hinf*d + 2^Hinf))
+        n_eq = N * ((1 << (h - 1)) + d + (1 << h)) + N * ((1 << h) + d + (1 << (h + 1))) \
+            + NI * ((1 << Hinf) - 1 + Hinf * d + (1 << Hinf))
+        eq_ms, eq_l = prof["eqgrid"]
+        cnt_ms, cnt_l = prof["count"]
+        macs = 3 * 2 * N * ((1 << h) * CW + (1 << (h + 1)) * K)         # ring MACs per step, all parties
+        kern = {
+            "eqgrid": {"bound": "hbm", "achieved": 200.0 * n_eq * k / (eq_ms / 1e3) / 1e9, "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "traffic": None,
+                       "note": "200 B of message traffic per equality test (3 parties, write + read), %d tests/step" % n_eq,
+                       "avg_launch_ms": eq_ms / max(eq_l, 1), "launches_per_step": eq_l // k,
+                       "eq_tests_per_s": n_eq * k / (eq_ms / 1e3)},
+            "count": {"bound": "alu", "achieved": 4.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": LANE_OPS_PEAK,
+                      "unit": "Tops/s", "traffic": None,
+                      "note": "ring MAC = 3 32-bit multiplies + 64-bit add, counted as 4 lane-ops; %d MACs/step" % macs,
+                      "avg_launch_ms": cnt_ms / max(cnt_l, 1), "launches_per_step": cnt_l // k},
+        }
+        for v in kern.values():
+            v["frac"] = v["achieved"] / v["peak"]
+        out["roofline"] = dict(kern[dom] if dom in kern else kern["eqgrid"], kernel=dom if dom in kern else "eqgrid")
+        out["kernel_classes_ms_per_step"] = {c: prof[c][0] / k for c in prof}
+        out["roofline_other"] = {c: v for c, v in kern.items() if c != out["roofline"]["kernel"]}
+
+    if args.cpu_samples > 0:
+        from oracle import Oracle, orc
+        Ns = min(args.cpu_samples, N)
+        ws = wl.c5_level(N=Ns, d=d, K=K, h=h)
+        o = Oracle(wl.PROTOCOL_SEED, tau=16, K=K)
+        xs, ys = o.share(ws["X"].reshape(-1)), o.share(ws["Y"].reshape(-1))
+        sto = [o.share(a) for a in (ws["M"], ws["Tprev"], ws["F"], np.zeros((1 << h) * CW, dtype=np.uint64), ws["gamma"].reshape(-1))]
+        o.train_create(xs, ys, Ns, d, H)
+        o.train_import(h, *sto)
+        c0 = time.perf_counter()
+        o.train_level(h)
+        cpu_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {
+            "value": ncand / (cpu_s * N / Ns), "unit": "candidates/s", "cores": orc.get_threads(), "kind": "oracle",
+            "sample": "the same level on %d of the %d samples took %.2f s on the host; scaled linearly in the sample count"
+                      % (Ns, N, cpu_s)}
+        o.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -64,11 +64,28 @@ typedef struct { uint64_t rounds; uint64_t wire_bytes[3][3]; double kernel_ms; }
 typedef struct {
     uint32_t tau, K;
     uint64_t seed[5][4];
-    uint32_t flags; /* reserved, 0 */
+    uint32_t flags; /* 0 or GT_FLAG_PROFILE */
     void *hip_stream;
 } gt_params;
 
+/* GT_FLAG_PROFILE: bracket every kernel launch with a pair of HIP events on the
+ * context's stream and accumulate time and launch count per kernel class. */
+#define GT_FLAG_PROFILE 1u
+enum {
+    GT_KC_SHARE = 0, /* share / reconstruct */
+    GT_KC_MULT = 1,  /* elementwise products with reshare */
+    GT_KC_EQGRID = 2,/* equality grid (+ conversion, + inner product) of the array access */
+    GT_KC_COUNT = 3, /* statistics contraction */
+    GT_KC_SMALL = 4, /* per-node protocols: division, arg-max, updates */
+    GT_KC_LOCAL = 5, /* copies, transposes, fills (no messages) */
+    GT_KC_N = 6
+};
+typedef struct { double ms[GT_KC_N]; uint64_t launches[GT_KC_N]; } gt_prof;
+
 int gt_ctx_create(gt_ctx **out, const gt_params *params);
+/* per-class kernel times since creation or the last gt_stats_reset (zeros without
+ * GT_FLAG_PROFILE); synchronises the stream */
+int gt_prof_get(gt_ctx *ctx, gt_prof *out);
 int gt_ctx_destroy(gt_ctx *ctx);
 /* accumulated counters since creation or the last reset; synchronises the stream */
 int gt_stats_get(gt_ctx *ctx, gt_stats *out);
@@ -101,6 +118,9 @@ int gt_div(gt_ctx *ctx, const gt_shares *S, const gt_shares *Q, size_t n, const 
  * labels.  N <= GT_MAX_N, 1 <= dcols, H <= GT_MAX_DEPTH. */
 int gt_train_create(gt_ctx *ctx, const gt_shares *X, const gt_shares *Y, size_t N,
                     uint32_t dcols, uint32_t max_depth, gt_train **out);
+/* Start a new job in an existing gt_train of the same N, dcols, depth: copy X, Y in,
+ * recompute the one-time products, reset M, T, F, C, gamma.  Allocates nothing. */
+int gt_train_reset(gt_ctx *ctx, gt_train *tr, const gt_shares *X, const gt_shares *Y);
 /* one level h (0 <= h < H, in order): data partition (h > 0), per-sample leaf
  * flags, class counts for every (node, candidate), Gini scores by exact
  * fixed-point division, first arg-max, updates of gamma, F, C, T. */

@@ -32,6 +32,12 @@ struct gt_ctx {
     gt_stats acc;
     hipEvent_t ev0, ev1;
     bool timing;
+    bool profile;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used;
+    std::vector<int> ev_cls;
+    gt_prof prof;
+    DSh ws[5];                // inference workspace, grown on demand, kept between calls
 };
 
 struct gt_tree {
@@ -128,6 +134,13 @@ struct Timed {                // times one API call with events on the context's
         if (hipEventSynchronize(c->ev1) != hipSuccess) return rc ? rc : GT_EHIP;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->acc.kernel_ms += ms;
+        for (size_t i = 0; i < c->ev_cls.size(); i++) {
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) == hipSuccess) {
+                c->prof.ms[c->ev_cls[i]] += t; c->prof.launches[c->ev_cls[i]] += 1;
+            }
+        }
+        c->ev_cls.clear(); c->ev_used = 0;
         if (rc == GT_OK && hipGetLastError() != hipSuccess) return GT_EHIP;
         return rc;
     }
@@ -135,7 +148,27 @@ struct Timed {                // times one API call with events on the context's
 };
 
 static KCommon kc(gt_ctx *c, u32 op) { KCommon k; k.keys = c->keys_d; k.wire = c->wire; k.op = op; return k; }
-#define LAUNCH_OK() do { if (hipGetLastError() != hipSuccess) return GT_EHIP; } while (0)
+
+// Every kernel goes through here.  With GT_FLAG_PROFILE the launch is bracketed by a
+// pair of events of its kernel class; the pairs are resolved when the API call ends.
+template <typename Kern, typename... Args>
+static int launch(gt_ctx *c, int cls, Kern kern, dim3 grid, dim3 block, Args... args)
+{
+    hipEvent_t e1 = nullptr;
+    if (c->profile) {
+        if (c->ev_used + 2 > c->ev_pool.size())
+            for (int i = 0; i < 64; i++) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) return GT_EHIP; c->ev_pool.push_back(e); }
+        hipEvent_t e0 = c->ev_pool[c->ev_used++];
+        e1 = c->ev_pool[c->ev_used++];
+        c->ev_cls.push_back(cls);
+        (void)hipEventRecord(e0, c->stream);
+    }
+    hipLaunchKernelGGL(kern, grid, block, 0, c->stream, args...);
+    if (e1) (void)hipEventRecord(e1, c->stream);
+    return hipGetLastError() == hipSuccess ? GT_OK : GT_EHIP;
+}
+static dim3 g1(u64 n) { return dim3(blocks_for(n, 256)); }   // plain elementwise kernels
+static const dim3 B256(256);
 
 // ---------------------------------------------------------------------------------
 extern "C" const char *gt_strerror(int code)
@@ -156,7 +189,9 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (prm->K < 1 || prm->K > GT_MAX_K || prm->tau < 1 || prm->tau > GT_MAX_TAU) return GT_EINVAL;
     gt_ctx *c = new (std::nothrow) gt_ctx();
     if (!c) return GT_ENOMEM;
-    memset(c, 0, sizeof *c);
+    c->op = 0; c->timing = false; c->ev_used = 0; c->keys_d = nullptr; c->wire = nullptr;
+    memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
+    c->profile = (prm->flags & GT_FLAG_PROFILE) != 0;
     c->tau = prm->tau; c->K = prm->K; c->stream = (hipStream_t)prm->hip_stream;
     u32 keys[5][8];
     for (int k = 0; k < 5; k++)
@@ -176,6 +211,8 @@ extern "C" int gt_ctx_destroy(gt_ctx *c)
     if (!c) return GT_EINVAL;
     (void)hipStreamSynchronize(c->stream);
     (void)hipEventDestroy(c->ev0); (void)hipEventDestroy(c->ev1);
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    for (DSh &w : c->ws) dsh_free(w);
     (void)hipFree(c->keys_d); (void)hipFree(c->wire);
     delete c;
     return GT_OK;
@@ -188,7 +225,19 @@ extern "C" int gt_stats_get(gt_ctx *c, gt_stats *out)
     *out = c->acc;
     return GT_OK;
 }
-extern "C" int gt_stats_reset(gt_ctx *c) { if (!c) return GT_EINVAL; memset(&c->acc, 0, sizeof c->acc); return GT_OK; }
+extern "C" int gt_stats_reset(gt_ctx *c)
+{
+    if (!c) return GT_EINVAL;
+    memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
+    return GT_OK;
+}
+extern "C" int gt_prof_get(gt_ctx *c, gt_prof *out)
+{
+    if (!c || !out) return GT_EINVAL;
+    HIPCHK(hipStreamSynchronize(c->stream));
+    *out = c->prof;
+    return GT_OK;
+}
 extern "C" uint32_t gt_op_counter(const gt_ctx *c) { return c ? c->op : 0; }
 
 // ---------------------------------------------------------------------------------
@@ -197,24 +246,24 @@ extern "C" int gt_share_a(gt_ctx *c, const uint64_t *plain, size_t n, const gt_s
     if (!c || !shares_ok(out, n) || (n && !plain)) return GT_EINVAL;
     Timed T(c);
     u32 op = c->op++;
-    if (n) { hipLaunchKernelGGL(k_share, dim3(blocks_for((n + 7) / 8, 256)), dim3(256), 0, c->stream, c->keys_d, op, plain, (u64)n, to_p6(out)); LAUNCH_OK(); }
-    return T.finish(GT_OK);
+    int rc = GT_OK;
+    if (n) rc = launch(c, GT_KC_SHARE, k_share, g1((n + 7) / 8), B256, (const u32 *)c->keys_d, op, plain, (u64)n, to_p6(out));
+    return T.finish(rc);
 }
 
 extern "C" int gt_reconstruct_a(gt_ctx *c, const gt_shares *in, uint64_t *plain, size_t n)
 {
     if (!c || !shares_ok(in, n) || (n && !plain)) return GT_EINVAL;
     Timed T(c);
-    if (n) { hipLaunchKernelGGL(k_reconstruct, dim3(blocks_for(n, 256)), dim3(256), 0, c->stream, to_p6(in), (u64)n, plain); LAUNCH_OK(); }
-    return T.finish(GT_OK);
+    int rc = GT_OK;
+    if (n) rc = launch(c, GT_KC_SHARE, k_reconstruct, g1(n), B256, to_p6(in), (u64)n, plain);
+    return T.finish(rc);
 }
 
 static int copy6(gt_ctx *c, P6 dst, u64 doff, P6 src, u64 soff, u64 sstride, u64 n)
 {
     if (!n) return GT_OK;
-    hipLaunchKernelGGL(k_copy, dim3(blocks_for(n, 256)), dim3(256), 0, c->stream, dst, doff, src, soff, sstride, n);
-    LAUNCH_OK();
-    return GT_OK;
+    return launch(c, GT_KC_LOCAL, k_copy, g1(n), B256, dst, doff, src, soff, sstride, n);
 }
 
 // ---- building blocks ---------------------------------------------------------------
@@ -223,10 +272,9 @@ static int do_mult(gt_ctx *c, int mode, MultArgs a)
     a.c = kc(c, c->op++);
     if (a.n) {
         dim3 g(tiles8(a.n));
-        if (mode == 0) hipLaunchKernelGGL(k_mult<0>, g, GT_BLOCK, 0, c->stream, a);
-        else if (mode == 1) hipLaunchKernelGGL(k_mult<1>, g, GT_BLOCK, 0, c->stream, a);
-        else hipLaunchKernelGGL(k_mult<2>, g, GT_BLOCK, 0, c->stream, a);
-        LAUNCH_OK();
+        if (mode == 0) return launch(c, GT_KC_MULT, k_mult<0>, g, GT_BLOCK, a);
+        if (mode == 1) return launch(c, GT_KC_MULT, k_mult<1>, g, GT_BLOCK, a);
+        return launch(c, GT_KC_MULT, k_mult<2>, g, GT_BLOCK, a);
     }
     return GT_OK;
 }
@@ -244,11 +292,8 @@ extern "C" int gt_mult(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t
 static int do_eq(gt_ctx *c, bool bool_out, P6 x, u64 xoff, const u64 *ypub, u64 ysub, P6 z, u64 n)
 {
     EqArgs a{}; a.c = kc(c, c->op++); a.x = x; a.xoff = xoff; a.ypub = ypub; a.ysub = ysub; a.z = z; a.n = n;
-    if (n) {
-        if (bool_out) hipLaunchKernelGGL(k_eq<true>, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a);
-        else hipLaunchKernelGGL(k_eq<false>, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a);
-        LAUNCH_OK();
-    }
+    if (n) GTCHK(bool_out ? launch(c, GT_KC_SMALL, k_eq<true>, dim3(tiles(n)), GT_BLOCK, a)
+                          : launch(c, GT_KC_SMALL, k_eq<false>, dim3(tiles(n)), GT_BLOCK, a));
     acct_eq(c, n);
     if (!bool_out) acct_b2a(c, n);
     return GT_OK;
@@ -266,9 +311,10 @@ extern "C" int gt_ge_a(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t
     if (!c || !shares_ok(x, n) || !shares_ok(y, n) || !shares_ok(z, n)) return GT_EINVAL;
     Timed T(c);
     GeArgs a{}; a.c = kc(c, c->op++); a.x = to_p6(x); a.y = to_p6(y); a.z = to_p6(z); a.n = n;
-    if (n) { hipLaunchKernelGGL(k_ge, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a); LAUNCH_OK(); }
+    int rc = GT_OK;
+    if (n) rc = launch(c, GT_KC_SMALL, k_ge, dim3(tiles(n)), GT_BLOCK, a);
     acct_ge(c, n); acct_b2a(c, n);
-    return T.finish(GT_OK);
+    return T.finish(rc);
 }
 
 // the equality grid with its accounting
@@ -278,12 +324,13 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
     const u64 nel = (u64)a.w * a.N;
     if (a.N && a.w) {
         dim3 g(tiles8(a.N8));
-        if (mode == GM_STORE && has_g) hipLaunchKernelGGL((k_eqgrid<GM_STORE, true, 1>), g, GT_BLOCK, 0, c->stream, a);
-        else if (mode == GM_STORE) hipLaunchKernelGGL((k_eqgrid<GM_STORE, false, 1>), g, GT_BLOCK, 0, c->stream, a);
-        else if (mode == GM_COMMON && ndot == 2) hipLaunchKernelGGL((k_eqgrid<GM_COMMON, false, 2>), g, GT_BLOCK, 0, c->stream, a);
-        else if (mode == GM_COMMON) hipLaunchKernelGGL((k_eqgrid<GM_COMMON, false, 1>), g, GT_BLOCK, 0, c->stream, a);
-        else hipLaunchKernelGGL((k_eqgrid<GM_ROWS, false, 1>), g, GT_BLOCK, 0, c->stream, a);
-        LAUNCH_OK();
+        int rc;
+        if (mode == GM_STORE && has_g) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, true, 1>, g, GT_BLOCK, a);
+        else if (mode == GM_STORE) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, false, 1>, g, GT_BLOCK, a);
+        else if (mode == GM_COMMON && ndot == 2) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_COMMON, false, 2>, g, GT_BLOCK, a);
+        else if (mode == GM_COMMON) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_COMMON, false, 1>, g, GT_BLOCK, a);
+        else rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_ROWS, false, 1>, g, GT_BLOCK, a);
+        GTCHK(rc);
     }
     acct_eq(c, nel);
     if (has_g) acct_and1(c, nel);
@@ -305,7 +352,7 @@ static int div_steps(gt_ctx *c, P6 S, P6 Q, P6 rem, P6 quo, u64 n)
 {
     for (u32 t = 0; t <= c->tau; t++) {
         DivArgs a{}; a.c = kc(c, c->op++); a.S = S; a.Q = Q; a.r = rem; a.quo = quo; a.n = n; a.first = t == 0;
-        if (n) { hipLaunchKernelGGL(k_div_step, dim3(tiles(n)), GT_BLOCK, 0, c->stream, a); LAUNCH_OK(); }
+        if (n) GTCHK(launch(c, GT_KC_SMALL, k_div_step, dim3(tiles(n)), GT_BLOCK, a));
         acct_ge(c, n); acct_b2a(c, n); acct_reshare(c, n, 1);
     }
     return GT_OK;
@@ -336,6 +383,30 @@ static void train_free(gt_train *t)
 
 extern "C" int gt_train_destroy(gt_train *t) { if (!t) return GT_EINVAL; (void)hipDeviceSynchronize(); train_free(t); return GT_OK; }
 
+// copy the data in, compute the one-time products, set the initial state (no allocation)
+static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shares *Y)
+{
+    const u32 d = t->d, K = t->K;
+    const size_t N = t->N, N8 = t->N8, nmax = (size_t)1 << t->H, nodes = ((size_t)2 << t->H) - 1;
+    // sample-contiguous copies of X and Y (Y goes behind the d*K product columns)
+    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * d), B256, t->XT.v, to_p6(X), (u64)N, (u64)N8, d));
+    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * K), B256, off6(t->BT.v, (size_t)d * K * N8), to_p6(Y), (u64)N, (u64)N8, K));
+    // one-time products X[i][k] * Y[i][c]
+    MultArgs a{}; a.x = t->XT.v; a.y = off6(t->BT.v, (size_t)d * K * N8); a.z = t->BT.v;
+    a.n = (u64)d * K * N8; a.N = N; a.N8 = N8; a.K = K;
+    GTCHK(do_mult(c, 1, a));
+    acct_reshare(c, (u64)N * d * K, 1);
+    // M = 0, T = 0, the root is a leaf with empty statistics, no candidate used yet
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(N), B256, t->M.v, (u64)0, (u64)N, (u64)0));
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(nodes), B256, t->T.v, (u64)0, (u64)nodes, (u64)0));
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(nodes), B256, t->F.v, (u64)0, (u64)nodes, (u64)0));
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(nmax * t->CW), B256, t->C.v, (u64)0, (u64)(nmax * t->CW), (u64)0));
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, dim3(1), B256, t->F.v, (u64)0, (u64)1, (u64)1));
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(d), B256, t->gamma.v, (u64)0, (u64)d, (u64)1));
+    t->level = 0; t->last = 0; t->finished = false;
+    return GT_OK;
+}
+
 extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y, size_t N, uint32_t d,
                                uint32_t H, gt_train **out)
 {
@@ -362,22 +433,18 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     for (auto &pl : plan) { rc = dsh_alloc(*pl.v, pl.n, s); if (rc != GT_OK) break; }
     if (rc == GT_OK && hipMalloc(&t->Zacc, 3 * nmax * CW * 8) != hipSuccess) rc = GT_ENOMEM;
     if (rc != GT_OK) { (void)hipStreamSynchronize(s); train_free(t); return T.finish(rc); }
-    // sample-contiguous copies of X and Y (Y goes behind the d*K product columns)
-    hipLaunchKernelGGL(k_transpose, dim3(blocks_for(N * d, 256)), dim3(256), 0, s, t->XT.v, to_p6(X), (u64)N, (u64)N8, d);
-    hipLaunchKernelGGL(k_transpose, dim3(blocks_for(N * K, 256)), dim3(256), 0, s, off6(t->BT.v, (size_t)d * K * N8), to_p6(Y), (u64)N, (u64)N8, K);
-    // one-time products X[i][k] * Y[i][c]
-    MultArgs a{}; a.x = t->XT.v; a.y = off6(t->BT.v, (size_t)d * K * N8); a.z = t->BT.v;
-    a.n = (u64)d * K * N8; a.N = N; a.N8 = N8; a.K = K;
-    rc = do_mult(c, 1, a);
-    acct_reshare(c, (u64)N * d * K, 1);
-    // M = 0, the root is a leaf, no candidate used yet
-    hipLaunchKernelGGL(k_fill_const, dim3(1), dim3(256), 0, s, t->F.v, (u64)0, (u64)1, (u64)1);
-    hipLaunchKernelGGL(k_fill_const, dim3(blocks_for(d, 256)), dim3(256), 0, s, t->gamma.v, (u64)0, (u64)d, (u64)1);
-    if (rc == GT_OK && hipGetLastError() != hipSuccess) rc = GT_EHIP;
+    rc = train_start(c, t, X, Y);
     rc = T.finish(rc);
     if (rc != GT_OK) { train_free(t); return rc; }
     *out = t;
     return GT_OK;
+}
+
+extern "C" int gt_train_reset(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shares *Y)
+{
+    if (!c || !t || !shares_ok(X, t->N * t->d) || !shares_ok(Y, t->N * t->K) || t->K != c->K) return GT_EINVAL;
+    Timed T(c);
+    return T.finish(train_start(c, t, X, Y));
 }
 
 // data partition: Tval = T_level(h-1)[M - base], Dval = X[i][Tval], M <- 2M + Dval + 1
@@ -412,11 +479,9 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     a.Zacc = t->Zacc; a.kchunk = 2048;
     a.nchunk = (u32)((t->N8 + a.kchunk - 1) / a.kchunk);
     dim3 g((ncol + CT_T - 1) / CT_T, (unsigned)((nh + CT_T - 1) / CT_T), 3 * a.nchunk);
-    hipLaunchKernelGGL(k_count, g, dim3(256), 0, c->stream, a);
-    LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_COUNT, k_count, g, B256, a));
     CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
-    hipLaunchKernelGGL(k_count_fin, dim3(tiles(f.n)), GT_BLOCK, 0, c->stream, f);
-    LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_SMALL, k_count_fin, dim3(tiles(f.n)), GT_BLOCK, f));
     acct_reshare(c, nh * ncol, 1);
     return GT_OK;
 }
@@ -424,7 +489,7 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
 static int select_max(gt_ctx *c, SelArgs a)
 {
     a.c = kc(c, c->op++);
-    if (a.n) { hipLaunchKernelGGL(k_select_max, dim3(tiles(a.n)), GT_BLOCK, 0, c->stream, a); LAUNCH_OK(); }
+    if (a.n) GTCHK(launch(c, GT_KC_SMALL, k_select_max, dim3(tiles(a.n)), GT_BLOCK, a));
     acct_ge(c, a.n); acct_b2a(c, a.n); acct_reshare(c, a.n, 2);
     return GT_OK;
 }
@@ -433,16 +498,16 @@ static int heuristic(gt_ctx *c, gt_train *t, u32 h)
 {
     const u64 nh = (u64)1 << h, d = t->d, nq = nh * d * 2, ns = nh * d;
     PrepArgs pa{}; pa.c = kc(c, c->op++); pa.C = t->C.v; pa.S = t->S.v; pa.Q = t->Q.v; pa.n = nq; pa.d = t->d; pa.K = t->K; pa.CW = t->CW;
-    hipLaunchKernelGGL(k_score_prep, dim3(tiles(nq)), GT_BLOCK, 0, c->stream, pa); LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_SMALL, k_score_prep, dim3(tiles(nq)), GT_BLOCK, pa));
     acct_reshare(c, nq, 2);
     // empty branch: make the divisor 1
     DSh &z = t->rem;    // scratch for the 0/1 sharing of [Q == 0]
     GTCHK(do_eq(c, false, t->Q.v, 0, nullptr, 0, z.v, nq));
-    hipLaunchKernelGGL(k_add_inplace, dim3(blocks_for(nq, 256)), dim3(256), 0, c->stream, t->Q.v, z.v, nq); LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_LOCAL, k_add_inplace, g1(nq), B256, t->Q.v, z.v, nq));
     GTCHK(div_steps(c, t->S.v, t->Q.v, t->rem.v, t->quo.v, nq));
-    hipLaunchKernelGGL(k_iota, dim3(blocks_for(nh * t->P2, 256)), dim3(256), 0, c->stream, t->idx[0].v, t->val[0].v, (u32)nh, t->P2, t->d); LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_LOCAL, k_iota, g1(nh * t->P2), B256, t->idx[0].v, t->val[0].v, (u32)nh, t->P2, t->d));
     MaskArgs ma{}; ma.c = kc(c, c->op++); ma.quo = t->quo.v; ma.gamma = t->gamma.v; ma.score = t->Slast.v; ma.val = t->val[0].v; ma.n = ns; ma.d = t->d; ma.P2 = t->P2;
-    hipLaunchKernelGGL(k_mask_score, dim3(tiles(ns)), GT_BLOCK, 0, c->stream, ma); LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_SMALL, k_mask_score, dim3(tiles(ns)), GT_BLOCK, ma));
     acct_reshare(c, ns, 1);
     int cur = 0;
     for (u64 len = t->P2; len > 1; len /= 2) {
@@ -458,11 +523,11 @@ static int update(gt_ctx *c, gt_train *t, u32 h)
 {
     const u64 nh = (u64)1 << h, base = nh - 1, d = t->d, CW = t->CW;
     GammaArgs ga{}; ga.c = kc(c, c->op++); ga.SD = t->SD.v; ga.gamma = t->gamma.v; ga.n = nh * d; ga.d = t->d;
-    hipLaunchKernelGGL(k_gamma, dim3(tiles(ga.n)), GT_BLOCK, 0, c->stream, ga); LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_SMALL, k_gamma, dim3(tiles(ga.n)), GT_BLOCK, ga));
     acct_eq(c, nh * d); acct_b2a(c, nh * d); acct_reshare(c, nh * d, 1);
     SplitArgs sa{}; sa.c = kc(c, c->op++); sa.C = t->C.v; sa.isLeaf = t->isLeaf.v; sa.F = t->F.v; sa.split = t->split.v;
     sa.n = nh; sa.base = base; sa.K = t->K; sa.CW = t->CW; sa.dK = (u64)t->d * t->K;
-    hipLaunchKernelGGL(k_split, dim3(tiles(nh)), GT_BLOCK, 0, c->stream, sa); LAUNCH_OK();
+    GTCHK(launch(c, GT_KC_SMALL, k_split, dim3(tiles(nh)), GT_BLOCK, sa));
     acct_reshare(c, nh, 1); acct_eq(c, nh); acct_and1(c, nh); acct_b2a(c, nh); acct_reshare(c, nh, 1);
     // keep this level's statistics and flags for export; T takes the split decisions
     GTCHK(copy6(c, t->Clast.v, 0, t->C.v, 0, 1, nh * CW));
@@ -475,7 +540,7 @@ static int update(gt_ctx *c, gt_train *t, u32 h)
     acct_reshare(c, nh * CW, 1);
     std::swap(t->C, t->Cn);
     if (h + 1 <= t->H && 2 * nh <= ((u64)1 << t->H)) {
-        hipLaunchKernelGGL(k_dup_rows, dim3(blocks_for(nh * d, 256)), dim3(256), 0, c->stream, t->Gn.v, t->gamma.v, nh, d); LAUNCH_OK();
+        GTCHK(launch(c, GT_KC_LOCAL, k_dup_rows, g1(nh * d), B256, t->Gn.v, t->gamma.v, nh, d));
         std::swap(t->gamma, t->Gn);
     }
     return GT_OK;
@@ -523,7 +588,7 @@ extern "C" int gt_train_finish(gt_ctx *c, gt_train *t, gt_tree **out)
     if (rc == GT_OK) rc = count(c, t, H, true);
     // label = first maximum of the class totals
     if (rc == GT_OK) rc = copy6(c, t->best.v, 0, t->C.v, dK, t->CW, nh);
-    if (rc == GT_OK) { hipLaunchKernelGGL(k_fill_const, dim3(blocks_for(nh, 256)), dim3(256), 0, c->stream, t->lab.v, (u64)0, nh, (u64)0); if (hipGetLastError() != hipSuccess) rc = GT_EHIP; }
+    if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_fill_const, g1(nh), B256, t->lab.v, (u64)0, nh, (u64)0);
     for (u32 cl = 1; cl < t->K && rc == GT_OK; cl++) {
         SelArgs sa{}; sa.vin = t->best.v; sa.iin = t->lab.v; sa.vout = t->best.v; sa.iout = t->lab.v; sa.C = t->C.v;
         sa.n = nh; sa.CW = t->CW; sa.coff = dK + cl; sa.cidx = cl; sa.mode = 1;
@@ -580,8 +645,7 @@ extern "C" int gt_train_export(gt_ctx *c, const gt_train *t, int what, const gt_
     if (src) rc = copy6(c, to_p6(out), 0, src->v, 0, 1, n);
     else {
         const u32 nh = 1u << t->last;
-        hipLaunchKernelGGL(k_c_paper, dim3(blocks_for(n, 256)), dim3(256), 0, c->stream, t->Clast.v, to_p6(out), nh, t->d, t->K, t->CW);
-        if (hipGetLastError() != hipSuccess) rc = GT_EHIP;
+        rc = launch(c, GT_KC_LOCAL, k_c_paper, g1(n), B256, t->Clast.v, to_p6(out), nh, t->d, t->K, t->CW);
     }
     return T.finish(rc);
 }
@@ -649,16 +713,14 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
     Timed T(c);
     const size_t N8 = pad8(NI);
     const u32 H = tr->H;
-    DSh IT, tidx, f, th, x;
-    int rc = dsh_alloc(IT, (size_t)d * N8, c->stream);
-    if (rc == GT_OK) rc = dsh_alloc(tidx, NI, c->stream);
-    if (rc == GT_OK) rc = dsh_alloc(f, NI, c->stream);
-    if (rc == GT_OK && tr->has_thr) rc = dsh_alloc(th, NI, c->stream);
-    if (rc == GT_OK && tr->has_thr) rc = dsh_alloc(x, NI, c->stream);
-    if (rc == GT_OK) {
-        hipLaunchKernelGGL(k_transpose, dim3(blocks_for(NI * d, 256)), dim3(256), 0, c->stream, IT.v, to_p6(I), (u64)NI, (u64)N8, d);
-        if (hipGetLastError() != hipSuccess) rc = GT_EHIP;
-    }
+    // workspace: transposed instances, node index, fetched id / threshold / value
+    const size_t need[5] = { (size_t)d * N8, NI, NI, tr->has_thr ? NI : 0, tr->has_thr ? NI : 0 };
+    int rc = GT_OK;
+    for (int i = 0; i < 5 && rc == GT_OK; i++)
+        if (c->ws[i].n < need[i]) { (void)hipStreamSynchronize(c->stream); dsh_free(c->ws[i]); rc = dsh_alloc(c->ws[i], need[i], c->stream); }
+    DSh &IT = c->ws[0], &tidx = c->ws[1], &f = c->ws[2], &th = c->ws[3], &x = c->ws[4];
+    if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_fill_const, g1(NI), B256, tidx.v, (u64)0, (u64)NI, (u64)0);
+    if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_transpose, g1(NI * d), B256, IT.v, to_p6(I), (u64)NI, (u64)N8, d);
     for (u32 n = 0; n < H && rc == GT_OK; n++) {
         const u64 w = (u64)1 << n, base = w - 1;
         GridArgs a{}; a.u = tidx.v; a.base = base; a.w = (u32)w; a.N = NI; a.N8 = N8;
@@ -672,8 +734,7 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
         if (rc != GT_OK) break;
         if (tr->has_thr) {
             CmpArgs ca{}; ca.c = kc(c, c->op++); ca.th = th.v; ca.x = x.v; ca.tidx = tidx.v; ca.n = NI;
-            hipLaunchKernelGGL(k_cmp_step, dim3(tiles(NI)), GT_BLOCK, 0, c->stream, ca);
-            if (hipGetLastError() != hipSuccess) rc = GT_EHIP;
+            rc = launch(c, GT_KC_SMALL, k_cmp_step, dim3(tiles(NI)), GT_BLOCK, ca);
             acct_ge(c, NI); acct_b2a(c, NI);
         }
     }
@@ -683,7 +744,5 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
         a.W1 = tr->leaf.v; a.w1off = 0; a.out = to_p6(R); a.epi = 0;
         rc = do_grid(c, GM_COMMON, false, 1, a);
     }
-    rc = T.finish(rc);
-    dsh_free(IT); dsh_free(tidx); dsh_free(f); dsh_free(th); dsh_free(x);
-    return rc;
+    return T.finish(rc);
 }

@@ -36,6 +36,14 @@ class _Stats(C.Structure):
     _fields_ = [("rounds", C.c_uint64), ("wire_bytes", (C.c_uint64 * 3) * 3), ("kernel_ms", C.c_double)]
 
 
+GT_FLAG_PROFILE = 1
+KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local")
+
+
+class _Prof(C.Structure):
+    _fields_ = [("ms", C.c_double * 6), ("launches", C.c_uint64 * 6)]
+
+
 class _Params(C.Structure):
     _fields_ = [("tau", C.c_uint32), ("K", C.c_uint32), ("seed", (C.c_uint64 * 4) * 5),
                 ("flags", C.c_uint32), ("hip_stream", C.c_void_p)]
@@ -66,6 +74,8 @@ def load():
         "gt_ctx_destroy": (i, [vp]),
         "gt_stats_get": (i, [vp, C.POINTER(_Stats)]),
         "gt_stats_reset": (i, [vp]),
+        "gt_prof_get": (i, [vp, C.POINTER(_Prof)]),
+        "gt_train_reset": (i, [vp, vp, S, S]),
         "gt_op_counter": (u32, [vp]),
         "gt_strerror": (C.c_char_p, [i]),
         "gt_share_a": (i, [vp, vp, sz, S]),
@@ -145,14 +155,14 @@ def _ref(s):
 class GTree:
     """One protocol context (keys, operation counter, message buffers, stream)."""
 
-    def __init__(self, seed, tau=16, K=2, device="cuda:0", stream=None):
+    def __init__(self, seed, tau=16, K=2, device="cuda:0", stream=None, profile=False):
         import torch
         self.L = load()
         self.torch = torch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         prm = _Params()
-        prm.tau, prm.K, prm.flags = int(tau), int(K), 0
+        prm.tau, prm.K, prm.flags = int(tau), int(K), GT_FLAG_PROFILE if profile else 0
         sd = np.asarray(seed, dtype=np.uint64).reshape(5, 4)
         for a in range(5):
             for b in range(4):
@@ -194,6 +204,12 @@ class GTree:
         _chk(self.L.gt_stats_get(self.ctx, C.byref(st)), "gt_stats_get")
         wire = np.array([[st.wire_bytes[a][b] for b in range(3)] for a in range(3)], dtype=np.uint64)
         return int(st.rounds), wire, float(st.kernel_ms)
+
+    def prof(self):
+        """{class name: (milliseconds, launches)} since the last stats_reset (profile=True)."""
+        pr = _Prof()
+        _chk(self.L.gt_prof_get(self.ctx, C.byref(pr)), "gt_prof_get")
+        return {KC_NAMES[k]: (float(pr.ms[k]), int(pr.launches[k])) for k in range(6)}
 
     def stats_reset(self):
         _chk(self.L.gt_stats_reset(self.ctx), "gt_stats_reset")
@@ -253,6 +269,9 @@ class GTree:
         h = C.c_void_p()
         _chk(self.L.gt_train_create(self.ctx, _ref(X), _ref(Y), N, d, H, C.byref(h)), "gt_train_create")
         self._train, self._tshape = h, (N, d, H)
+
+    def train_reset(self, X, Y):
+        _chk(self.L.gt_train_reset(self.ctx, self._train, _ref(X), _ref(Y)), "gt_train_reset")
 
     def train_level(self, h):
         _chk(self.L.gt_train_level(self.ctx, self._train, h), "gt_train_level")
