@@ -28,7 +28,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--samples", type=int, default=1000000, help="training samples (C5: 10^6)")
     ap.add_argument("--instances", type=int, default=1000000, help="inference batch (C5: 10^6)")
-    ap.add_argument("--cpu-samples", type=int, default=40000, help="oracle sample for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-samples", type=int, default=250000, help="oracle sample for cpu_baseline (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
