@@ -228,52 +228,75 @@ __device__ __forceinline__ void eq_round8(Wire &W, Sh (&t)[8], const u64 (&A)[8]
     for (int s = 0; s < 8; s++) { t[s].o = z[s]; t[s].n = r[s]; }
 }
 
+// The dealer's block of an element yields the components of all three parties, so
+// the 512 blocks of a step are computed once per workgroup, spread over its 192
+// lanes (the dealer is a role of its own, not one of the parties), and left in LDS;
+// each party's wavefront then reads only the words its two components derive from.
+#define GT_TILE_EL (8 * GT_LANES)
+
+// party p's two components of (a, b, c) where c is the dealer's correction term
+#define GT_PICK_O(p, a, b, c) ((p) == 0 ? (a) : ((p) == 1 ? (b) : (c)))
+#define GT_PICK_N(p, a, b, c) ((p) == 0 ? (b) : ((p) == 1 ? (c) : (a)))
+
 template <int MODE, bool HAS_G, int NDOT>
-__global__ __launch_bounds__(192) void k_eqgrid(GridArgs a)
+__global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 {
-    const int p = threadIdx.y, lane = threadIdx.x;
+    __shared__ u64 s_D[8][GT_TILE_EL];         // raw dealer words D0..D7 per element
+    const int p = threadIdx.y, lane = threadIdx.x, tid = p * GT_LANES + lane;
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u32 op = a.c.op;
     const u64 ngrp = a.N8 / 8;
     const Sh one = pub(p, 1);
+    const u64 mo = p == 0 ? ~0ull : 0ull, mn_ = p == 2 ? ~0ull : 0ull;   // who holds component 0
     for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
         const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
         const bool act = grp < ngrp;
-        Sh v[8];
         u64 acc[8], acc2[8];
 #pragma unroll
-        for (int s = 0; s < 8; s++) {
-            v[s].o = 0; v[s].n = 0; acc[s] = 0; acc2[s] = 0;
-            if (act && i0 + s < a.N) v[s] = ld(a.u, p, i0 + s) - pub(p, a.base);
-        }
+        for (int s = 0; s < 8; s++) { acc[s] = 0; acc2[s] = 0; }
         for (u32 k = 0; k < a.w; k++) {
             const u64 e0 = (u64)k * a.N8 + i0;
+#pragma unroll 1
+            for (int j = 0; j < 3; j++) {
+                const int el = j * 192 + tid;
+                if (el < GT_TILE_EL) {
+                    const u64 e = (u64)k * a.N8 + (tile * GT_LANES + (el & (GT_LANES - 1))) * 8 + (el >> 6);
+                    u64 D[8];
+                    chacha8(K.dlr, e, op, 0, D);
+#pragma unroll
+                    for (int i = 0; i < 8; i++) s_D[i][el] = D[i];
+                }
+            }
+            __syncthreads();
+            u64 snd[8], rcv[8], mn[8];
+            const Sh sub = pub(p, a.base + k);
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const int el = s * GT_LANES + lane;
+                Sh v = { 0, 0 };
+                if (act && i0 + s < a.N) v = ld(a.u, p, i0 + s) - sub;
+                const u64 d0 = s_D[0][el], d1 = s_D[1][el], d2 = s_D[2][el], d3 = d0 - d1 - d2;
+                snd[s] = v.o + GT_PICK_O(p, d1, d2, d3);
+                mn[s] = v.n + GT_PICK_N(p, d1, d2, d3);
+            }
+            W.open<8>(snd, rcv);                       // masked values, 64 bits each
+            Sh t[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const int el = s * GT_LANES + lane;
+                const u64 nc = ~(snd[s] + mn[s] + rcv[s]);
+                const u64 d3 = s_D[3][el], d4 = s_D[4][el], d5 = s_D[0][el] ^ d3 ^ d4;
+                t[s].o = GT_PICK_O(p, d3, d4, d5) ^ (nc & mo);
+                t[s].n = GT_PICK_N(p, d3, d4, d5) ^ (nc & mn_);
+            }
             u64 A[8];
+            chacha8(K.own, e0 >> 3, op, 1, A);
             {
                 u64 An[8];
-                chacha8(K.own, e0 >> 3, op, 1, A);
                 chacha8(K.nxt, e0 >> 3, op, 1, An);
 #pragma unroll
                 for (int s = 0; s < 8; s++) A[s] ^= An[s];
-            }
-            Sh t[8], bA[8];
-            u32 bBo = 0, bBn = 0;
-            u64 snd[8], rcv[8], mn[8];
-#pragma unroll
-            for (int s = 0; s < 8; s++) {
-                const Dealer D = dealer_of(K, p, op, e0 + s);
-                const Sh m = v[s] - pub(p, k) + D.rA;
-                snd[s] = m.o; mn[s] = m.n;
-                t[s] = D.rho; bA[s] = D.bA;
-                bBo |= D.bBo << s; bBn |= D.bBn << s;
-            }
-            W.open<8>(snd, rcv);                       // masked values, 64 bits each
-#pragma unroll
-            for (int s = 0; s < 8; s++) {
-                const u64 c = snd[s] + mn[s] + rcv[s];
-                if (p == 0) t[s].o ^= ~c;
-                if (p == 2) t[s].n ^= ~c;
             }
             eq_round8<32>(W, t, A, 0);                 // six AND rounds, 63 bits
             eq_round8<16>(W, t, A, 32);
@@ -296,8 +319,12 @@ __global__ __launch_bounds__(192) void k_eqgrid(GridArgs a)
             {                                          // bit -> arithmetic: open s xor beta
                 u32 fo = 0, fn = 0;
 #pragma unroll
-                for (int s = 0; s < 8; s++) { fo |= ((u32)t[s].o & 1) << s; fn |= ((u32)t[s].n & 1) << s; }
-                fo ^= bBo; fn ^= bBn;
+                for (int s = 0; s < 8; s++) {
+                    const u64 d5 = s_D[5][s * GT_LANES + lane];
+                    const u32 b0 = (u32)(d5 >> 1) & 1, b1 = (u32)(d5 >> 2) & 1, b2 = ((u32)d5 ^ b0 ^ b1) & 1;
+                    fo |= (((u32)t[s].o ^ GT_PICK_O(p, b0, b1, b2)) & 1) << s;
+                    fn |= (((u32)t[s].n ^ GT_PICK_N(p, b0, b1, b2)) & 1) << s;
+                }
                 f = fo ^ fn ^ (u32)W.open1((u64)fo);
             }
             Sh Wk = { 0, 0 }, Wk2 = { 0, 0 };
@@ -307,14 +334,18 @@ __global__ __launch_bounds__(192) void k_eqgrid(GridArgs a)
             }
 #pragma unroll
             for (int s = 0; s < 8; s++) {
+                const int el = s * GT_LANES + lane;
+                const u64 d6 = s_D[6][el], d7 = s_D[7][el], d8 = (s_D[5][el] & 1) - d6 - d7;
+                const Sh bA = { GT_PICK_O(p, d6, d7, d8), GT_PICK_N(p, d6, d7, d8) };
                 Sh E;
-                E.o = ((f >> s) & 1) ? one.o - bA[s].o : bA[s].o;
-                E.n = ((f >> s) & 1) ? one.n - bA[s].n : bA[s].n;
+                E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
+                E.n = ((f >> s) & 1) ? one.n - bA.n : bA.n;
                 const bool live = act && i0 + s < a.N;
                 if (MODE == GM_STORE) { if (live) st(a.out, p, e0 + s, E); }
                 if (MODE == GM_COMMON) { acc[s] += prod3(E, Wk); if (NDOT == 2) acc2[s] += prod3(E, Wk2); }
                 if (MODE == GM_ROWS) { if (live) acc[s] += prod3(E, ld(a.XT, p, e0 + s)); }
             }
+            __syncthreads();                           // dealer words are overwritten next
         }
         if (MODE != GM_STORE) {
             u64 ao[8], an[8], snd[8], rcv[8];
