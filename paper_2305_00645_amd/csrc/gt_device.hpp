@@ -139,6 +139,11 @@ struct Wire {
         base = wire + (size_t)blockIdx.x * GT_WIRE_WORDS_PER_BLOCK;
         slot = 0; p = threadIdx.y; lane = threadIdx.x;
     }
+    __device__ __forceinline__ void init2d(u64 *wire)         // grid (x, y): one region per workgroup
+    {
+        base = wire + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * GT_WIRE_WORDS_PER_BLOCK;
+        slot = 0; p = threadIdx.y; lane = threadIdx.x;
+    }
     template <int NW>
     __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
     {

@@ -118,10 +118,64 @@ __global__ __launch_bounds__(256) void k_iota(P6 idx, P6 val, u32 nh, u32 P2, u3
 }
 
 // ---------------------------------------------------------------------------------
+// Limb-tiled layout of the two operands of the statistics contraction.  A 64-bit
+// ring element is written as eight signed bytes d_s in [-128,127] with
+// x = sum_s d_s 256^s (mod 2^64): add 0x80 to every byte position with carries, then
+// flip the top bit of every byte.  A matrix M[row][sample] is stored as
+// [sample block of 32][limb s][row][32 bytes], so that one lane of a matrix-core
+// operand (one row, 16 consecutive samples, one limb) is one 16-byte load and a
+// wavefront reads 1 KB contiguous per limb.  Samples beyond N hold zero bytes.
+struct LimbMat { unsigned char *base; u64 rows; };      // rows = row stride of a limb plane
+#define GT_BIAS 0x8080808080808080ull
+
+__device__ __forceinline__ u64 limb_addr(const LimbMat &m, u64 ib, u32 s, u64 row) { return ((ib * 8 + s) * m.rows + row) * 32; }
+
+// x[0..8) are 8 consecutive samples (first sample i0, a multiple of 8) of one row
+__device__ __forceinline__ void store_limbs8(const LimbMat &m, u64 row, u64 i0, const u64 (&x)[8])
+{
+    u64 y[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) y[j] = (x[j] + GT_BIAS) ^ GT_BIAS;
+    // 8 x 8 byte transpose: afterwards byte j of y[s] is limb s of sample j
+    const u64 m1 = 0x00FF00FF00FF00FFull, m2 = 0x0000FFFF0000FFFFull, m4 = 0x00000000FFFFFFFFull;
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+        const u64 a = y[j], b = y[j + 1];
+        y[j] = (a & m1) | ((b & m1) << 8); y[j + 1] = ((a >> 8) & m1) | (b & ~m1);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j += 4)
+#pragma unroll
+        for (int q = 0; q < 2; q++) {
+            const u64 a = y[j + q], b = y[j + q + 2];
+            y[j + q] = (a & m2) | ((b & m2) << 16); y[j + q + 2] = ((a >> 16) & m2) | (b & ~m2);
+        }
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const u64 a = y[q], b = y[q + 4];
+        y[q] = (a & m4) | (b << 32); y[q + 4] = (a >> 32) | (b & ~m4);
+    }
+    const u64 ib = i0 >> 5;
+    const u32 off = (u32)i0 & 31;
+#pragma unroll
+    for (int sl = 0; sl < 8; sl++) *(u64 *)(m.base + limb_addr(m, ib, sl, row) + off) = y[sl];
+}
+
+// value of sample i of a row
+__device__ __forceinline__ u64 load_limbs1(const LimbMat &m, u64 row, u64 i)
+{
+    u64 y = 0;
+#pragma unroll
+    for (int sl = 0; sl < 8; sl++) y |= (u64)m.base[limb_addr(m, i >> 5, sl, row) + (i & 31)] << (8 * sl);
+    return (y ^ GT_BIAS) - GT_BIAS;
+}
+
+// the per-party operands: L as (own+next, own), B as (own, next)
+struct LimbSet { LimbMat m[3][2]; };
+
+// ---------------------------------------------------------------------------------
 // Elementwise product (Sec. II-B), 8 consecutive elements per lane.
 // MODE 0: z[e] = x[e]*y[e].
-// MODE 1 (one-time products of the learning protocol): e = (k*K+c)*N8 + i,
-//         z[e] = XT[k*N8+i] * YT[c*N8+i], defined for i < N.
 // MODE 2 (node split): e = r*CW + col, z = C[e] * (1 - split[r]), written to both
 //         children (2r, 2r+1) of the next level.
 struct MultArgs { KCommon c; P6 x, y, z; u64 n, N, N8; u32 K, CW; };
@@ -144,10 +198,6 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
             Sh x = { 0, 0 }, y = { 0, 0 };
             if (e < a.n) {
                 if (MODE == 0) { x = ld(a.x, p, e); y = ld(a.y, p, e); }
-                if (MODE == 1) {
-                    const u64 col = e / a.N8, i = e % a.N8;
-                    if (i < a.N) { x = ld(a.x, p, (col / a.K) * a.N8 + i); y = ld(a.y, p, (col % a.K) * a.N8 + i); }
-                }
                 if (MODE == 2) { x = ld(a.x, p, e); y = pub(p, 1) - ld(a.y, p, e / a.CW); }
             }
             snd[s] = prod3(x, y) + (ao[s] - an[s]);
@@ -159,13 +209,81 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
             if (e < a.n) {
                 Sh z = { snd[s], rcv[s] };
                 if (MODE == 0) st(a.z, p, e, z);
-                if (MODE == 1) { if (e % a.N8 < a.N) st(a.z, p, e, z); }
                 if (MODE == 2) {
                     const u64 r = e / a.CW, col = e % a.CW;
                     st(a.z, p, (2 * r) * a.CW + col, z);
                     st(a.z, p, (2 * r + 1) * a.CW + col, z);
                 }
             }
+        }
+    }
+}
+
+// One-time products of the learning protocol (Sec. V-B): column col = k*K + c,
+// element e = col*N8 + i, z = XT[k][i] * YT[c][i] for i < N, written as limb tiles
+// (own component into B.m[p][0], next into B.m[p][1]).  blockIdx.y = column.
+struct XyArgs { KCommon c; P6 XT, YT; LimbSet B; u64 N, N8; u32 K, ncol; };
+__global__ __launch_bounds__(192) void k_xy(XyArgs a)
+{
+    const int p = threadIdx.y, lane = threadIdx.x;
+    Wire W; W.init2d(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    const u64 ngrp = a.N8 / 8;
+    for (u64 col = blockIdx.y; col < a.ncol; col += gridDim.y) {
+        const u64 kx = col / a.K, cy = col % a.K;
+        for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
+            const u64 g = tile * GT_LANES + lane, i0 = g * 8;
+            const bool act = g < ngrp;
+            u64 ao[8], an[8], snd[8], rcv[8];
+            const u64 blk = (col * a.N8 + i0) >> 3;
+            chacha8(K.own, blk, a.c.op, 0, ao);
+            chacha8(K.nxt, blk, a.c.op, 0, an);
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                Sh x = { 0, 0 }, y = { 0, 0 };
+                if (act && i0 + s < a.N) { x = ld(a.XT, p, kx * a.N8 + i0 + s); y = ld(a.YT, p, cy * a.N8 + i0 + s); }
+                snd[s] = prod3(x, y) + (ao[s] - an[s]);
+            }
+            W.reshare<8>(snd, rcv);
+            if (act) {
+#pragma unroll
+                for (int s = 0; s < 8; s++) if (i0 + s >= a.N) { snd[s] = 0; rcv[s] = 0; }
+                store_limbs8(a.B.m[p][0], col, i0, snd);
+                store_limbs8(a.B.m[p][1], col, i0, rcv);
+            }
+        }
+    }
+}
+
+// class indicator columns into limb tiles: row = rowbase + c
+__global__ __launch_bounds__(256) void k_y_limbs(P6 YT, LimbSet B, u64 N, u64 N8, u32 K, u64 rowbase)
+{
+    const u64 ngrp = N8 / 8, total = ngrp * K;
+    for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (u64)gridDim.x * blockDim.x) {
+        const u64 c = t / ngrp, i0 = (t % ngrp) * 8;
+        for (int p = 0; p < 3; p++) {
+            u64 xo[8], xn[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const bool live = i0 + s < N;
+                xo[s] = live ? YT.o[p][c * N8 + i0 + s] : 0; xn[s] = live ? YT.n[p][c * N8 + i0 + s] : 0;
+            }
+            store_limbs8(B.m[p][0], rowbase + c, i0, xo);
+            store_limbs8(B.m[p][1], rowbase + c, i0, xn);
+        }
+    }
+}
+
+// per-sample leaf one-hot back to 64-bit words for export: out[r*N8 + i]
+__global__ __launch_bounds__(256) void k_l_export(LimbSet L, P6 out, u64 nh, u64 N, u64 N8)
+{
+    const u64 total = nh * N8;
+    for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (u64)gridDim.x * blockDim.x) {
+        const u64 r = t / N8, i = t % N8;
+        for (int p = 0; p < 3; p++) {
+            u64 sum = 0, own = 0;
+            if (i < N) { sum = load_limbs1(L.m[p][0], r, i); own = load_limbs1(L.m[p][1], r, i); }
+            out.o[p][t] = own; out.n[p][t] = sum - own;
         }
     }
 }
@@ -177,7 +295,7 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 // over the columns, so that one PRF block yields the mask words of its 8 elements
 // and the inner products of the array access accumulate in registers.
 //   E[k][i] = [u[i] - base == k]  (and g[k] if HAS_G)  -> arithmetic sharing, then
-//   GM_STORE : out[k*N8+i] = E
+//   GM_STORE : E written as limb tiles, the left operand of the statistics contraction
 //   GM_COMMON: z[i] = sum_k E[k][i] * W1[w1off+k]   (NDOT = 2: also W2 -> out2)
 //   GM_ROWS  : z[i] = sum_k E[k][i] * XT[k*N8+i]
 //   epilogue 0: out[i] = z;  1: out[i] = 2*prev[i] + z + 1  (index update of the
@@ -189,6 +307,7 @@ struct GridArgs {
     P6 g, out, out2, W1, W2, XT, prev;
     u64 w1off, w2off;
     int epi;
+    LimbSet L;      // GM_STORE: limb tiles of (own+next, own), row = column k
 };
 
 template <int W2B>
@@ -332,6 +451,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 Wk = ld(a.W1, p, a.w1off + k);
                 if (NDOT == 2) Wk2 = ld(a.W2, p, a.w2off + k);
             }
+            u64 Es[8], Eo[8];
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
@@ -341,9 +461,13 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
                 E.n = ((f >> s) & 1) ? one.n - bA.n : bA.n;
                 const bool live = act && i0 + s < a.N;
-                if (MODE == GM_STORE) { if (live) st(a.out, p, e0 + s, E); }
+                if (MODE == GM_STORE) { Es[s] = live ? E.o + E.n : 0; Eo[s] = live ? E.o : 0; }
                 if (MODE == GM_COMMON) { acc[s] += prod3(E, Wk); if (NDOT == 2) acc2[s] += prod3(E, Wk2); }
                 if (MODE == GM_ROWS) { if (live) acc[s] += prod3(E, ld(a.XT, p, e0 + s)); }
+            }
+            if (MODE == GM_STORE && act) {
+                store_limbs8(a.L.m[p][0], k, i0, Es);
+                store_limbs8(a.L.m[p][1], k, i0, Eo);
             }
             __syncthreads();                           // dealer words are overwritten next
         }
@@ -607,62 +731,69 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 // ---------------------------------------------------------------------------------
 // Statistics counting as a contraction in Z_2^64 (Sec. V-B):
 //   Z_p[r][col] = sum_i (L_p + L_{p+1})[r][i] * B_p[col][i] + L_p[r][i] * B_{p+1}[col][i]
-// with L the per-sample leaf one-hot (n_h x N8) and B the sample-contiguous columns
-// (XY products, then the K class indicators).  64 x 64 output tile per workgroup,
-// 4 x 4 per lane, 16-sample slices staged through LDS; the sample range is split
-// over workgroups and partial sums meet by 64-bit atomic adds, which are exact and
-// order-independent in the ring.
-#define CT_T 64
-#define CT_K 16
-struct CountArgs { P6 LT, BT; u64 N8; u32 nh, ncol; u64 colbase; u64 *Zacc; u64 kchunk; u32 nchunk; };
+// with L the per-sample leaf one-hot and B the sample-contiguous columns (XY products,
+// then the K class indicators).  Both operands are uniformly random 64-bit shares, so
+// this is a dense integer GEMM; it runs on the matrix cores in signed 8-bit limbs:
+//   x*y mod 2^64 = sum_{s+t<=7} d_s(x) d_t(y) 256^(s+t),
+// 36 limb pairs, one v_mfma_i32_32x32x32_i8 each, accumulated per u = s+t in int32.
+// |d_s d_t| <= 2^14 and at most 8 pairs x 2 products x 4096 samples meet in one
+// accumulator, which stays below 2^31.  A wavefront owns a 32 x 64 output tile
+// (8 x 2 accumulators of 16 registers); the sample range is split over workgroups
+// and the recombined 64-bit partial sums meet by atomic adds (exact, order-free).
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+#define CT_CHUNK_BLOCKS 128          // 128 blocks of 32 samples per workgroup
+struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 colbase; u64 *Zacc; u32 nchunk, nrowgrp; };
 
 __global__ __launch_bounds__(256) void k_count(CountArgs a)
 {
-    __shared__ u64 As[CT_K][CT_T + 1], Ao[CT_K][CT_T + 1], Bo[CT_K][CT_T + 1], Bn[CT_K][CT_T + 1];
-    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
-    const int p = blockIdx.z / a.nchunk;
-    const u64 chunk = blockIdx.z % a.nchunk;
-    const u64 r0 = (u64)blockIdx.y * CT_T, c0 = (u64)blockIdx.x * CT_T;
-    const u64 kbeg = chunk * a.kchunk, kend = kbeg + a.kchunk < a.N8 ? kbeg + a.kchunk : a.N8;
-    const u64 *Lo = own_of(a.LT, p), *Ln = nxt_of(a.LT, p), *Xo = own_of(a.BT, p), *Xn = nxt_of(a.BT, p);
-    u64 acc[4][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = blockIdx.z / a.nrowgrp, rg = blockIdx.z % a.nrowgrp;
+    const u64 r0 = (u64)rg * 128 + wave * 32;
+    if (r0 >= a.nh) return;                                   // whole wavefront, no barrier in this kernel
+    const u64 c0 = a.colbase + (u64)blockIdx.x * 64;
+    const u64 ib0 = (u64)blockIdx.y * CT_CHUNK_BLOCKS;
+    const u64 ib1 = ib0 + CT_CHUNK_BLOCKS < a.nblk ? ib0 + CT_CHUNK_BLOCKS : a.nblk;
+    const u32 lr = lane & 31, lg = (lane >> 5) * 16;
+    v16i acc[8][2];
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int u = 0; u < 8; u++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) acc[i][j] = 0;
-    const int lrow = tid / 4, lk = (tid % 4) * 4;      // loader: 64 rows x 16 samples, 4 samples per lane
-    for (u64 k0 = kbeg; k0 < kend; k0 += CT_K) {
+        for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const u64 i = k0 + lk + q;
-            u64 lo = 0, ln = 0, xo = 0, xn = 0;
-            if (i < kend) {
-                if (r0 + lrow < a.nh) { lo = Lo[(r0 + lrow) * a.N8 + i]; ln = Ln[(r0 + lrow) * a.N8 + i]; }
-                if (c0 + lrow < a.ncol) { xo = Xo[(a.colbase + c0 + lrow) * a.N8 + i]; xn = Xn[(a.colbase + c0 + lrow) * a.N8 + i]; }
+            for (int v = 0; v < 16; v++) acc[u][nb][v] = 0;
+    for (u64 ib = ib0; ib < ib1; ib++) {
+#pragma unroll
+        for (int m = 0; m < 2; m++) {
+            const LimbMat &LA = p == 0 ? a.L.m[0][m] : (p == 1 ? a.L.m[1][m] : a.L.m[2][m]);
+            const LimbMat &LB = p == 0 ? a.B.m[0][m] : (p == 1 ? a.B.m[1][m] : a.B.m[2][m]);
+            v4i av[8], bv[2][8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                av[s] = *(const v4i *)(LA.base + limb_addr(LA, ib, s, r0 + lr) + lg);
+                bv[0][s] = *(const v4i *)(LB.base + limb_addr(LB, ib, s, c0 + lr) + lg);
+                bv[1][s] = *(const v4i *)(LB.base + limb_addr(LB, ib, s, c0 + 32 + lr) + lg);
             }
-            As[lk + q][lrow] = lo + ln; Ao[lk + q][lrow] = lo;
-            Bo[lk + q][lrow] = xo; Bn[lk + q][lrow] = xn;
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+#pragma unroll
+                for (int s = 0; s <= u; s++) {
+                    acc[u][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[s], bv[0][u - s], acc[u][0], 0, 0, 0);
+                    acc[u][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[s], bv[1][u - s], acc[u][1], 0, 0, 0);
+                }
         }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < CT_K; kk++) {
-            u64 as[4], ao[4], bo[4], bn[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) { as[i] = As[kk][ty * 4 + i]; ao[i] = Ao[kk][ty * 4 + i]; bo[i] = Bo[kk][tx * 4 + i]; bn[i] = Bn[kk][tx * 4 + i]; }
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-#pragma unroll
-                for (int j = 0; j < 4; j++) acc[i][j] += as[i] * bo[j] + ao[i] * bn[j];
-        }
-        __syncthreads();
     }
     u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const u64 r = r0 + ty * 4 + i, c = c0 + tx * 4 + j;
-            if (r < a.nh && c < a.ncol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)acc[i][j]);
+        for (int v = 0; v < 16; v++) {
+            const u64 r = r0 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
+            const u64 c = (u64)blockIdx.x * 64 + nb * 32 + lr;
+            u64 z = 0;
+#pragma unroll
+            for (int u = 0; u < 8; u++) z += (u64)(long long)acc[u][nb][v] << (8 * u);
+            if (r < a.nh && c < a.ncol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)z);
         }
 }
 

@@ -50,8 +50,10 @@ struct gt_train {
     size_t N, N8;
     u32 d, K, H, CW, level, last, P2;
     bool finished;
-    DSh XT, BT;                      // [k][i]; [(k*K+c) | d*K+c][i]
-    DSh M, T, F, C, Cn, gamma, Gn, isLeaf, LT, SD, split;
+    DSh XT, YT;                      // [k][i], [c][i]: sample-contiguous copies of the inputs
+    unsigned char *LQ, *BQ;          // limb tiles: leaf one-hot (own+next, own), columns (own, next)
+    size_t nblk, Lrows, Brows;       // sample blocks of 32, row strides of the limb planes
+    DSh M, T, F, C, Cn, gamma, Gn, isLeaf, SD, split;
     DSh S, Q, quo, rem, val[2], idx[2], tval, best, lab;
     DSh Clast, Glast, Slast;
     u64 *Zacc;
@@ -273,7 +275,6 @@ static int do_mult(gt_ctx *c, int mode, MultArgs a)
     if (a.n) {
         dim3 g(tiles8(a.n));
         if (mode == 0) return launch(c, GT_KC_MULT, k_mult<0>, g, GT_BLOCK, a);
-        if (mode == 1) return launch(c, GT_KC_MULT, k_mult<1>, g, GT_BLOCK, a);
         return launch(c, GT_KC_MULT, k_mult<2>, g, GT_BLOCK, a);
     }
     return GT_OK;
@@ -373,13 +374,25 @@ extern "C" int gt_div(gt_ctx *c, const gt_shares *S, const gt_shares *Q, size_t 
 // ---- training -------------------------------------------------------------------------
 static void train_free(gt_train *t)
 {
-    DSh *all[] = { &t->XT, &t->BT, &t->M, &t->T, &t->F, &t->C, &t->Cn, &t->gamma, &t->Gn, &t->isLeaf, &t->LT, &t->SD,
+    if (t->LQ) (void)hipFree(t->LQ);
+    if (t->BQ) (void)hipFree(t->BQ);
+    DSh *all[] = { &t->XT, &t->YT, &t->M, &t->T, &t->F, &t->C, &t->Cn, &t->gamma, &t->Gn, &t->isLeaf, &t->SD,
                    &t->split, &t->S, &t->Q, &t->quo, &t->rem, &t->val[0], &t->val[1], &t->idx[0], &t->idx[1],
                    &t->tval, &t->best, &t->lab, &t->Clast, &t->Glast, &t->Slast };
     for (DSh *s : all) dsh_free(*s);
     if (t->Zacc) (void)hipFree(t->Zacc);
     delete t;
 }
+
+static LimbSet limbs_of(unsigned char *base, size_t nblk, size_t rows)
+{
+    LimbSet L;
+    const size_t per = nblk * 8 * rows * 32;
+    for (int p = 0; p < 3; p++) for (int m = 0; m < 2; m++) { L.m[p][m].base = base + (size_t)(2 * p + m) * per; L.m[p][m].rows = rows; }
+    return L;
+}
+static LimbSet limbs_L(const gt_train *t) { return limbs_of(t->LQ, t->nblk, t->Lrows); }
+static LimbSet limbs_B(const gt_train *t) { return limbs_of(t->BQ, t->nblk, t->Brows); }
 
 extern "C" int gt_train_destroy(gt_train *t) { if (!t) return GT_EINVAL; (void)hipDeviceSynchronize(); train_free(t); return GT_OK; }
 
@@ -390,12 +403,14 @@ static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shar
     const size_t N = t->N, N8 = t->N8, nmax = (size_t)1 << t->H, nodes = ((size_t)2 << t->H) - 1;
     // sample-contiguous copies of X and Y (Y goes behind the d*K product columns)
     GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * d), B256, t->XT.v, to_p6(X), (u64)N, (u64)N8, d));
-    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * K), B256, off6(t->BT.v, (size_t)d * K * N8), to_p6(Y), (u64)N, (u64)N8, K));
-    // one-time products X[i][k] * Y[i][c]
-    MultArgs a{}; a.x = t->XT.v; a.y = off6(t->BT.v, (size_t)d * K * N8); a.z = t->BT.v;
-    a.n = (u64)d * K * N8; a.N = N; a.N8 = N8; a.K = K;
-    GTCHK(do_mult(c, 1, a));
+    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * K), B256, t->YT.v, to_p6(Y), (u64)N, (u64)N8, K));
+    // one-time products X[i][k] * Y[i][c] and the class columns, as limb tiles
+    XyArgs a{}; a.c = kc(c, c->op++); a.XT = t->XT.v; a.YT = t->YT.v; a.B = limbs_B(t); a.N = N; a.N8 = N8; a.K = K;
+    a.ncol = d * K;
+    const unsigned gy = std::min(a.ncol, 1024u), gx = std::max(1u, std::min(tiles8(N8), GT_MAX_BLOCKS / gy));
+    GTCHK(launch(c, GT_KC_MULT, k_xy, dim3(gx, gy), GT_BLOCK, a));
     acct_reshare(c, (u64)N * d * K, 1);
+    GTCHK(launch(c, GT_KC_LOCAL, k_y_limbs, g1((N8 / 8) * K), B256, t->YT.v, limbs_B(t), (u64)N, (u64)N8, K, (u64)d * K));
     // M = 0, T = 0, the root is a leaf with empty statistics, no candidate used yet
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(N), B256, t->M.v, (u64)0, (u64)N, (u64)0));
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(nodes), B256, t->T.v, (u64)0, (u64)nodes, (u64)0));
@@ -419,19 +434,26 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     const size_t N8 = pad8(N), nmax = (size_t)1 << H, nodes = ((size_t)2 << H) - 1, CW = (size_t)d * K + K;
     size_t P2 = 1; while (P2 < d) P2 *= 2;
     t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
-    t->finished = false; t->Zacc = nullptr;
+    t->finished = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr;
     hipStream_t s = c->stream;
     int rc = GT_OK;
     struct { DSh *v; size_t n; } plan[] = {
-        { &t->XT, d * N8 }, { &t->BT, CW * N8 }, { &t->M, N }, { &t->T, nodes }, { &t->F, nodes },
+        { &t->XT, d * N8 }, { &t->YT, K * N8 }, { &t->M, N }, { &t->T, nodes }, { &t->F, nodes },
         { &t->C, nmax * CW }, { &t->Cn, nmax * CW }, { &t->gamma, nmax * d }, { &t->Gn, nmax * d }, { &t->isLeaf, nmax },
-        { &t->LT, nmax * N8 }, { &t->SD, nmax }, { &t->split, nmax }, { &t->S, nmax * d * 2 }, { &t->Q, nmax * d * 2 },
+        { &t->SD, nmax }, { &t->split, nmax }, { &t->S, nmax * d * 2 }, { &t->Q, nmax * d * 2 },
         { &t->quo, nmax * d * 2 }, { &t->rem, nmax * d * 2 }, { &t->val[0], nmax * P2 }, { &t->val[1], nmax * P2 },
         { &t->idx[0], nmax * P2 }, { &t->idx[1], nmax * P2 }, { &t->tval, N }, { &t->best, nmax }, { &t->lab, nmax },
         { &t->Clast, nmax * CW }, { &t->Glast, nmax * d }, { &t->Slast, nmax * d },
     };
     for (auto &pl : plan) { rc = dsh_alloc(*pl.v, pl.n, s); if (rc != GT_OK) break; }
     if (rc == GT_OK && hipMalloc(&t->Zacc, 3 * nmax * CW * 8) != hipSuccess) rc = GT_ENOMEM;
+    t->nblk = (N + 31) / 32;
+    t->Lrows = std::max<size_t>(32, (nmax + 31) / 32 * 32);
+    t->Brows = (CW + 63) / 64 * 64 + 64;
+    const size_t lq = 6 * t->nblk * 8 * t->Lrows * 32, bq = 6 * t->nblk * 8 * t->Brows * 32;
+    if (rc == GT_OK && hipMalloc(&t->LQ, lq) != hipSuccess) rc = GT_ENOMEM;
+    if (rc == GT_OK && hipMalloc(&t->BQ, bq) != hipSuccess) rc = GT_ENOMEM;
+    if (rc == GT_OK && (hipMemsetAsync(t->LQ, 0, lq, s) != hipSuccess || hipMemsetAsync(t->BQ, 0, bq, s) != hipSuccess)) rc = GT_EHIP;
     if (rc != GT_OK) { (void)hipStreamSynchronize(s); train_free(t); return T.finish(rc); }
     rc = train_start(c, t, X, Y);
     rc = T.finish(rc);
@@ -464,7 +486,7 @@ static int leaf_onehot(gt_ctx *c, gt_train *t, u32 h)
     const u64 nh = (u64)1 << h, base = nh - 1;
     GTCHK(do_eq(c, true, t->F.v, base, nullptr, 1, t->isLeaf.v, nh));
     GridArgs a{}; a.u = t->M.v; a.base = base; a.w = (u32)nh; a.N = t->N; a.N8 = t->N8;
-    a.g = t->isLeaf.v; a.out = t->LT.v;
+    a.g = t->isLeaf.v; a.L = limbs_L(t);
     return do_grid(c, GM_STORE, true, 1, a);
 }
 
@@ -475,10 +497,11 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     const u64 colbase = totals_only ? dK : 0;
     const u32 op = c->op++;
     HIPCHK(hipMemsetAsync(t->Zacc, 0, 3 * nh * ncol * 8, c->stream));
-    CountArgs a{}; a.LT = t->LT.v; a.BT = t->BT.v; a.N8 = t->N8; a.nh = (u32)nh; a.ncol = ncol; a.colbase = colbase;
-    a.Zacc = t->Zacc; a.kchunk = 2048;
-    a.nchunk = (u32)((t->N8 + a.kchunk - 1) / a.kchunk);
-    dim3 g((ncol + CT_T - 1) / CT_T, (unsigned)((nh + CT_T - 1) / CT_T), 3 * a.nchunk);
+    CountArgs a{}; a.L = limbs_L(t); a.B = limbs_B(t); a.nblk = t->nblk; a.nh = (u32)nh; a.ncol = ncol; a.colbase = colbase;
+    a.Zacc = t->Zacc;
+    a.nchunk = (u32)((t->nblk + CT_CHUNK_BLOCKS - 1) / CT_CHUNK_BLOCKS);
+    a.nrowgrp = (u32)((nh + 127) / 128);
+    dim3 g((ncol + 63) / 64, a.nchunk, 3 * a.nrowgrp);
     GTCHK(launch(c, GT_KC_COUNT, k_count, g, B256, a));
     CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
     GTCHK(launch(c, GT_KC_SMALL, k_count_fin, dim3(tiles(f.n)), GT_BLOCK, f));
@@ -637,12 +660,13 @@ extern "C" int gt_train_export(gt_ctx *c, const gt_train *t, int what, const gt_
     case GT_X_C: src = &t->Clast; break;
     case GT_X_GAMMA: src = &t->Glast; break;
     case GT_X_SD: src = &t->SD; break;
-    case GT_X_L: src = &t->LT; break;
+    case GT_X_L: break;
     case GT_X_SCORE: src = &t->Slast; break;
     default: break;
     }
     int rc = GT_OK;
     if (src) rc = copy6(c, to_p6(out), 0, src->v, 0, 1, n);
+    else if (what == GT_X_L) rc = launch(c, GT_KC_LOCAL, k_l_export, g1(n), B256, limbs_L(t), to_p6(out), (u64)1 << t->last, (u64)t->N, (u64)t->N8);
     else {
         const u32 nh = 1u << t->last;
         rc = launch(c, GT_KC_LOCAL, k_c_paper, g1(n), B256, t->Clast.v, to_p6(out), nh, t->d, t->K, t->CW);
