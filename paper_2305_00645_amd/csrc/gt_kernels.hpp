@@ -136,24 +136,30 @@ __device__ __forceinline__ void store_limbs8(const LimbMat &m, u64 row, u64 i0, 
     u64 y[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) y[j] = (x[j] + GT_BIAS) ^ GT_BIAS;
-    // 8 x 8 byte transpose: afterwards byte j of y[s] is limb s of sample j
-    const u64 m1 = 0x00FF00FF00FF00FFull, m2 = 0x0000FFFF0000FFFFull, m4 = 0x00000000FFFFFFFFull;
+    // 8 x 8 byte transpose: afterwards byte j of y[s] is limb s of sample j.  Three
+    // butterfly stages on byte, 16-bit and 32-bit units; the first two are byte
+    // permutes of register pairs, the last is a renaming of 32-bit halves.
+    u32 lo[8], hi[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) { lo[j] = (u32)y[j]; hi[j] = (u32)(y[j] >> 32); }
 #pragma unroll
     for (int j = 0; j < 8; j += 2) {
-        const u64 a = y[j], b = y[j + 1];
-        y[j] = (a & m1) | ((b & m1) << 8); y[j + 1] = ((a >> 8) & m1) | (b & ~m1);
+        const u32 al = lo[j], bl = lo[j + 1], ah = hi[j], bh = hi[j + 1];
+        lo[j] = __builtin_amdgcn_perm(bl, al, 0x06020400u); lo[j + 1] = __builtin_amdgcn_perm(bl, al, 0x07030501u);
+        hi[j] = __builtin_amdgcn_perm(bh, ah, 0x06020400u); hi[j + 1] = __builtin_amdgcn_perm(bh, ah, 0x07030501u);
     }
 #pragma unroll
     for (int j = 0; j < 8; j += 4)
 #pragma unroll
         for (int q = 0; q < 2; q++) {
-            const u64 a = y[j + q], b = y[j + q + 2];
-            y[j + q] = (a & m2) | ((b & m2) << 16); y[j + q + 2] = ((a >> 16) & m2) | (b & ~m2);
+            const u32 al = lo[j + q], bl = lo[j + q + 2], ah = hi[j + q], bh = hi[j + q + 2];
+            lo[j + q] = __builtin_amdgcn_perm(bl, al, 0x05040100u); lo[j + q + 2] = __builtin_amdgcn_perm(bl, al, 0x07060302u);
+            hi[j + q] = __builtin_amdgcn_perm(bh, ah, 0x05040100u); hi[j + q + 2] = __builtin_amdgcn_perm(bh, ah, 0x07060302u);
         }
 #pragma unroll
     for (int q = 0; q < 4; q++) {
-        const u64 a = y[q], b = y[q + 4];
-        y[q] = (a & m4) | (b << 32); y[q + 4] = (a >> 32) | (b & ~m4);
+        y[q] = (u64)lo[q] | ((u64)lo[q + 4] << 32);
+        y[q + 4] = (u64)hi[q] | ((u64)hi[q + 4] << 32);
     }
     const u64 ib = i0 >> 5;
     const u32 off = (u32)i0 & 31;
@@ -347,21 +353,80 @@ __device__ __forceinline__ void eq_round8(Wire &W, Sh (&t)[8], const u64 (&A)[8]
     for (int s = 0; s < 8; s++) { t[s].o = z[s]; t[s].n = r[s]; }
 }
 
-// The dealer's block of an element yields the components of all three parties, so
-// the 512 blocks of a step are computed once per workgroup, spread over its 192
-// lanes (the dealer is a role of its own, not one of the parties), and left in LDS;
-// each party's wavefront then reads only the words its two components derive from.
-#define GT_TILE_EL (8 * GT_LANES)
+// The six AND rounds of eight equality tests held by one lane, in 32-bit registers.
+// Round 0 folds the high word onto the low word; afterwards everything fits 32 bits.
+// to/tn: the lane's two Boolean components; A: the lane's mask words (own xor next key).
+__device__ __forceinline__ void eq_rounds8_32(Wire &W, const Sh (&t)[8], const u64 (&A)[8], u32 (&to)[8], u32 (&tn)[8])
+{
+    {   // width 32: 8 x 32 bits = 4 words
+        u64 snd[4], rcv[4];
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const u32 ao = (u32)t[s].o, an = (u32)t[s].n, bo = (u32)(t[s].o >> 32), bn = (u32)(t[s].n >> 32);
+            to[s] = (ao & (bo ^ bn)) ^ (an & bo) ^ (u32)A[s];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) snd[j] = (u64)to[2 * j] | ((u64)to[2 * j + 1] << 32);
+        W.reshare<4>(snd, rcv);
+#pragma unroll
+        for (int j = 0; j < 4; j++) { tn[2 * j] = (u32)rcv[j]; tn[2 * j + 1] = (u32)(rcv[j] >> 32); }
+    }
+    u32 Ah[8];
+#pragma unroll
+    for (int s = 0; s < 8; s++) Ah[s] = (u32)(A[s] >> 32);   // bits 32..62: rounds 1..5
+    {   // width 16: 8 x 16 bits = 2 words
+        u64 snd[2], rcv[2];
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const u32 bo = to[s] >> 16, bn = tn[s] >> 16;
+            to[s] = ((to[s] & (bo ^ bn)) ^ (tn[s] & bo) ^ Ah[s]) & 0xffffu;
+        }
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+            snd[j] = (u64)(to[4 * j] | (to[4 * j + 1] << 16)) | ((u64)(to[4 * j + 2] | (to[4 * j + 3] << 16)) << 32);
+        W.reshare<2>(snd, rcv);
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const u32 lo = (u32)rcv[j], hi = (u32)(rcv[j] >> 32);
+            tn[4 * j] = lo & 0xffffu; tn[4 * j + 1] = lo >> 16; tn[4 * j + 2] = hi & 0xffffu; tn[4 * j + 3] = hi >> 16;
+        }
+    }
+    // widths 8, 4, 2, 1: all eight values in one word
+#define GT_EQ_SMALL_ROUND(WB, OFF)                                                              \
+    {                                                                                           \
+        u64 snd[1] = { 0 }, rcv[1];                                                             \
+        _Pragma("unroll") for (int s = 0; s < 8; s++) {                                         \
+            const u32 bo = to[s] >> WB, bn = tn[s] >> WB;                                       \
+            to[s] = ((to[s] & (bo ^ bn)) ^ (tn[s] & bo) ^ (Ah[s] >> OFF)) & ((1u << WB) - 1);    \
+            snd[0] |= (u64)to[s] << (s * WB);                                                   \
+        }                                                                                       \
+        W.reshare<1>(snd, rcv);                                                                 \
+        _Pragma("unroll") for (int s = 0; s < 8; s++) tn[s] = (u32)(rcv[0] >> (s * WB)) & ((1u << WB) - 1); \
+    }
+    GT_EQ_SMALL_ROUND(8, 16)
+    GT_EQ_SMALL_ROUND(4, 24)
+    GT_EQ_SMALL_ROUND(2, 28)
+    GT_EQ_SMALL_ROUND(1, 30)
+#undef GT_EQ_SMALL_ROUND
+}
 
-// party p's two components of (a, b, c) where c is the dealer's correction term
-#define GT_PICK_O(p, a, b, c) ((p) == 0 ? (a) : ((p) == 1 ? (b) : (c)))
-#define GT_PICK_N(p, a, b, c) ((p) == 0 ? (b) : ((p) == 1 ? (c) : (a)))
+// Offline and pairwise-key material is produced once per workgroup and handed out
+// through LDS.  The dealer's block of an element yields the components of all three
+// parties, so the 512 blocks of a step are spread over the 192 lanes (the dealer is a
+// role of its own, not one of the parties); each party's wavefront then reads only its
+// two components.  The mask word under key k_j is evaluated by party j's wavefront and
+// also read by party j-1, the other holder of k_j; it reuses the rows of the edaBit's
+// arithmetic components, which are dead once the masked value has been opened.
+#define GT_TILE_EL (8 * GT_LANES)
 
 template <int MODE, bool HAS_G, int NDOT>
 __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 {
-    __shared__ u64 s_D[8][GT_TILE_EL];         // raw dealer words D0..D7 per element
-    const int p = threadIdx.y, lane = threadIdx.x, tid = p * GT_LANES + lane;
+    // rows 0-2: r arithmetic components, then the mask words under k_0..k_2;
+    // rows 3-5: r Boolean components; rows 6-8: beta arithmetic components
+    __shared__ u64 s_mat[9][GT_TILE_EL];
+    __shared__ unsigned char s_bits[GT_TILE_EL];   // beta Boolean components, bit j = component j
+    const int p = threadIdx.y, lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1;
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u32 op = a.c.op;
@@ -383,10 +448,16 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                     const u64 e = (u64)k * a.N8 + (tile * GT_LANES + (el & (GT_LANES - 1))) * 8 + (el >> 6);
                     u64 D[8];
                     chacha8(K.dlr, e, op, 0, D);
-#pragma unroll
-                    for (int i = 0; i < 8; i++) s_D[i][el] = D[i];
+                    const u64 beta = D[5] & 1;
+                    s_mat[0][el] = D[1]; s_mat[1][el] = D[2]; s_mat[2][el] = D[0] - D[1] - D[2];
+                    s_mat[3][el] = D[3]; s_mat[4][el] = D[4]; s_mat[5][el] = D[0] ^ D[3] ^ D[4];
+                    s_mat[6][el] = D[6]; s_mat[7][el] = D[7]; s_mat[8][el] = beta - D[6] - D[7];
+                    const u32 b0 = (u32)(D[5] >> 1) & 1, b1 = (u32)(D[5] >> 2) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
+                    s_bits[el] = (unsigned char)(b0 | (b1 << 1) | (b2 << 2));
                 }
             }
+            u64 A[8];
+            chacha8(K.own, e0 >> 3, op, 1, A);         // mask words under this party's own key
             __syncthreads();
             u64 snd[8], rcv[8], mn[8];
             const Sh sub = pub(p, a.base + k);
@@ -395,54 +466,46 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 const int el = s * GT_LANES + lane;
                 Sh v = { 0, 0 };
                 if (act && i0 + s < a.N) v = ld(a.u, p, i0 + s) - sub;
-                const u64 d0 = s_D[0][el], d1 = s_D[1][el], d2 = s_D[2][el], d3 = d0 - d1 - d2;
-                snd[s] = v.o + GT_PICK_O(p, d1, d2, d3);
-                mn[s] = v.n + GT_PICK_N(p, d1, d2, d3);
+                snd[s] = v.o + s_mat[p][el];
+                mn[s] = v.n + s_mat[pn][el];
             }
             W.open<8>(snd, rcv);                       // masked values, 64 bits each
+#pragma unroll
+            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = A[s];
             Sh t[8];
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
                 const u64 nc = ~(snd[s] + mn[s] + rcv[s]);
-                const u64 d3 = s_D[3][el], d4 = s_D[4][el], d5 = s_D[0][el] ^ d3 ^ d4;
-                t[s].o = GT_PICK_O(p, d3, d4, d5) ^ (nc & mo);
-                t[s].n = GT_PICK_N(p, d3, d4, d5) ^ (nc & mn_);
+                t[s].o = s_mat[3 + p][el] ^ (nc & mo);
+                t[s].n = s_mat[3 + pn][el] ^ (nc & mn_);
             }
-            u64 A[8];
-            chacha8(K.own, e0 >> 3, op, 1, A);
-            {
-                u64 An[8];
-                chacha8(K.nxt, e0 >> 3, op, 1, An);
+            __syncthreads();
 #pragma unroll
-                for (int s = 0; s < 8; s++) A[s] ^= An[s];
-            }
-            eq_round8<32>(W, t, A, 0);                 // six AND rounds, 63 bits
-            eq_round8<16>(W, t, A, 32);
-            eq_round8<8>(W, t, A, 48);
-            eq_round8<4>(W, t, A, 56);
-            eq_round8<2>(W, t, A, 60);
-            eq_round8<1>(W, t, A, 62);
+            for (int s = 0; s < 8; s++) A[s] ^= s_mat[pn][s * GT_LANES + lane];
+            u32 to[8], tn[8];
+            eq_rounds8_32(W, t, A, to, tn);            // six AND rounds, 63 bits
             if (HAS_G) {                               // and with the column's shared bit
                 const Sh gk = ld(a.g, p, k);
-                u64 z[8], r[8], s1[1], r1[1];
+                const u32 go = (u32)gk.o & 1, gn = (u32)gk.n & 1;
+                u64 s1[1] = { 0 }, r1[1];
 #pragma unroll
-                for (int s = 0; s < 8; s++) z[s] = (and3(t[s], gk) ^ (A[s] >> 63)) & 1;
-                pack8<1>(z, s1);
+                for (int s = 0; s < 8; s++) {
+                    to[s] = ((to[s] & (go ^ gn)) ^ (tn[s] & go) ^ (u32)(A[s] >> 63)) & 1;
+                    s1[0] |= (u64)to[s] << s;
+                }
                 W.reshare<1>(s1, r1);
-                unpack8<1>(r1, r);
 #pragma unroll
-                for (int s = 0; s < 8; s++) { t[s].o = z[s]; t[s].n = r[s]; }
+                for (int s = 0; s < 8; s++) tn[s] = (u32)(r1[0] >> s) & 1;
             }
             u32 f;
             {                                          // bit -> arithmetic: open s xor beta
                 u32 fo = 0, fn = 0;
 #pragma unroll
                 for (int s = 0; s < 8; s++) {
-                    const u64 d5 = s_D[5][s * GT_LANES + lane];
-                    const u32 b0 = (u32)(d5 >> 1) & 1, b1 = (u32)(d5 >> 2) & 1, b2 = ((u32)d5 ^ b0 ^ b1) & 1;
-                    fo |= (((u32)t[s].o ^ GT_PICK_O(p, b0, b1, b2)) & 1) << s;
-                    fn |= (((u32)t[s].n ^ GT_PICK_N(p, b0, b1, b2)) & 1) << s;
+                    const u32 bb = s_bits[s * GT_LANES + lane];
+                    fo |= ((to[s] ^ (bb >> p)) & 1) << s;
+                    fn |= ((tn[s] ^ (bb >> pn)) & 1) << s;
                 }
                 f = fo ^ fn ^ (u32)W.open1((u64)fo);
             }
@@ -455,8 +518,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
-                const u64 d6 = s_D[6][el], d7 = s_D[7][el], d8 = (s_D[5][el] & 1) - d6 - d7;
-                const Sh bA = { GT_PICK_O(p, d6, d7, d8), GT_PICK_N(p, d6, d7, d8) };
+                const Sh bA = { s_mat[6 + p][el], s_mat[6 + pn][el] };
                 Sh E;
                 E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
                 E.n = ((f >> s) & 1) ? one.n - bA.n : bA.n;
@@ -469,7 +531,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 store_limbs8(a.L.m[p][0], k, i0, Es);
                 store_limbs8(a.L.m[p][1], k, i0, Eo);
             }
-            __syncthreads();                           // dealer words are overwritten next
+            __syncthreads();                           // the material in LDS is overwritten next
         }
         if (MODE != GM_STORE) {
             u64 ao[8], an[8], snd[8], rcv[8];
@@ -762,27 +824,34 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
         for (int nb = 0; nb < 2; nb++)
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[u][nb][v] = 0;
-    for (u64 ib = ib0; ib < ib1; ib++) {
-#pragma unroll
-        for (int m = 0; m < 2; m++) {
-            const LimbMat &LA = p == 0 ? a.L.m[0][m] : (p == 1 ? a.L.m[1][m] : a.L.m[2][m]);
-            const LimbMat &LB = p == 0 ? a.B.m[0][m] : (p == 1 ? a.B.m[1][m] : a.B.m[2][m]);
-            v4i av[8], bv[2][8];
-#pragma unroll
-            for (int s = 0; s < 8; s++) {
-                av[s] = *(const v4i *)(LA.base + limb_addr(LA, ib, s, r0 + lr) + lg);
-                bv[0][s] = *(const v4i *)(LB.base + limb_addr(LB, ib, s, c0 + lr) + lg);
-                bv[1][s] = *(const v4i *)(LB.base + limb_addr(LB, ib, s, c0 + 32 + lr) + lg);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; u++)
-#pragma unroll
-                for (int s = 0; s <= u; s++) {
-                    acc[u][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[s], bv[0][u - s], acc[u][0], 0, 0, 0);
-                    acc[u][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[s], bv[1][u - s], acc[u][1], 0, 0, 0);
-                }
-        }
+    // two register sets: the operands of the next product are in flight while the
+    // matrix cores work on the current one (product 0: (L_p + L_{p+1}) x B_p, 1: L_p x B_{p+1})
+    const LimbMat LA0 = p == 0 ? a.L.m[0][0] : (p == 1 ? a.L.m[1][0] : a.L.m[2][0]);
+    const LimbMat LA1 = p == 0 ? a.L.m[0][1] : (p == 1 ? a.L.m[1][1] : a.L.m[2][1]);
+    const LimbMat LB0 = p == 0 ? a.B.m[0][0] : (p == 1 ? a.B.m[1][0] : a.B.m[2][0]);
+    const LimbMat LB1 = p == 0 ? a.B.m[0][1] : (p == 1 ? a.B.m[1][1] : a.B.m[2][1]);
+    v4i av0[8], bv0[2][8], av1[8], bv1[2][8];
+#define CT_LOAD(AV, BV, LA, LB, IB)                                                           \
+    _Pragma("unroll") for (int s = 0; s < 8; s++) {                                           \
+        AV[s] = *(const v4i *)(LA.base + limb_addr(LA, IB, s, r0 + lr) + lg);                 \
+        BV[0][s] = *(const v4i *)(LB.base + limb_addr(LB, IB, s, c0 + lr) + lg);              \
+        BV[1][s] = *(const v4i *)(LB.base + limb_addr(LB, IB, s, c0 + 32 + lr) + lg);         \
     }
+#define CT_MMA(AV, BV)                                                                        \
+    _Pragma("unroll") for (int u = 0; u < 8; u++)                                             \
+        _Pragma("unroll") for (int s = 0; s <= u; s++) {                                      \
+            acc[u][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[0][u - s], acc[u][0], 0, 0, 0); \
+            acc[u][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[1][u - s], acc[u][1], 0, 0, 0); \
+        }
+    CT_LOAD(av0, bv0, LA0, LB0, ib0)
+    for (u64 ib = ib0; ib < ib1; ib++) {
+        CT_LOAD(av1, bv1, LA1, LB1, ib)
+        CT_MMA(av0, bv0)
+        if (ib + 1 < ib1) { CT_LOAD(av0, bv0, LA0, LB0, ib + 1) }
+        CT_MMA(av1, bv1)
+    }
+#undef CT_LOAD
+#undef CT_MMA
     u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
 #pragma unroll
     for (int nb = 0; nb < 2; nb++)
