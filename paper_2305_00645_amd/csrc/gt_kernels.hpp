@@ -60,16 +60,44 @@ __global__ __launch_bounds__(256) void k_copy(P6 dst, u64 doff, P6 src, u64 soff
         }
 }
 
-// dst[r][i] (row stride N8) = src[i][r] (row stride w): sample-contiguous layout
+// dst[k][i] (row stride N8) = src[i][k] (row stride w): sample-contiguous layout.
+// 32 x 32 tiles through LDS so that both the reads and the writes are contiguous;
+// blockIdx.z selects one of the six planes.
 __global__ __launch_bounds__(256) void k_transpose(P6 dst, P6 src, u64 N, u64 N8, u32 w)
 {
-    const u64 total = N * w;
-    for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (u64)gridDim.x * blockDim.x) {
-        const u64 k = t / N, i = t % N;
-        for (int j = 0; j < 3; j++) {
-            dst.o[j][k * N8 + i] = src.o[j][i * w + k];
-            dst.n[j][k * N8 + i] = src.n[j][i * w + k];
+    __shared__ u64 tile[32][33];
+    const int pl = blockIdx.z, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8 threads
+    const u64 *in = pl < 3 ? src.o[pl] : src.n[pl - 3];
+    u64 *out = pl < 3 ? dst.o[pl] : dst.n[pl - 3];
+    const u64 ntx = (w + 31) / 32, nty = (N + 31) / 32;
+    for (u64 t = blockIdx.x; t < ntx * nty; t += gridDim.x) {
+        const u64 k0 = (t % ntx) * 32, i0 = (t / ntx) * 32;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const u64 i = i0 + ty + 8 * r, k = k0 + tx;
+            tile[ty + 8 * r][tx] = (i < N && k < w) ? in[i * w + k] : 0;
         }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const u64 k = k0 + ty + 8 * r, i = i0 + tx;
+            if (i < N && k < w) out[k * N8 + i] = tile[tx][ty + 8 * r];
+        }
+        __syncthreads();
+    }
+}
+
+// eight consecutive words starting at a multiple of 8: vector loads when all eight lie
+// inside the array and the address is 16-byte aligned, guarded loads (zero beyond n) otherwise
+__device__ __forceinline__ void ld8(const u64 *ptr, u64 i0, u64 n, u64 (&x)[8])
+{
+    if (i0 + 8 <= n && ((size_t)(ptr + i0) & 15) == 0) {
+        const ulonglong2 *q = (const ulonglong2 *)(ptr + i0);
+#pragma unroll
+        for (int j = 0; j < 4; j++) { const ulonglong2 v = q[j]; x[2 * j] = v.x; x[2 * j + 1] = v.y; }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++) x[j] = i0 + j < n ? ptr[i0 + j] : 0;
     }
 }
 
@@ -244,10 +272,13 @@ __global__ __launch_bounds__(192) void k_xy(XyArgs a)
             const u64 blk = (col * a.N8 + i0) >> 3;
             chacha8(K.own, blk, a.c.op, 0, ao);
             chacha8(K.nxt, blk, a.c.op, 0, an);
+            u64 xo[8], xn[8], yo[8], yn[8];
+            const u64 nv = act ? a.N : 0;               // rows start at multiples of 8
+            ld8(own_of(a.XT, p) + kx * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + kx * a.N8, i0, nv, xn);
+            ld8(own_of(a.YT, p) + cy * a.N8, i0, nv, yo); ld8(nxt_of(a.YT, p) + cy * a.N8, i0, nv, yn);
 #pragma unroll
             for (int s = 0; s < 8; s++) {
-                Sh x = { 0, 0 }, y = { 0, 0 };
-                if (act && i0 + s < a.N) { x = ld(a.XT, p, kx * a.N8 + i0 + s); y = ld(a.YT, p, cy * a.N8 + i0 + s); }
+                const Sh x = { xo[s], xn[s] }, y = { yo[s], yn[s] };
                 snd[s] = prod3(x, y) + (ao[s] - an[s]);
             }
             W.reshare<8>(snd, rcv);
@@ -436,6 +467,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
         const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
         const bool act = grp < ngrp;
+        const u64 nv = act ? a.N : 0;                  // samples of this lane that exist
         u64 acc[8], acc2[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) { acc[s] = 0; acc2[s] = 0; }
@@ -461,13 +493,13 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             __syncthreads();
             u64 snd[8], rcv[8], mn[8];
             const Sh sub = pub(p, a.base + k);
+            ld8(own_of(a.u, p), i0, nv, snd); ld8(nxt_of(a.u, p), i0, nv, mn);
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
-                Sh v = { 0, 0 };
-                if (act && i0 + s < a.N) v = ld(a.u, p, i0 + s) - sub;
-                snd[s] = v.o + s_mat[p][el];
-                mn[s] = v.n + s_mat[pn][el];
+                const bool live = i0 + s < nv;
+                snd[s] = (live ? snd[s] - sub.o : 0) + s_mat[p][el];
+                mn[s] = (live ? mn[s] - sub.n : 0) + s_mat[pn][el];
             }
             W.open<8>(snd, rcv);                       // masked values, 64 bits each
 #pragma unroll
@@ -514,7 +546,8 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 Wk = ld(a.W1, p, a.w1off + k);
                 if (NDOT == 2) Wk2 = ld(a.W2, p, a.w2off + k);
             }
-            u64 Es[8], Eo[8];
+            u64 Es[8], Eo[8], xo[8], xn[8];
+            if (MODE == GM_ROWS) { ld8(own_of(a.XT, p) + (u64)k * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + (u64)k * a.N8, i0, nv, xn); }
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
@@ -525,7 +558,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 const bool live = act && i0 + s < a.N;
                 if (MODE == GM_STORE) { Es[s] = live ? E.o + E.n : 0; Eo[s] = live ? E.o : 0; }
                 if (MODE == GM_COMMON) { acc[s] += prod3(E, Wk); if (NDOT == 2) acc2[s] += prod3(E, Wk2); }
-                if (MODE == GM_ROWS) { if (live) acc[s] += prod3(E, ld(a.XT, p, e0 + s)); }
+                if (MODE == GM_ROWS) { const Sh x = { xo[s], xn[s] }; acc[s] += prod3(E, x); }
             }
             if (MODE == GM_STORE && act) {
                 store_limbs8(a.L.m[p][0], k, i0, Es);

@@ -64,10 +64,11 @@ static size_t pad8(size_t n) { return (n + 7) & ~(size_t)7; }
 static int dsh_alloc(DSh &s, size_t n, hipStream_t st)
 {
     s.n = n;
-    size_t words = 6 * (n ? n : 1);
+    const size_t stride = pad8(n ? n : 1);           // planes start 64-byte aligned
+    const size_t words = 6 * stride;
     if (hipMalloc(&s.base, words * 8) != hipSuccess) { s.base = nullptr; return GT_ENOMEM; }
     HIPCHK(hipMemsetAsync(s.base, 0, words * 8, st));
-    for (int p = 0; p < 3; p++) { s.v.o[p] = s.base + (size_t)(2 * p) * n; s.v.n[p] = s.base + (size_t)(2 * p + 1) * n; }
+    for (int p = 0; p < 3; p++) { s.v.o[p] = s.base + (size_t)(2 * p) * stride; s.v.n[p] = s.base + (size_t)(2 * p + 1) * stride; }
     return GT_OK;
 }
 static void dsh_free(DSh &s) { if (s.base) (void)hipFree(s.base); s.base = nullptr; s.n = 0; }
@@ -171,6 +172,7 @@ static int launch(gt_ctx *c, int cls, Kern kern, dim3 grid, dim3 block, Args... 
 }
 static dim3 g1(u64 n) { return dim3(blocks_for(n, 256)); }   // plain elementwise kernels
 static const dim3 B256(256);
+static dim3 gT(u64 N, u64 w) { return dim3((unsigned)std::min<u64>(((N + 31) / 32) * ((w + 31) / 32), 65535), 1, 6); }  // k_transpose
 
 // ---------------------------------------------------------------------------------
 extern "C" const char *gt_strerror(int code)
@@ -402,8 +404,8 @@ static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shar
     const u32 d = t->d, K = t->K;
     const size_t N = t->N, N8 = t->N8, nmax = (size_t)1 << t->H, nodes = ((size_t)2 << t->H) - 1;
     // sample-contiguous copies of X and Y (Y goes behind the d*K product columns)
-    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * d), B256, t->XT.v, to_p6(X), (u64)N, (u64)N8, d));
-    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, g1(N * K), B256, t->YT.v, to_p6(Y), (u64)N, (u64)N8, K));
+    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, gT(N, d), B256, t->XT.v, to_p6(X), (u64)N, (u64)N8, d));
+    GTCHK(launch(c, GT_KC_LOCAL, k_transpose, gT(N, K), B256, t->YT.v, to_p6(Y), (u64)N, (u64)N8, K));
     // one-time products X[i][k] * Y[i][c] and the class columns, as limb tiles
     XyArgs a{}; a.c = kc(c, c->op++); a.XT = t->XT.v; a.YT = t->YT.v; a.B = limbs_B(t); a.N = N; a.N8 = N8; a.K = K;
     a.ncol = d * K;
@@ -744,7 +746,7 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
         if (c->ws[i].n < need[i]) { (void)hipStreamSynchronize(c->stream); dsh_free(c->ws[i]); rc = dsh_alloc(c->ws[i], need[i], c->stream); }
     DSh &IT = c->ws[0], &tidx = c->ws[1], &f = c->ws[2], &th = c->ws[3], &x = c->ws[4];
     if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_fill_const, g1(NI), B256, tidx.v, (u64)0, (u64)NI, (u64)0);
-    if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_transpose, g1(NI * d), B256, IT.v, to_p6(I), (u64)NI, (u64)N8, d);
+    if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_transpose, gT(NI, d), B256, IT.v, to_p6(I), (u64)NI, (u64)N8, d);
     for (u32 n = 0; n < H && rc == GT_OK; n++) {
         const u64 w = (u64)1 << n, base = w - 1;
         GridArgs a{}; a.u = tidx.v; a.base = base; a.w = (u32)w; a.N = NI; a.N8 = N8;
