@@ -21,6 +21,33 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
 
 
+def micro(args, np, torch, gtree, wl):
+    """Calibration: gt_reconstruct_a on 2^27 words reads 3 GiB and writes 1 GiB exactly.
+    Then one array access (equality grid with inner product) over 64 entries for
+    --instances rows, and one split-scoring level of the C5 recipe at --samples."""
+    g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=4)
+    n = 1 << 27
+    s = g.new(n)
+    g.reconstruct_a(s)
+    del s
+    torch.cuda.empty_cache()
+    NI = args.instances
+    rng = np.random.default_rng(1)
+    W = g.share_a(rng.integers(0, 1 << 20, size=64).astype(np.uint64))
+    u = g.share_a(rng.integers(0, 64, size=NI).astype(np.uint64))
+    g.oaa(W, u)
+    N, d, K, h = args.samples, 64, 4, 7
+    w = wl.c5_level(N=N, d=d, K=K, h=h)
+    CW = d * K + K
+    X, Y = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+    st = [g.share_a(a) for a in (w["M"], w["Tprev"], w["F"], np.zeros((1 << h) * CW, dtype=np.uint64), w["gamma"].reshape(-1))]
+    g.train_create(X, Y, N, d, h + 1)
+    g.train_import(h, *st)
+    g.train_level(h)
+    torch.cuda.synchronize()
+    print(json.dumps({"micro": "done", "calibration_words": n, "oaa_rows": NI, "oaa_entries": 64, "level_samples": N}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -30,6 +57,8 @@ def main():
     ap.add_argument("--instances", type=int, default=1000000, help="inference batch (C5: 10^6)")
     ap.add_argument("--cpu-samples", type=int, default=250000, help="oracle sample for cpu_baseline (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--micro", action="store_true",
+                    help="one launch of each hot kernel plus a calibration kernel of known traffic, for rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build simulates the three parties on ONE GPU; --gpus %d is not supported "
@@ -42,6 +71,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     gtree.load()
 
+    if args.micro:
+        return micro(args, np, torch, gtree, wl)
     N, NI, d, K, h, Hinf = args.samples, args.instances, 64, 4, 7, 10
     H = h + 1
     CW = d * K + K

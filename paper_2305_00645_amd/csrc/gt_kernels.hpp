@@ -345,6 +345,9 @@ struct GridArgs {
     u64 w1off, w2off;
     int epi;
     LimbSet L;      // GM_STORE: limb tiles of (own+next, own), row = column k
+    u32 nkc, kchunk;// column ranges per tile and their length
+    u64 *dacc;      // [2][3][N8] partial inner products when nkc > 1
+    int ndot;
 };
 
 template <int W2B>
@@ -464,14 +467,20 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     const u64 ngrp = a.N8 / 8;
     const Sh one = pub(p, 1);
     const u64 mo = p == 0 ? ~0ull : 0ull, mn_ = p == 2 ? ~0ull : 0ull;   // who holds component 0
-    for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
+    // work item = (tile of 512 samples, range of columns); with more than one column
+    // range per tile the inner products are completed by atomic adds (exact in the
+    // ring) and the reshare runs in k_dot_fin
+    const u64 nt = (ngrp + GT_LANES - 1) / GT_LANES;
+    for (u64 item = blockIdx.x; item < nt * a.nkc; item += gridDim.x) {
+        const u64 tile = item / a.nkc;
+        const u32 kbeg = (u32)(item % a.nkc) * a.kchunk, kend = kbeg + a.kchunk < a.w ? kbeg + a.kchunk : a.w;
         const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
         const bool act = grp < ngrp;
         const u64 nv = act ? a.N : 0;                  // samples of this lane that exist
         u64 acc[8], acc2[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) { acc[s] = 0; acc2[s] = 0; }
-        for (u32 k = 0; k < a.w; k++) {
+        for (u32 k = kbeg; k < kend; k++) {
             const u64 e0 = (u64)k * a.N8 + i0;
 #pragma unroll 1
             for (int j = 0; j < 3; j++) {
@@ -566,7 +575,15 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             }
             __syncthreads();                           // the material in LDS is overwritten next
         }
-        if (MODE != GM_STORE) {
+        if (MODE != GM_STORE && a.nkc > 1) {
+#pragma unroll
+            for (int s = 0; s < 8; s++)
+                if (i0 + s < nv) {
+                    atomicAdd((unsigned long long *)&a.dacc[(u64)p * a.N8 + i0 + s], (unsigned long long)acc[s]);
+                    if (NDOT == 2) atomicAdd((unsigned long long *)&a.dacc[(u64)(3 + p) * a.N8 + i0 + s], (unsigned long long)acc2[s]);
+                }
+        }
+        if (MODE != GM_STORE && a.nkc == 1) {
             u64 ao[8], an[8], snd[8], rcv[8];
             chacha8(K.own, grp, op, 2, ao);
             chacha8(K.nxt, grp, op, 2, an);
@@ -591,6 +608,36 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 for (int s = 0; s < 8; s++)
                     if (act && i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.out2, p, i0 + s, z); }
             }
+        }
+    }
+}
+
+// Completion of split inner products: z_p = partial sum + alpha (stream 2, second
+// output stream 3), reshare, epilogue as in k_eqgrid.  Eight rows per lane.
+__global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
+{
+    const int p = threadIdx.y, lane = threadIdx.x;
+    Wire W; W.init(a.c.wire);
+    const PartyKeys K = load_party_keys(a.c.keys, p);
+    const u64 ngrp = a.N8 / 8;
+    const Sh one = pub(p, 1);
+    for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
+        const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
+        const u64 nv = grp < ngrp ? a.N : 0;
+        for (int q = 0; q < a.ndot; q++) {
+            u64 ao[8], an[8], snd[8], rcv[8];
+            chacha8(K.own, grp, a.c.op, 2 + q, ao);
+            chacha8(K.nxt, grp, a.c.op, 2 + q, an);
+#pragma unroll
+            for (int s = 0; s < 8; s++) snd[s] = (i0 + s < nv ? a.dacc[(u64)(3 * q + p) * a.N8 + i0 + s] : 0) + (ao[s] - an[s]);
+            W.reshare<8>(snd, rcv);
+#pragma unroll
+            for (int s = 0; s < 8; s++)
+                if (i0 + s < nv) {
+                    Sh z = { snd[s], rcv[s] };
+                    if (q == 0 && a.epi == 1) z = scale(ld(a.prev, p, i0 + s), 2) + z + one;
+                    st(q == 0 ? a.out : a.out2, p, i0 + s, z);
+                }
         }
     }
 }
@@ -838,7 +885,7 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 #define CT_CHUNK_BLOCKS 128          // 128 blocks of 32 samples per workgroup
-struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 colbase; u64 *Zacc; u32 nchunk, nrowgrp; };
+struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 colbase; u64 *Zacc; u32 nchunk, nrowgrp, ncg; };
 
 __global__ __launch_bounds__(256) void k_count(CountArgs a)
 {
@@ -846,8 +893,14 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
     const int p = blockIdx.z / a.nrowgrp, rg = blockIdx.z % a.nrowgrp;
     const u64 r0 = (u64)rg * 128 + wave * 32;
     if (r0 >= a.nh) return;                                   // whole wavefront, no barrier in this kernel
-    const u64 c0 = a.colbase + (u64)blockIdx.x * 64;
-    const u64 ib0 = (u64)blockIdx.y * CT_CHUNK_BLOCKS;
+    // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The column
+    // groups of one sample chunk read the same rows of L, so they are given
+    // consecutive slots of the same XCD: id = slot*8 + xcd, chunk = (slot / ncg)*8 + xcd.
+    const u32 ncg = a.ncg, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const u32 cg = slot % ncg, chunk = (slot / ncg) * 8 + xcd;
+    if (chunk >= a.nchunk) return;
+    const u64 c0 = a.colbase + (u64)cg * 64;
+    const u64 ib0 = (u64)chunk * CT_CHUNK_BLOCKS;
     const u64 ib1 = ib0 + CT_CHUNK_BLOCKS < a.nblk ? ib0 + CT_CHUNK_BLOCKS : a.nblk;
     const u32 lr = lane & 31, lg = (lane >> 5) * 16;
     v16i acc[8][2];
@@ -891,7 +944,7 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
             const u64 r = r0 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-            const u64 c = (u64)blockIdx.x * 64 + nb * 32 + lr;
+            const u64 c = (u64)cg * 64 + nb * 32 + lr;
             u64 z = 0;
 #pragma unroll
             for (int u = 0; u < 8; u++) z += (u64)(long long)acc[u][nb][v] << (8 * u);

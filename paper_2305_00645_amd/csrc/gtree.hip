@@ -38,6 +38,8 @@ struct gt_ctx {
     std::vector<int> ev_cls;
     gt_prof prof;
     DSh ws[5];                // inference workspace, grown on demand, kept between calls
+    u64 *dacc;                // partial inner products of split equality grids
+    size_t dacc_words;
 };
 
 struct gt_tree {
@@ -97,7 +99,9 @@ static unsigned blocks_for(u64 n, unsigned per)
     return (unsigned)std::min<u64>(b, GT_MAX_BLOCKS);
 }
 static unsigned tiles(u64 n) { return blocks_for(n, GT_LANES); }          // one element per lane
-static unsigned tiles8(u64 n) { return blocks_for((n + 7) / 8, GT_LANES); } // eight per lane
+static unsigned g_resident = 1024;   // workgroups that fit on the device at once (set at context creation)
+// eight elements per lane
+static unsigned tiles8(u64 n) { return blocks_for((n + 7) / 8, GT_LANES); }
 
 // ---- message accounting: one message of n elements of `bits` bits is ceil(n*bits/8)
 // bytes; dir = +1 to the successor (opening), -1 to the predecessor (resharing).
@@ -193,13 +197,16 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (prm->K < 1 || prm->K > GT_MAX_K || prm->tau < 1 || prm->tau > GT_MAX_TAU) return GT_EINVAL;
     gt_ctx *c = new (std::nothrow) gt_ctx();
     if (!c) return GT_ENOMEM;
-    c->op = 0; c->timing = false; c->ev_used = 0; c->keys_d = nullptr; c->wire = nullptr;
+    c->op = 0; c->timing = false; c->ev_used = 0; c->keys_d = nullptr; c->wire = nullptr; c->dacc = nullptr; c->dacc_words = 0;
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     c->profile = (prm->flags & GT_FLAG_PROFILE) != 0;
     c->tau = prm->tau; c->K = prm->K; c->stream = (hipStream_t)prm->hip_stream;
     u32 keys[5][8];
     for (int k = 0; k < 5; k++)
         for (int i = 0; i < 4; i++) { keys[k][2 * i] = (u32)prm->seed[k][i]; keys[k][2 * i + 1] = (u32)(prm->seed[k][i] >> 32); }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        g_resident = std::min<unsigned>(GT_MAX_BLOCKS, 4u * (unsigned)cus);
     if (hipMalloc(&c->keys_d, sizeof keys) != hipSuccess) { delete c; return GT_ENOMEM; }
     if (hipMalloc(&c->wire, (size_t)GT_MAX_BLOCKS * GT_WIRE_WORDS_PER_BLOCK * 8) != hipSuccess) { (void)hipFree(c->keys_d); delete c; return GT_ENOMEM; }
     if (hipMemcpy(c->keys_d, keys, sizeof keys, hipMemcpyHostToDevice) != hipSuccess ||
@@ -217,6 +224,7 @@ extern "C" int gt_ctx_destroy(gt_ctx *c)
     (void)hipEventDestroy(c->ev0); (void)hipEventDestroy(c->ev1);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (DSh &w : c->ws) dsh_free(w);
+    if (c->dacc) (void)hipFree(c->dacc);
     (void)hipFree(c->keys_d); (void)hipFree(c->wire);
     delete c;
     return GT_OK;
@@ -324,9 +332,28 @@ extern "C" int gt_ge_a(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t
 static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
 {
     a.c = kc(c, c->op++);
+    a.ndot = ndot;
     const u64 nel = (u64)a.w * a.N;
     if (a.N && a.w) {
-        dim3 g(tiles8(a.N8));
+        // enough work items to keep every resident workgroup slot busy for several rounds
+        const u64 ntile = (a.N8 / 8 + GT_LANES - 1) / GT_LANES, want = 8ull * g_resident;
+        u64 nkc = std::min<u64>(a.w, std::max<u64>(1, (want + ntile - 1) / ntile));
+        a.kchunk = (u32)((a.w + nkc - 1) / nkc);
+        a.nkc = (a.w + a.kchunk - 1) / a.kchunk;
+        a.dacc = nullptr;
+        if (mode != GM_STORE && a.nkc > 1) {
+            const size_t need = (size_t)6 * a.N8;
+            if (c->dacc_words < need) {
+                (void)hipStreamSynchronize(c->stream);
+                if (c->dacc) (void)hipFree(c->dacc);
+                c->dacc = nullptr; c->dacc_words = 0;
+                if (hipMalloc(&c->dacc, need * 8) != hipSuccess) return GT_ENOMEM;
+                c->dacc_words = need;
+            }
+            a.dacc = c->dacc;
+            HIPCHK(hipMemsetAsync(c->dacc, 0, (size_t)3 * ndot * a.N8 * 8, c->stream));
+        }
+        dim3 g((unsigned)std::min<u64>(ntile * a.nkc, GT_MAX_BLOCKS));
         int rc;
         if (mode == GM_STORE && has_g) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, true, 1>, g, GT_BLOCK, a);
         else if (mode == GM_STORE) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, false, 1>, g, GT_BLOCK, a);
@@ -334,6 +361,7 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
         else if (mode == GM_COMMON) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_COMMON, false, 1>, g, GT_BLOCK, a);
         else rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_ROWS, false, 1>, g, GT_BLOCK, a);
         GTCHK(rc);
+        if (a.dacc) GTCHK(launch(c, GT_KC_EQGRID, k_dot_fin, dim3(tiles8(a.N8)), GT_BLOCK, a));
     }
     acct_eq(c, nel);
     if (has_g) acct_and1(c, nel);
@@ -503,7 +531,8 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     a.Zacc = t->Zacc;
     a.nchunk = (u32)((t->nblk + CT_CHUNK_BLOCKS - 1) / CT_CHUNK_BLOCKS);
     a.nrowgrp = (u32)((nh + 127) / 128);
-    dim3 g((ncol + 63) / 64, a.nchunk, 3 * a.nrowgrp);
+    a.ncg = (ncol + 63) / 64;
+    dim3 g(((a.nchunk + 7) / 8) * a.ncg * 8, 1, 3 * a.nrowgrp);
     GTCHK(launch(c, GT_KC_COUNT, k_count, g, B256, a));
     CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
     GTCHK(launch(c, GT_KC_SMALL, k_count_fin, dim3(tiles(f.n)), GT_BLOCK, f));
