@@ -21,6 +21,51 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
 
 
+def paper_shapes(np, torch, gtree, wl):
+    """Timings on the two workloads shaped like the paper's headline experiments: C3 (census
+    shape, 48,842 x 294 columns, depth 7) full training, and C4 (10^4 instances, depth-7 tree with
+    thresholds) inference.  Median of 5 runs after one warm-up; context only, not `value`."""
+    res = {}
+    w = wl.c3_train()
+    N, d, K, H = w["N"], w["d"], w["K"], w["H"]
+    g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=K)
+    X, Y = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+    g.train_create(X, Y, N, d, H)
+    times, per_level = [], None
+    for it in range(6):
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        g.train_reset(X, Y)
+        lv = []
+        for h in range(H):
+            t1 = time.perf_counter(); g.train_level(h); lv.append(time.perf_counter() - t1)
+        g.train_finish().close()
+        torch.cuda.synchronize()
+        if it:
+            times.append(time.perf_counter() - t0); per_level = lv
+    tm = sorted(times)[len(times) // 2]
+    ncand = sum((1 << h) * d for h in range(H))
+    res["c3_train_depth7"] = {"samples": N, "columns": d, "seconds": tm, "candidates_per_s": ncand / tm,
+                              "last_level_candidates_per_s": (1 << (H - 1)) * d / per_level[-1]}
+    g.close(); del g, X, Y
+    wi = wl.c4_infer()
+    g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=2)
+    tree = g.tree_import(g.share_a(wi["feat"]), g.share_a(wi["thr"]), g.share_a(wi["leaf"]), wi["H"])
+    I = g.share_a(wi["I"].reshape(-1))
+    times = []
+    for it in range(6):
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        g.infer_batch(tree, I, wi["NI"], wi["d"])
+        torch.cuda.synchronize()
+        if it:
+            times.append(time.perf_counter() - t0)
+    tm = sorted(times)[len(times) // 2]
+    res["c4_infer_depth7"] = {"instances": wi["NI"], "features": wi["d"], "mode": "threshold", "seconds": tm,
+                              "instances_per_s": wi["NI"] / tm}
+    tree.close(); g.close()
+    torch.cuda.empty_cache()
+    return res
+
+
 def micro(args, np, torch, gtree, wl):
     """Calibration: gt_reconstruct_a on 2^27 words reads 3 GiB and writes 1 GiB exactly.
     Then one array access (equality grid with inner product) over 64 entries for
@@ -57,6 +102,7 @@ def main():
     ap.add_argument("--instances", type=int, default=1000000, help="inference batch (C5: 10^6)")
     ap.add_argument("--cpu-samples", type=int, default=250000, help="oracle sample for cpu_baseline (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-paper-shapes", action="store_true", help="skip the C3 training / C4 inference timings")
     ap.add_argument("--micro", action="store_true",
                     help="one launch of each hot kernel plus a calibration kernel of known traffic, for rocprofv3 --pmc")
     args = ap.parse_args()
@@ -180,6 +226,9 @@ def main():
         out["roofline"] = dict(kern[dom] if dom in kern else kern["eqgrid"], kernel=dom if dom in kern else "eqgrid")
         out["kernel_classes_ms_per_step"] = {c: prof[c][0] / k for c in prof}
         out["roofline_other"] = {c: v for c, v in kern.items() if c != out["roofline"]["kernel"]}
+
+    if not args.no_paper_shapes:
+        out["paper_shape_workloads"] = paper_shapes(np, torch, gtree, wl)
 
     if args.cpu_samples > 0:
         from oracle import Oracle, orc

@@ -131,8 +131,11 @@ typedef struct {
 
 static void dealer(const orc_ctx *c, u32 op, u64 e, dealer_t *D)
 {
+    /* words 8e..8e+7 of stream 0 are exactly block e */
+    u32 out[16];
     u64 w[8];
-    for (int i = 0; i < 8; i++) w[i] = prf(c, KEY_DEALER, op, 0, 8 * e + (u64)i);
+    orc_chacha_block(c->key[KEY_DEALER], (u32)e, (u32)(e >> 32), op, 0, PRF_ROUNDS, out);
+    for (int i = 0; i < 8; i++) w[i] = (u64)out[2 * i] | ((u64)out[2 * i + 1] << 32);
     D->r = w[0];
     D->rA[0] = w[1]; D->rA[1] = w[2]; D->rA[2] = D->r - w[1] - w[2];
     D->rho[0] = w[3]; D->rho[1] = w[4]; D->rho[2] = D->r ^ w[3] ^ w[4];
@@ -434,16 +437,25 @@ void orc_ge_a(orc_ctx *c, const uint64_t *x, const uint64_t *y, size_t n, uint64
  * Rows are samples i < n, columns k < w; E[k][i] = [u[i] - base == k], optionally
  * ANDed with a shared bit g[k] common to all rows, then converted to arithmetic.
  * Element index (and position in EA) is k*n8 + i with n8 = n padded to 8. */
-static void eq_grid(orc_ctx *c, u32 op, const sh *u, u64 base, size_t w, size_t n,
-                    const sh *g, sh *EA)
+/* A row subset (rows != NULL) computes only the listed samples, with the element
+ * indices of the full problem; results are stored compactly, row r of the list at
+ * position k*pad8(nrows) + r.  This lets a test check sampled outputs of a problem
+ * that is too large to simulate in full. */
+typedef struct { const size_t *rows; size_t nrows; } rowsel;
+static size_t rs_count(const rowsel *rs, size_t n) { return rs && rs->rows ? rs->nrows : n; }
+static size_t rs_row(const rowsel *rs, size_t r) { return rs && rs->rows ? rs->rows[r] : r; }
+
+static void eq_grid_rs(orc_ctx *c, u32 op, const sh *u, u64 base, size_t w, size_t n,
+                       const sh *g, sh *EA, const rowsel *rs)
 {
-    size_t n8 = pad8(n);
+    size_t n8 = pad8(n), nr = rs_count(rs, n), s8 = pad8(nr);
 #pragma omp parallel for schedule(static) collapse(2)
     for (size_t k = 0; k < w; k++)
-        for (size_t i = 0; i < n; i++) {
+        for (size_t r = 0; r < nr; r++) {
+            size_t i = rs_row(rs, r);
             size_t e = k * n8 + i;
             u64 v[3], A[3], t[3], a[3]; dealer_t D;
-            sh_get(u, i, v);
+            sh_get(u, r, v);                           /* u is stored per listed row */
             v[0] -= base + k;                          /* public operand: component 1 only */
             dealer(c, op, e, &D);
             eq_el(c, op, e, v, &D, A, t);
@@ -454,52 +466,68 @@ static void eq_grid(orc_ctx *c, u32 op, const sh *u, u64 base, size_t w, size_t 
                 and_el(t, gb, al, 1, t);
             }
             b2a_el(t, &D, a);
-            sh_set(EA, e, a);
+            sh_set(EA, k * s8 + r, a);
         }
-    wire_eq(c, (u64)w * n);
-    if (g) wire_and1(c, (u64)w * n);
-    wire_b2a(c, (u64)w * n);
+    wire_eq(c, (u64)w * nr);
+    if (g) wire_and1(c, (u64)w * nr);
+    wire_b2a(c, (u64)w * nr);
+}
+
+static void eq_grid(orc_ctx *c, u32 op, const sh *u, u64 base, size_t w, size_t n,
+                    const sh *g, sh *EA)
+{
+    eq_grid_rs(c, op, u, base, w, n, g, EA, NULL);
 }
 
 /* z[i] = sum_k EA[k][i] * W[k] + alpha (stream `stream`, word i): the select and
  * sum of the array-access protocol done as one inner product, one reshare per row. */
+static void dot_common_rs(const orc_ctx *c, u32 op, u32 stream, const sh *EA, const sh *W,
+                          size_t woff, size_t w, size_t n, sh *z, const rowsel *rs)
+{
+    size_t nr = rs_count(rs, n), s8 = pad8(nr);
+#pragma omp parallel for schedule(static)
+    for (size_t r = 0; r < nr; r++) {
+        u64 acc[3] = { 0, 0, 0 }, al[3];
+        for (size_t k = 0; k < w; k++) {
+            u64 a[3], b[3], p[3];
+            sh_get(EA, k * s8 + r, a); sh_get(W, woff + k, b);
+            prod3(a, b, p);
+            for (int j = 0; j < 3; j++) acc[j] += p[j];
+        }
+        zero_a(c, op, stream, rs_row(rs, r), al);
+        for (int j = 0; j < 3; j++) acc[j] += al[j];
+        sh_set(z, r, acc);
+    }
+}
 static void dot_common(const orc_ctx *c, u32 op, u32 stream, const sh *EA, const sh *W,
                        size_t woff, size_t w, size_t n, sh *z)
 {
-    size_t n8 = pad8(n);
+    dot_common_rs(c, op, stream, EA, W, woff, w, n, z, NULL);
+}
+
+/* same with a per-row array: z[i] = sum_k EA[k][i] * XT[k][i]; XT is stored like EA */
+static void dot_rows_rs(const orc_ctx *c, u32 op, u32 stream, const sh *EA, const sh *XT,
+                        size_t w, size_t n, sh *z, const rowsel *rs)
+{
+    size_t nr = rs_count(rs, n), s8 = pad8(nr);
 #pragma omp parallel for schedule(static)
-    for (size_t i = 0; i < n; i++) {
+    for (size_t r = 0; r < nr; r++) {
         u64 acc[3] = { 0, 0, 0 }, al[3];
         for (size_t k = 0; k < w; k++) {
             u64 a[3], b[3], p[3];
-            sh_get(EA, k * n8 + i, a); sh_get(W, woff + k, b);
+            sh_get(EA, k * s8 + r, a); sh_get(XT, k * s8 + r, b);
             prod3(a, b, p);
             for (int j = 0; j < 3; j++) acc[j] += p[j];
         }
-        zero_a(c, op, stream, i, al);
+        zero_a(c, op, stream, rs_row(rs, r), al);
         for (int j = 0; j < 3; j++) acc[j] += al[j];
-        sh_set(z, i, acc);
+        sh_set(z, r, acc);
     }
 }
-
-/* same with a per-row array: z[i] = sum_k EA[k][i] * XT[k][i] */
 static void dot_rows(const orc_ctx *c, u32 op, u32 stream, const sh *EA, const sh *XT,
                      size_t w, size_t n, sh *z)
 {
-    size_t n8 = pad8(n);
-#pragma omp parallel for schedule(static)
-    for (size_t i = 0; i < n; i++) {
-        u64 acc[3] = { 0, 0, 0 }, al[3];
-        for (size_t k = 0; k < w; k++) {
-            u64 a[3], b[3], p[3];
-            sh_get(EA, k * n8 + i, a); sh_get(XT, k * n8 + i, b);
-            prod3(a, b, p);
-            for (int j = 0; j < 3; j++) acc[j] += p[j];
-        }
-        zero_a(c, op, stream, i, al);
-        for (int j = 0; j < 3; j++) acc[j] += al[j];
-        sh_set(z, i, acc);
-    }
+    dot_rows_rs(c, op, stream, EA, XT, w, n, z, NULL);
 }
 
 /* Oblivious array access (Sec. V-A): 7 + 1 + 1 rounds = log l + 3. */
@@ -1024,53 +1052,71 @@ int orc_train_import(orc_train *t, uint32_t h, const uint64_t *M, const uint64_t
  * instance, step to a child; the label is the value fetched at level H.
  * Binary mode: the fetched feature value is the branch bit.  Threshold mode (an
  * extension for non-binary inputs): the bit is [value > threshold]. */
-int orc_infer_batch(orc_ctx *c, const uint64_t *featf, const uint64_t *thrf, const uint64_t *leaff,
-                    uint32_t H, const uint64_t *If, size_t NI, uint32_t d, uint64_t *Rf)
+static int infer_rs(orc_ctx *c, const uint64_t *featf, const uint64_t *thrf, const uint64_t *leaff,
+                    uint32_t H, const uint64_t *If, size_t NI, uint32_t d, uint64_t *Rf, const rowsel *rs)
 {
-    size_t N8 = pad8(NI), nint = ((size_t)1 << H) - 1, nleaf = (size_t)1 << H;
+    /* If holds the listed rows only (nr x d, row-major); NI is the size of the full batch */
+    size_t nr = rs_count(rs, NI), S8 = pad8(nr), nint = ((size_t)1 << H) - 1, nleaf = (size_t)1 << H;
     size_t wmax = nleaf > d ? nleaf : d;
     sh feat = sh_alloc(nint), thr = sh_alloc(nint), leaf = sh_alloc(nleaf);
-    sh IT = sh_alloc(d * N8), Tidx = sh_alloc(NI), f = sh_alloc(NI), th = sh_alloc(NI),
-       x = sh_alloc(NI), R = sh_alloc(NI), EA = sh_alloc(wmax * N8);
+    sh IT = sh_alloc(d * S8), Tidx = sh_alloc(nr), f = sh_alloc(nr), th = sh_alloc(nr),
+       x = sh_alloc(nr), R = sh_alloc(nr), EA = sh_alloc(wmax * S8);
     sh_from_flat(&feat, featf); if (thrf) sh_from_flat(&thr, thrf); sh_from_flat(&leaf, leaff);
     for (int j = 0; j < 3; j++)
-        for (size_t i = 0; i < NI; i++)
-            for (u32 k = 0; k < d; k++) IT.c[j][k * N8 + i] = If[(size_t)j * NI * d + i * d + k];
+        for (size_t r = 0; r < nr; r++)
+            for (u32 k = 0; k < d; k++) IT.c[j][k * S8 + r] = If[(size_t)j * nr * d + r * d + k];
     for (u32 n = 0; n < H; n++) {
         size_t w = (size_t)1 << n, base = w - 1;
         u32 op = c->op++;
-        eq_grid(c, op, &Tidx, base, w, NI, NULL, &EA);
-        dot_common(c, op, 2, &EA, &feat, base, w, NI, &f);
-        if (thrf) dot_common(c, op, 3, &EA, &thr, base, w, NI, &th);
-        wire_reshare(c, NI, thrf ? 2 : 1);
+        eq_grid_rs(c, op, &Tidx, base, w, NI, NULL, &EA, rs);
+        dot_common_rs(c, op, 2, &EA, &feat, base, w, NI, &f, rs);
+        if (thrf) dot_common_rs(c, op, 3, &EA, &thr, base, w, NI, &th, rs);
+        wire_reshare(c, nr, thrf ? 2 : 1);
         op = c->op++;
-        eq_grid(c, op, &f, 0, d, NI, NULL, &EA);
-        dot_rows(c, op, 2, &EA, &IT, d, NI, &x);
-        wire_reshare(c, NI, 1);
+        eq_grid_rs(c, op, &f, 0, d, NI, NULL, &EA, rs);
+        dot_rows_rs(c, op, 2, &EA, &IT, d, NI, &x, rs);
+        wire_reshare(c, nr, 1);
         if (thrf) {
             op = c->op++;
 #pragma omp parallel for schedule(static)
-            for (size_t i = 0; i < NI; i++) {
+            for (size_t r = 0; r < nr; r++) {
+                size_t i = rs_row(rs, r);
                 u64 v[3], g[3], b[3]; dealer_t D;
-                for (int j = 0; j < 3; j++) v[j] = th.c[j][i] - x.c[j][i];
+                for (int j = 0; j < 3; j++) v[j] = th.c[j][r] - x.c[j][r];
                 dealer(c, op, i, &D);
                 ge_el(c, op, i, v, &D, g);     /* [threshold >= value] */
                 g[0] ^= 1;                     /* [value > threshold] */
                 b2a_el(g, &D, b);
-                sh_set(&x, i, b);
+                sh_set(&x, r, b);
             }
-            wire_ge(c, NI); wire_b2a(c, NI);
+            wire_ge(c, nr); wire_b2a(c, nr);
         }
         for (int j = 0; j < 3; j++)
-            for (size_t i = 0; i < NI; i++)
-                Tidx.c[j][i] = 2 * Tidx.c[j][i] + x.c[j][i] + (j == 0 ? 1 : 0);
+            for (size_t r = 0; r < nr; r++)
+                Tidx.c[j][r] = 2 * Tidx.c[j][r] + x.c[j][r] + (j == 0 ? 1 : 0);
     }
     u32 op = c->op++;
-    eq_grid(c, op, &Tidx, nleaf - 1, nleaf, NI, NULL, &EA);
-    dot_common(c, op, 2, &EA, &leaf, 0, nleaf, NI, &R);
-    wire_reshare(c, NI, 1);
+    eq_grid_rs(c, op, &Tidx, nleaf - 1, nleaf, NI, NULL, &EA, rs);
+    dot_common_rs(c, op, 2, &EA, &leaf, 0, nleaf, NI, &R, rs);
+    wire_reshare(c, nr, 1);
     sh_to_flat(&R, Rf);
     sh_free(&feat); sh_free(&thr); sh_free(&leaf); sh_free(&IT); sh_free(&Tidx); sh_free(&f);
     sh_free(&th); sh_free(&x); sh_free(&R); sh_free(&EA);
     return 0;
+}
+
+int orc_infer_batch(orc_ctx *c, const uint64_t *featf, const uint64_t *thrf, const uint64_t *leaff,
+                    uint32_t H, const uint64_t *If, size_t NI, uint32_t d, uint64_t *Rf)
+{
+    return infer_rs(c, featf, thrf, leaff, H, If, NI, d, Rf, NULL);
+}
+
+/* The same protocol for the listed rows of a batch of NI instances: I holds those rows
+ * only (nrows x d), R receives nrows results.  Shares equal those of the full run. */
+int orc_infer_rows(orc_ctx *c, const uint64_t *featf, const uint64_t *thrf, const uint64_t *leaff,
+                   uint32_t H, const uint64_t *If, size_t NI, uint32_t d, const size_t *rows,
+                   size_t nrows, uint64_t *Rf)
+{
+    rowsel rs = { rows, nrows };
+    return infer_rs(c, featf, thrf, leaff, H, If, NI, d, Rf, &rs);
 }

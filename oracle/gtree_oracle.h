@@ -111,6 +111,12 @@ int orc_train_import(orc_train *, uint32_t h, const uint64_t *M, const uint64_t 
 int orc_infer_batch(orc_ctx *, const uint64_t *feat, const uint64_t *thr, const uint64_t *leaf,
                     uint32_t H, const uint64_t *I, size_t NI, uint32_t d, uint64_t *R);
 
+/* Sampled rows of a large batch: I holds the listed rows only (nrows x d comps, row-major),
+ * rows[] their indices in the batch of NI instances, R receives nrows comps. */
+int orc_infer_rows(orc_ctx *, const uint64_t *feat, const uint64_t *thr, const uint64_t *leaf,
+                   uint32_t H, const uint64_t *I, size_t NI, uint32_t d, const size_t *rows,
+                   size_t nrows, uint64_t *R);
+
 #ifdef __cplusplus
 }
 #endif

@@ -74,6 +74,7 @@ def _load():
         "orc_train_export": (i, [vp, i, _u64p]),
         "orc_train_import": (i, [vp, u32, _u64p, _u64p, _u64p, _u64p, _u64p]),
         "orc_infer_batch": (i, [vp, _u64p, _u64p, _u64p, u32, _u64p, sz, u32, _u64p]),
+        "orc_infer_rows": (i, [vp, _u64p, _u64p, _u64p, u32, _u64p, sz, u32, C.POINTER(C.c_size_t), sz, _u64p]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -276,4 +277,17 @@ class Oracle:
                                     _p(R.reshape(-1)))
         if rc:
             raise RuntimeError("orc_infer_batch -> %d" % rc)
+        return R
+
+    def infer_rows(self, feat, thr, leaf, H, I_rows, NI, d, rows):
+        """I_rows: (3, len(rows)*d) components of the listed rows of a batch of NI instances."""
+        feat, leaf, I_rows = self._c(feat), self._c(leaf), self._c(I_rows)
+        thr = None if thr is None else self._c(thr)
+        rows = np.ascontiguousarray(rows, dtype=np.uintp)
+        R = np.zeros((3, rows.size), dtype=np.uint64)
+        rc = self.L.orc_infer_rows(self.ctx, _p(feat.reshape(-1)), None if thr is None else _p(thr.reshape(-1)),
+                                   _p(leaf.reshape(-1)), H, _p(I_rows.reshape(-1)), NI, d,
+                                   rows.ctypes.data_as(C.POINTER(C.c_size_t)), rows.size, _p(R.reshape(-1)))
+        if rc:
+            raise RuntimeError("orc_infer_rows -> %d" % rc)
         return R

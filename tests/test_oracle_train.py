@@ -225,3 +225,20 @@ def test_inference_depth0_and_single_instance(seed):
     I = o.share(np.array([1, 0], dtype=np.uint64))
     R = o.infer(feat, None, leaf, 0, I, 1, 2)
     assert Oracle.rec(R).tolist() == [3]
+
+
+@pytest.mark.parametrize("binary", [False, True])
+def test_sampled_rows_equal_full_inference(seed, binary):
+    """The row-subset mode used for spot checks of large batches gives the same shares."""
+    w = wl.c4_infer(NI=203, H=4, binary=binary)
+    oa, ob = Oracle(seed), Oracle(seed)
+    parts = [w["feat"], w["leaf"]] + ([] if binary else [w["thr"]])
+    sa = [oa.share(a) for a in parts]
+    sb = [ob.share(a) for a in parts]
+    Ia, Ib = oa.share(w["I"].reshape(-1)), ob.share(w["I"].reshape(-1))
+    full = oa.infer(sa[0], None if binary else sa[2], sa[1], w["H"], Ia, w["NI"], w["d"])
+    rows = np.array([0, 7, 8, 100, 202])
+    Irows = Ib.reshape(3, w["NI"], w["d"])[:, rows, :].reshape(3, -1)
+    part = ob.infer_rows(sb[0], None if binary else sb[2], sb[1], w["H"], Irows, w["NI"], w["d"], rows)
+    assert np.array_equal(part, full[:, rows])
+    assert oa.op_counter() == ob.op_counter()
