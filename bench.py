@@ -19,6 +19,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
+EQ_ALU_OPS = 800                # algorithmic 32-bit ALU ops per equality test, three parties
+EQ_HBM_BYTES_MEASURED = 40.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
 
 
 def paper_shapes(np, torch, gtree, wl):
@@ -100,7 +102,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--samples", type=int, default=1000000, help="training samples (C5: 10^6)")
     ap.add_argument("--instances", type=int, default=1000000, help="inference batch (C5: 10^6)")
-    ap.add_argument("--cpu-samples", type=int, default=250000, help="oracle sample for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-samples", type=int, default=500000, help="oracle sample for cpu_baseline (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the C3 training / C4 inference timings")
     ap.add_argument("--micro", action="store_true",
@@ -210,22 +212,31 @@ def main():
         eq_ms, eq_l = prof["eqgrid"]
         cnt_ms, cnt_l = prof["count"]
         macs = 3 * 2 * N * ((1 << h) * CW + (1 << (h + 1)) * K)         # ring MACs per step, all parties
+        eq_per_launch = n_eq * k / max(eq_l, 1)
         kern = {
-            "eqgrid": {"bound": "hbm", "achieved": 200.0 * n_eq * k / (eq_ms / 1e3) / 1e9, "peak": HBM_PEAK_GBS,
-                       "unit": "GB/s", "traffic": None,
-                       "note": "200 B of message traffic per equality test (3 parties, write + read), %d tests/step" % n_eq,
+            "eqgrid": {"bound": "alu", "achieved": EQ_ALU_OPS * n_eq * k / (eq_ms / 1e3) / 1e12, "peak": LANE_OPS_PEAK,
+                       "unit": "Tops/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
+                       "note": "%d 32-bit ALU ops per equality test for the three parties (PRF blocks + protocol, derived in "
+                               "DESIGN.md); peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; traffic = measured HBM bytes per "
+                               "test (profiles/pmc_traffic_micro.md) x tests per launch; %d tests/step" % (EQ_ALU_OPS, n_eq),
                        "avg_launch_ms": eq_ms / max(eq_l, 1), "launches_per_step": eq_l // k,
                        "eq_tests_per_s": n_eq * k / (eq_ms / 1e3)},
-            "count": {"bound": "alu", "achieved": 4.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": LANE_OPS_PEAK,
-                      "unit": "Tops/s", "traffic": None,
-                      "note": "ring MAC = 3 32-bit multiplies + 64-bit add, counted as 4 lane-ops; %d MACs/step" % macs,
+            "eqgrid_message_bytes_view": {"bound": "hbm", "achieved": 200.0 * n_eq * k / (eq_ms / 1e3) / 1e9,
+                                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
+                                          "note": "200 B of protocol messages per test (3 parties, written and read once); "
+                                                  "the messages stay in L2, so this is not the binding limit"},
+            "count": {"bound": "mfma", "achieved": 72.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": 5000.0,
+                      "unit": "TOP/s", "traffic": None,
+                      "note": "ring MAC = 36 int8 limb products on the matrix cores = 72 int8 ops; int8 dense peak 5.0 POP/s; "
+                              "%d ring MACs/step" % macs,
                       "avg_launch_ms": cnt_ms / max(cnt_l, 1), "launches_per_step": cnt_l // k},
         }
         for v in kern.values():
             v["frac"] = v["achieved"] / v["peak"]
-        out["roofline"] = dict(kern[dom] if dom in kern else kern["eqgrid"], kernel=dom if dom in kern else "eqgrid")
+        dom = dom if dom in kern else "eqgrid"
+        out["roofline"] = dict(kern[dom], kernel=dom)
         out["kernel_classes_ms_per_step"] = {c: prof[c][0] / k for c in prof}
-        out["roofline_other"] = {c: v for c, v in kern.items() if c != out["roofline"]["kernel"]}
+        out["roofline_other"] = {c: v for c, v in kern.items() if c != dom}
 
     if not args.no_paper_shapes:
         out["paper_shape_workloads"] = paper_shapes(np, torch, gtree, wl)

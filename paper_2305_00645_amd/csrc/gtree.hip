@@ -353,7 +353,9 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
             a.dacc = c->dacc;
             HIPCHK(hipMemsetAsync(c->dacc, 0, (size_t)3 * ndot * a.N8 * 8, c->stream));
         }
-        dim3 g((unsigned)std::min<u64>(ntile * a.nkc, GT_MAX_BLOCKS));
+        // persistent workgroups: no more than fit on the device, so that the message regions
+        // they keep rewriting stay in L2; each walks over its share of the work items
+        dim3 g((unsigned)std::min<u64>(ntile * a.nkc, g_resident));
         int rc;
         if (mode == GM_STORE && has_g) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, true, 1>, g, GT_BLOCK, a);
         else if (mode == GM_STORE) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, false, 1>, g, GT_BLOCK, a);
@@ -361,7 +363,7 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
         else if (mode == GM_COMMON) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_COMMON, false, 1>, g, GT_BLOCK, a);
         else rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_ROWS, false, 1>, g, GT_BLOCK, a);
         GTCHK(rc);
-        if (a.dacc) GTCHK(launch(c, GT_KC_EQGRID, k_dot_fin, dim3(tiles8(a.N8)), GT_BLOCK, a));
+        if (a.dacc) GTCHK(launch(c, GT_KC_SMALL, k_dot_fin, dim3(tiles8(a.N8)), GT_BLOCK, a));
     }
     acct_eq(c, nel);
     if (has_g) acct_and1(c, nel);
