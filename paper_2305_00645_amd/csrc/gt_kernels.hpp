@@ -885,8 +885,15 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 #define CT_CHUNK_BLOCKS 128          // 128 blocks of 32 samples per workgroup
-struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 colbase; u64 *Zacc; u32 nchunk, nrowgrp, ncg; };
+// bcol0: first column (row of B) of this launch, zcol0: its column in the output
+struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg; };
 
+// Workgroup = 4 wavefronts = 128 rows x (32*NB) columns; NB = 2 for full groups of 64
+// columns, NB = 1 for a remainder of at most 32.  The kernel is limited by the rate at
+// which the L1 cache can fetch the two operands (about 24 KB per wavefront and
+// product), not by the matrix cores; the operands of the next product are in flight
+// while the current one is multiplied.
+template <int NB>
 __global__ __launch_bounds__(256) void k_count(CountArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -899,36 +906,36 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
     const u32 ncg = a.ncg, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
     const u32 cg = slot % ncg, chunk = (slot / ncg) * 8 + xcd;
     if (chunk >= a.nchunk) return;
-    const u64 c0 = a.colbase + (u64)cg * 64;
+    const u64 c0 = a.bcol0 + (u64)cg * (32 * NB);
     const u64 ib0 = (u64)chunk * CT_CHUNK_BLOCKS;
     const u64 ib1 = ib0 + CT_CHUNK_BLOCKS < a.nblk ? ib0 + CT_CHUNK_BLOCKS : a.nblk;
-    const u32 lr = lane & 31, lg = (lane >> 5) * 16;
-    v16i acc[8][2];
+    const u32 lr = lane & 31;
+    v16i acc[8][NB];
 #pragma unroll
     for (int u = 0; u < 8; u++)
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++)
+        for (int nb = 0; nb < NB; nb++)
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[u][nb][v] = 0;
-    // two register sets: the operands of the next product are in flight while the
-    // matrix cores work on the current one (product 0: (L_p + L_{p+1}) x B_p, 1: L_p x B_{p+1})
+    // product 0: (L_p + L_{p+1}) x B_p, product 1: L_p x B_{p+1}
     const LimbMat LA0 = p == 0 ? a.L.m[0][0] : (p == 1 ? a.L.m[1][0] : a.L.m[2][0]);
     const LimbMat LA1 = p == 0 ? a.L.m[0][1] : (p == 1 ? a.L.m[1][1] : a.L.m[2][1]);
     const LimbMat LB0 = p == 0 ? a.B.m[0][0] : (p == 1 ? a.B.m[1][0] : a.B.m[2][0]);
     const LimbMat LB1 = p == 0 ? a.B.m[0][1] : (p == 1 ? a.B.m[1][1] : a.B.m[2][1]);
-    v4i av0[8], bv0[2][8], av1[8], bv1[2][8];
+    // addresses = wave-uniform base (scalar registers) + a 32-bit lane offset
+    const u32 offA = (u32)((r0 + lr) * 32 + (lane >> 5) * 16), offB = (u32)(lr * 32 + (lane >> 5) * 16);
+    v4i av0[8], bv0[NB][8], av1[8], bv1[NB][8];
 #define CT_LOAD(AV, BV, LA, LB, IB)                                                           \
     _Pragma("unroll") for (int s = 0; s < 8; s++) {                                           \
-        AV[s] = *(const v4i *)(LA.base + limb_addr(LA, IB, s, r0 + lr) + lg);                 \
-        BV[0][s] = *(const v4i *)(LB.base + limb_addr(LB, IB, s, c0 + lr) + lg);              \
-        BV[1][s] = *(const v4i *)(LB.base + limb_addr(LB, IB, s, c0 + 32 + lr) + lg);         \
+        AV[s] = *(const v4i *)(LA.base + limb_addr(LA, IB, s, 0) + offA);                     \
+        _Pragma("unroll") for (int nb = 0; nb < NB; nb++)                                     \
+            BV[nb][s] = *(const v4i *)(LB.base + limb_addr(LB, IB, s, c0 + nb * 32) + offB);  \
     }
 #define CT_MMA(AV, BV)                                                                        \
     _Pragma("unroll") for (int u = 0; u < 8; u++)                                             \
-        _Pragma("unroll") for (int s = 0; s <= u; s++) {                                      \
-            acc[u][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[0][u - s], acc[u][0], 0, 0, 0); \
-            acc[u][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[1][u - s], acc[u][1], 0, 0, 0); \
-        }
+        _Pragma("unroll") for (int s = 0; s <= u; s++)                                        \
+            _Pragma("unroll") for (int nb = 0; nb < NB; nb++)                                 \
+                acc[u][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[nb][u - s], acc[u][nb], 0, 0, 0);
     CT_LOAD(av0, bv0, LA0, LB0, ib0)
     for (u64 ib = ib0; ib < ib1; ib++) {
         CT_LOAD(av1, bv1, LA1, LB1, ib)
@@ -940,11 +947,11 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
 #undef CT_MMA
     u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
 #pragma unroll
-    for (int nb = 0; nb < 2; nb++)
+    for (int nb = 0; nb < NB; nb++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
             const u64 r = r0 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-            const u64 c = (u64)cg * 64 + nb * 32 + lr;
+            const u64 c = a.zcol0 + (u64)cg * (32 * NB) + nb * 32 + lr;
             u64 z = 0;
 #pragma unroll
             for (int u = 0; u < 8; u++) z += (u64)(long long)acc[u][nb][v] << (8 * u);

@@ -353,9 +353,8 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
             a.dacc = c->dacc;
             HIPCHK(hipMemsetAsync(c->dacc, 0, (size_t)3 * ndot * a.N8 * 8, c->stream));
         }
-        // persistent workgroups: no more than fit on the device, so that the message regions
-        // they keep rewriting stay in L2; each walks over its share of the work items
-        dim3 g((unsigned)std::min<u64>(ntile * a.nkc, g_resident));
+        // more workgroups than fit at once: the hardware balances them over the compute units
+        dim3 g((unsigned)std::min<u64>(ntile * a.nkc, GT_MAX_BLOCKS));
         int rc;
         if (mode == GM_STORE && has_g) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, true, 1>, g, GT_BLOCK, a);
         else if (mode == GM_STORE) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, false, 1>, g, GT_BLOCK, a);
@@ -529,13 +528,20 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     const u64 colbase = totals_only ? dK : 0;
     const u32 op = c->op++;
     HIPCHK(hipMemsetAsync(t->Zacc, 0, 3 * nh * ncol * 8, c->stream));
-    CountArgs a{}; a.L = limbs_L(t); a.B = limbs_B(t); a.nblk = t->nblk; a.nh = (u32)nh; a.ncol = ncol; a.colbase = colbase;
+    CountArgs a{}; a.L = limbs_L(t); a.B = limbs_B(t); a.nblk = t->nblk; a.nh = (u32)nh; a.ncol = ncol;
     a.Zacc = t->Zacc;
     a.nchunk = (u32)((t->nblk + CT_CHUNK_BLOCKS - 1) / CT_CHUNK_BLOCKS);
     a.nrowgrp = (u32)((nh + 127) / 128);
-    a.ncg = (ncol + 63) / 64;
-    dim3 g(((a.nchunk + 7) / 8) * a.ncg * 8, 1, 3 * a.nrowgrp);
-    GTCHK(launch(c, GT_KC_COUNT, k_count, g, B256, a));
+    // groups of 64 columns; a remainder of at most 32 columns runs with a 32-wide tile
+    const u32 rem = ncol % 64, nfull = ncol / 64 + (rem > 32 ? 1 : 0);
+    if (nfull) {
+        a.ncg = nfull; a.bcol0 = colbase; a.zcol0 = 0;
+        GTCHK(launch(c, GT_KC_COUNT, k_count<2>, dim3(((a.nchunk + 7) / 8) * a.ncg * 8, 1, 3 * a.nrowgrp), B256, a));
+    }
+    if (rem && rem <= 32) {
+        a.ncg = 1; a.bcol0 = colbase + (u64)nfull * 64; a.zcol0 = nfull * 64;
+        GTCHK(launch(c, GT_KC_COUNT, k_count<1>, dim3(((a.nchunk + 7) / 8) * 8, 1, 3 * a.nrowgrp), B256, a));
+    }
     CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
     GTCHK(launch(c, GT_KC_SMALL, k_count_fin, dim3(tiles(f.n)), GT_BLOCK, f));
     acct_reshare(c, nh * ncol, 1);
