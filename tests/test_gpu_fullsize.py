@@ -97,3 +97,66 @@ def test_c5_inference_full_size(seed):
     assert o.op_counter() == g.op_counter()
     tree.close(); g.close(); o.close()
     torch.cuda.empty_cache()
+
+
+def test_c3_full_training(seed):
+    """Census-shaped workload at full size: 48,842 samples x 294 candidate columns, depth 7,
+    every exported share of the last level and of the finished tree against the oracle."""
+    import torch
+    from oracle import Oracle, X_M, X_C, X_SD, X_SCORE, X_F, X_T, X_GAMMA
+    from paper_2305_00645_amd import gtree, workloads as wl
+    w = wl.c3_train()
+    N, d, K, H = w["N"], w["d"], w["K"], w["H"]
+    assert (N, d, H) == (48842, 294, 7)
+    o, g = Oracle(seed, K=K), gtree.GTree(seed, K=K)
+    xg, yg = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+    g.train_create(xg, yg, N, d, H)
+    xo, yo = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
+    o.train_create(xo, yo, N, d, H)
+    for h in range(H):
+        g.train_level(h)
+        o.train_level(h)
+        for what, name in ((X_SD, "SD"), (X_C, "C")):
+            _same(g.train_export(what), o.train_export(what), "level %d %s" % (h, name))
+    for what, name in ((X_M, "M"), (X_SCORE, "score"), (X_F, "F"), (X_GAMMA, "gamma")):
+        _same(g.train_export(what), o.train_export(what), name)
+    fo, lo = o.train_finish()
+    tree = g.train_finish()
+    fg, lg = tree.export()
+    _same(fg, fo, "tree features")
+    _same(lg, lo, "tree labels")
+    _same(g.train_export(X_T), o.train_export(X_T), "T")
+    ro, wo = o.stats()
+    rg, wg, _ = g.stats()
+    assert ro == rg and np.array_equal(wo, wg) and o.op_counter() == g.op_counter()
+    # the tree is the plaintext fixed-point Gini CART of the same data
+    import plain_cart
+    ref = plain_cart.train(w["X"], w["y"], K, H, 16)
+    assert np.array_equal(g.rec(g.train_export(X_T)).astype(np.int64), ref["T"])
+    tree.close(); g.close(); o.close()
+    torch.cuda.empty_cache()
+
+
+def test_c4_full_inference(seed):
+    """The 10^4-instance depth-7 batch with thresholds, every share against the oracle."""
+    import plain_cart
+    from oracle import Oracle
+    from paper_2305_00645_amd import gtree, workloads as wl
+    w = wl.c4_infer()
+    NI, d, H = w["NI"], w["d"], w["H"]
+    assert (NI, d, H) == (10000, 16, 7)
+    o, g = Oracle(seed), gtree.GTree(seed)
+    fo, to, lo = o.share(w["feat"]), o.share(w["thr"]), o.share(w["leaf"])
+    fg, tg, lg = g.share_a(w["feat"]), g.share_a(w["thr"]), g.share_a(w["leaf"])
+    Io, Ig = o.share(w["I"].reshape(-1)), g.share_a(w["I"].reshape(-1))
+    tree = g.tree_import(fg, tg, lg, H)
+    Ro = o.infer(fo, to, lo, H, Io, NI, d)
+    Rg = g.infer_batch(tree, Ig, NI, d)
+    _same(Rg, Ro, "inference")
+    T = np.concatenate([w["feat"], w["leaf"]]).astype(np.int64)
+    thr = np.concatenate([w["thr"], np.zeros(1 << H, dtype=np.uint64)])
+    assert np.array_equal(g.rec(Rg).astype(np.int64), plain_cart.predict(T, H, w["I"], thr))
+    ro, wo = o.stats()
+    rg, wg, _ = g.stats()
+    assert ro == rg and np.array_equal(wo, wg)
+    tree.close(); g.close(); o.close()
