@@ -317,3 +317,24 @@ def test_single_level_from_imported_state(mods, seed):
             assert C[r, d * K + c] == (sel & (y == c)).sum()
             assert np.array_equal(C[r, :d * K].reshape(d, K)[:, c], X[sel & (y == c)].sum(axis=0))
     same_stats(o, g)
+
+
+def test_launch_and_message_pattern_is_data_independent(mods, seed):
+    """Only sizes and depth may show (Sec. I, goals): two data sets of the same shape give
+    the same operation count, rounds, wire bytes and kernel launches per class."""
+    Oracle, gtree = mods
+    from paper_2305_00645_amd import workloads as wl
+    seen = []
+    for s in (21, 22):
+        w = wl.c1_train(N=300, d=7, depth=3, seed=s)
+        g = gtree.GTree(seed, K=2, profile=True)
+        g.train_create(g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1)), 300, 7, 3)
+        for h in range(3):
+            g.train_level(h)
+        tree = g.train_finish()
+        g.infer_batch(tree, g.share_a(w["X"].reshape(-1)), 300, 7)
+        rounds, wire, _ = g.stats()
+        seen.append((g.op_counter(), rounds, wire.tolist(), {k: v[1] for k, v in g.prof().items()}))
+        tree.close(); g.close()
+    assert seen[0] == seen[1]
+    assert seen[0][3]["eqgrid"] > 0 and seen[0][3]["count"] > 0
