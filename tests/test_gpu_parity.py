@@ -338,3 +338,25 @@ def test_launch_and_message_pattern_is_data_independent(mods, seed):
         tree.close(); g.close()
     assert seen[0] == seen[1]
     assert seen[0][3]["eqgrid"] > 0 and seen[0][3]["count"] > 0
+
+
+def test_context_on_a_side_stream(mods, seed):
+    """The library enqueues on the stream it is given (default priority)."""
+    import torch
+    Oracle, gtree = mods
+    o = Oracle(seed)
+    st = torch.cuda.Stream()
+    rng = np.random.default_rng(9)
+    x = rng.integers(0, M64, size=3000, dtype=np.uint64)
+    y = rng.integers(0, M64, size=3000, dtype=np.uint64)
+    with torch.cuda.stream(st):
+        g = gtree.GTree(seed, stream=st)
+        xg, yg = g.share_a(x), g.share_a(y)
+        zg = g.mult(xg, yg)
+        ug = g.oaa(g.share_a(x[:37]), g.share_a(np.arange(500, dtype=np.uint64) % 40))
+        st.synchronize()
+        zo = o.mult(o.share(x), o.share(y))
+        uo = o.oaa(o.share(x[:37]), o.share(np.arange(500, dtype=np.uint64) % 40))
+        same(zg, zo, "mult on side stream")
+        same(ug, uo, "oaa on side stream")
+        g.close()
