@@ -886,7 +886,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 #define CT_CHUNK_BLOCKS 128          // 128 blocks of 32 samples per workgroup
 // bcol0: first column (row of B) of this launch, zcol0: its column in the output
-struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg; };
+// rt: row tiles of 32 per workgroup (4, 2 or 1); the other 4/rt wavefronts take further column tiles
+// chunkblk: sample blocks of 32 per workgroup (at most CT_CHUNK_BLOCKS, the int32 accumulator bound)
+struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles; };   // ncoltiles: column tiles of 32*NB in this launch
 
 // Workgroup = 4 wavefronts = 128 rows x (32*NB) columns; NB = 2 for full groups of 64
 // columns, NB = 1 for a remainder of at most 32.  The kernel is limited by the rate at
@@ -898,7 +900,8 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p = blockIdx.z / a.nrowgrp, rg = blockIdx.z % a.nrowgrp;
-    const u64 r0 = (u64)rg * 128 + wave * 32;
+    const u32 wr = wave % a.rt, wc = wave / a.rt, cper = 4 / a.rt;   // this wavefront's row / column tile
+    const u64 r0 = ((u64)rg * a.rt + wr) * 32;
     if (r0 >= a.nh) return;                                   // whole wavefront, no barrier in this kernel
     // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The column
     // groups of one sample chunk read the same rows of L, so they are given
@@ -906,9 +909,11 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
     const u32 ncg = a.ncg, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
     const u32 cg = slot % ncg, chunk = (slot / ncg) * 8 + xcd;
     if (chunk >= a.nchunk) return;
-    const u64 c0 = a.bcol0 + (u64)cg * (32 * NB);
-    const u64 ib0 = (u64)chunk * CT_CHUNK_BLOCKS;
-    const u64 ib1 = ib0 + CT_CHUNK_BLOCKS < a.nblk ? ib0 + CT_CHUNK_BLOCKS : a.nblk;
+    const u64 ctile = (u64)cg * cper + wc;                   // column tile of 32*NB
+    if (ctile >= a.ncoltiles) return;                         // whole wavefront
+    const u64 c0 = a.bcol0 + ctile * (32 * NB);
+    const u64 ib0 = (u64)chunk * a.chunkblk;
+    const u64 ib1 = ib0 + a.chunkblk < a.nblk ? ib0 + a.chunkblk : a.nblk;
     const u32 lr = lane & 31;
     v16i acc[8][NB];
 #pragma unroll
@@ -951,7 +956,7 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
             const u64 r = r0 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-            const u64 c = a.zcol0 + (u64)cg * (32 * NB) + nb * 32 + lr;
+            const u64 c = a.zcol0 + ctile * (32 * NB) + nb * 32 + lr;
             u64 z = 0;
 #pragma unroll
             for (int u = 0; u < 8; u++) z += (u64)(long long)acc[u][nb][v] << (8 * u);

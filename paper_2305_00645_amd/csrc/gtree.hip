@@ -530,16 +530,27 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     HIPCHK(hipMemsetAsync(t->Zacc, 0, 3 * nh * ncol * 8, c->stream));
     CountArgs a{}; a.L = limbs_L(t); a.B = limbs_B(t); a.nblk = t->nblk; a.nh = (u32)nh; a.ncol = ncol;
     a.Zacc = t->Zacc;
-    a.nchunk = (u32)((t->nblk + CT_CHUNK_BLOCKS - 1) / CT_CHUNK_BLOCKS);
-    a.nrowgrp = (u32)((nh + 127) / 128);
+    // wavefront arrangement: 4, 2 or 1 row tiles of 32 per workgroup, the rest over columns
+    a.rt = nh > 64 ? 4 : (nh > 32 ? 2 : 1);
+    a.nrowgrp = (u32)((nh + 32 * a.rt - 1) / (32 * a.rt));
+    const u32 cper = 4 / a.rt;
     // groups of 64 columns; a remainder of at most 32 columns runs with a 32-wide tile
     const u32 rem = ncol % 64, nfull = ncol / 64 + (rem > 32 ? 1 : 0);
+    const u32 ncg2 = (nfull + cper - 1) / cper, ncg1 = (rem && rem <= 32) ? 1 : 0;
+    // sample chunk per workgroup: as long as the int32 accumulators allow, shorter when
+    // that is needed to give every compute unit several workgroups
+    const u64 wgs_per_chunk = (u64)(ncg2 + ncg1) * 3 * a.nrowgrp;
+    u64 want_chunks = (4ull * g_resident / 4 + wgs_per_chunk - 1) / wgs_per_chunk;
+    u64 cb = (t->nblk + want_chunks - 1) / want_chunks;
+    cb = std::max<u64>(8, std::min<u64>(CT_CHUNK_BLOCKS, cb));
+    a.chunkblk = (u32)cb;
+    a.nchunk = (u32)((t->nblk + cb - 1) / cb);
     if (nfull) {
-        a.ncg = nfull; a.bcol0 = colbase; a.zcol0 = 0;
+        a.ncg = ncg2; a.ncoltiles = nfull; a.bcol0 = colbase; a.zcol0 = 0;
         GTCHK(launch(c, GT_KC_COUNT, k_count<2>, dim3(((a.nchunk + 7) / 8) * a.ncg * 8, 1, 3 * a.nrowgrp), B256, a));
     }
-    if (rem && rem <= 32) {
-        a.ncg = 1; a.bcol0 = colbase + (u64)nfull * 64; a.zcol0 = nfull * 64;
+    if (ncg1) {
+        a.ncg = 1; a.ncoltiles = 1; a.bcol0 = colbase + (u64)nfull * 64; a.zcol0 = nfull * 64;
         GTCHK(launch(c, GT_KC_COUNT, k_count<1>, dim3(((a.nchunk + 7) / 8) * 8, 1, 3 * a.nrowgrp), B256, a));
     }
     CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
