@@ -47,7 +47,7 @@ def paper_shapes(np, torch, gtree, wl):
     tm = sorted(times)[len(times) // 2]
     ncand = sum((1 << h) * d for h in range(H))
     res["c3_train_depth7"] = {"samples": N, "columns": d, "seconds": tm, "candidates_per_s": ncand / tm,
-                              "last_level_candidates_per_s": (1 << (H - 1)) * d / per_level[-1]}
+                              "candidates_per_s_per_level": [(1 << h) * d / per_level[h] for h in range(H)]}
     g.close(); del g, X, Y
     wi = wl.c4_infer()
     g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=2)
