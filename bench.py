@@ -19,8 +19,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
-EQ_ALU_OPS = 800                # algorithmic 32-bit ALU ops per equality test, three parties
+EQ_ALU_OPS = 800                # algorithmic 32-bit ALU ops per equality test, three parties: one dealer ChaCha8 block (400 ops) + 3 mask blocks per 8 tests = 550, protocol steps 3 x 85
 EQ_HBM_BYTES_MEASURED = 93.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
+
+
+def paper_literal_ol_bytes(N, d, K, h, H, l=64):
+    """Per-party bytes of the learning protocol of one level if it were run as printed in the paper
+    (Sec. V-A cost formulas: equality test (2l-1) bits, array access (4l-1) bits per array element,
+    hence 2l bits per element for the select step): array access over the whole tree array of
+    2^H - 1 entries and over the d feature values for every sample, the leaf-flag equality grid, and
+    the per-sample select over n_h counter arrays of (1+K) x 2d entries."""
+    nh = 1 << h
+    bits = 0
+    if h > 0:
+        bits += N * ((1 << H) - 1) * (4 * l - 1) + N * d * (4 * l - 1)
+    bits += nh * (2 * l - 1) + N * nh * (2 * l - 1) + N * nh
+    bits += N * nh * (1 + K) * 2 * d * 2 * l
+    return bits / 8.0
 
 
 def paper_shapes(np, torch, gtree, wl):
@@ -168,6 +183,17 @@ def main():
     total = time.perf_counter() - T0
     k = args.steps
     ms = {a: 1e3 * b / k for a, b in t.items()}
+    # message volume of one split-scoring level (counted by the library) beside the unfused protocol
+    lvl_msgs = None
+    if not args.no_roofline:           # left out of runs made for a kernel trace: it repeats the level once more
+        g.train_import(h, st["M"], st["Tprev"], st["F"], st["C"], st["gamma"])
+        g.stats_reset()
+        g.train_level(h)
+        lvl_rounds, lvl_wire, _ = g.stats()
+        lvl_msgs = {"rounds": lvl_rounds, "bytes_sent_per_party": int(lvl_wire[0].sum()),
+                    "paper_literal_learning_bytes_per_party": paper_literal_ol_bytes(N, d, K, h, H),
+                    "note": "the library fuses select-and-accumulate into inner products with one reshare per "
+                            "output; the second figure prices the learning protocol as printed (analytic)"}
     ncand = (1 << h) * d
     value = ncand / (ms["level"] / 1e3)
     # sanity: predictions equal plaintext traversal on a sample of instances
@@ -192,6 +218,7 @@ def main():
         "breakdown_ms": {"a0_products": ms["a0"], "a1_a7_level": ms["level"], "a1_a2_a8_label_level": ms["finish"],
                          "b1_b5_inference": ms["infer"]},
         "inference_instances_per_s": NI / (ms["infer"] / 1e3), "inference_depth": Hinf,
+        "level_messages": lvl_msgs,
     }
 
     if not args.no_roofline:
@@ -216,8 +243,8 @@ def main():
         kern = {
             "eqgrid": {"bound": "alu", "achieved": EQ_ALU_OPS * n_eq * k / (eq_ms / 1e3) / 1e12, "peak": LANE_OPS_PEAK,
                        "unit": "Tops/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
-                       "note": "%d 32-bit ALU ops per equality test for the three parties (PRF blocks + protocol, derived in "
-                               "DESIGN.md); peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; traffic = measured HBM bytes per "
+                       "note": "%d 32-bit ALU ops per equality test for the three parties (PRF blocks + protocol); "
+                               "peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; traffic = measured HBM bytes per "
                                "test (profiles/pmc_traffic_micro.md) x tests per launch; %d tests/step" % (EQ_ALU_OPS, n_eq),
                        "avg_launch_ms": eq_ms / max(eq_l, 1), "launches_per_step": eq_l // k,
                        "eq_tests_per_s": n_eq * k / (eq_ms / 1e3)},
