@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
 EQ_ALU_OPS = 800                # algorithmic 32-bit ALU ops per equality test, three parties: one dealer ChaCha8 block (400 ops) + 3 mask blocks per 8 tests = 550, protocol steps 3 x 85
-EQ_HBM_BYTES_MEASURED = 93.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
+EQ_HBM_BYTES_MEASURED = 33.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
 
 
 def paper_literal_ol_bytes(N, d, K, h, H, l=64):
@@ -248,10 +248,10 @@ def main():
                                "test (profiles/pmc_traffic_micro.md) x tests per launch; %d tests/step" % (EQ_ALU_OPS, n_eq),
                        "avg_launch_ms": eq_ms / max(eq_l, 1), "launches_per_step": eq_l // k,
                        "eq_tests_per_s": n_eq * k / (eq_ms / 1e3)},
-            "eqgrid_message_bytes_view": {"bound": "hbm", "achieved": 200.0 * n_eq * k / (eq_ms / 1e3) / 1e9,
-                                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
-                                          "note": "200 B of protocol messages per test (3 parties, written and read once); "
-                                                  "the messages stay in L2, so this is not the binding limit"},
+            "eqgrid_hbm_view": {"bound": "hbm", "achieved": EQ_HBM_BYTES_MEASURED * n_eq * k / (eq_ms / 1e3) / 1e9,
+                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
+                                "note": "measured HBM bytes per test x tests/s: the protocol messages (200 B per test) pass "
+                                        "through LDS, HBM sees the operands and results only, so this is not the binding limit"},
             "count": {"bound": "mfma", "achieved": 72.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": 5000.0,
                       "unit": "TOP/s", "traffic": None,
                       "note": "ring MAC = 36 int8 limb products on the matrix cores = 72 int8 ops; int8 dense peak 5.0 POP/s; "

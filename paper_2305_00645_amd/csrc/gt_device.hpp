@@ -4,8 +4,9 @@
 // Execution model.  A workgroup is 3 wavefronts of 64 lanes: wavefront p IS party p
 // (threadIdx.y = p).  Lane l of each of the three wavefronts works on the same
 // element(s), each on its own party's two components.  A protocol message is a
-// store into the workgroup's region of the device-resident wire buffer; the
-// receiving wavefront loads it after a workgroup barrier.  A party's lanes never
+// store into the workgroup's message region (its part of the wire buffer in device
+// memory, or LDS in the kernels that carry most messages); the receiving wavefront
+// loads it after a workgroup barrier.  A party's lanes never
 // read another party's shares or keys, only the words sent to it.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -155,6 +156,37 @@ struct Wire {
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < NW; j++) rcv[j] = buf[(from * GT_XW + j) * GT_LANES + lane];
+    }
+    template <int NW>
+    __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }
+    template <int NW>
+    __device__ __forceinline__ void open(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 0 ? 2 : p - 1); }
+    __device__ __forceinline__ u64 reshare1(u64 v) { u64 s[1] = { v }, r[1]; reshare<1>(s, r); return r[0]; }
+    __device__ __forceinline__ u64 open1(u64 v) { u64 s[1] = { v }, r[1]; open<1>(s, r); return r[0]; }
+};
+
+// The same message exchange through a region of LDS of GT_LWIRE_WORDS words that the
+// workgroup owns: two alternating slots for messages of up to four words per lane; a
+// message of eight words takes the whole region (the caller separates it from its
+// neighbours by barriers of its own).
+#define GT_LWIRE_SLOT (3 * 4 * GT_LANES)
+#define GT_LWIRE_WORDS (2 * GT_LWIRE_SLOT)
+struct LWire {
+    u64 *base;
+    int slot, p, lane;
+    __device__ __forceinline__ void init(u64 *lds) { base = lds; slot = 0; p = threadIdx.y; lane = threadIdx.x; }
+    template <int NW>
+    __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
+    {
+        static_assert(NW <= 8, "message too wide");
+        constexpr int XW = NW <= 4 ? 4 : 8;
+        u64 *buf = NW <= 4 ? base + slot * GT_LWIRE_SLOT : base;
+        if (NW <= 4) slot ^= 1;
+#pragma unroll
+        for (int j = 0; j < NW; j++) buf[(p * XW + j) * GT_LANES + lane] = snd[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NW; j++) rcv[j] = buf[(from * XW + j) * GT_LANES + lane];
     }
     template <int NW>
     __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }

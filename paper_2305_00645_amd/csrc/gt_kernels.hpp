@@ -255,25 +255,31 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 
 // One-time products of the learning protocol (Sec. V-B): column col = k*K + c,
 // element e = col*N8 + i, z = XT[k][i] * YT[c][i] for i < N, written as limb tiles
-// (own component into B.m[p][0], next into B.m[p][1]).  blockIdx.y = column.
+// (own component into B.m[p][0], next into B.m[p][1]).  A step covers 16 groups of 8
+// samples of four adjacent columns (blockIdx.y = column quad): the four 32-byte pieces
+// that one wavefront writes per sample block and limb make up a whole 128-byte line
+// of the tile layout.
 struct XyArgs { KCommon c; P6 XT, YT; LimbSet B; u64 N, N8; u32 K, ncol; };
-__global__ __launch_bounds__(192) void k_xy(XyArgs a)
+__global__ __launch_bounds__(192, 3) void k_xy(XyArgs a)
 {
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
     const int p = threadIdx.y, lane = threadIdx.x;
-    Wire W; W.init2d(a.c.wire);
+    LWire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
-    const u64 ngrp = a.N8 / 8;
-    for (u64 col = blockIdx.y; col < a.ncol; col += gridDim.y) {
-        const u64 kx = col / a.K, cy = col % a.K;
-        for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
-            const u64 g = tile * GT_LANES + lane, i0 = g * 8;
-            const bool act = g < ngrp;
+    const u64 ngrp = a.N8 / 8, nq = (a.ncol + 3) / 4, nt = (ngrp + 15) / 16;
+    for (u64 q = blockIdx.y; q < nq; q += gridDim.y) {
+        const u64 colq = q * 4 + (lane >> 4);
+        const bool cok = colq < a.ncol;
+        const u64 col = cok ? colq : 0, kx = col / a.K, cy = col % a.K;
+        for (u64 tile = blockIdx.x; tile < nt; tile += gridDim.x) {
+            const u64 g = tile * 16 + (lane & 15), i0 = g * 8;
+            const bool act = cok && g < ngrp;
+            const u64 nv = act ? a.N : 0;               // rows start at multiples of 8
             u64 ao[8], an[8], snd[8], rcv[8];
             const u64 blk = (col * a.N8 + i0) >> 3;
             chacha8(K.own, blk, a.c.op, 0, ao);
             chacha8(K.nxt, blk, a.c.op, 0, an);
             u64 xo[8], xn[8], yo[8], yn[8];
-            const u64 nv = act ? a.N : 0;               // rows start at multiples of 8
             ld8(own_of(a.XT, p) + kx * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + kx * a.N8, i0, nv, xn);
             ld8(own_of(a.YT, p) + cy * a.N8, i0, nv, yo); ld8(nxt_of(a.YT, p) + cy * a.N8, i0, nv, yn);
 #pragma unroll
@@ -288,6 +294,7 @@ __global__ __launch_bounds__(192) void k_xy(XyArgs a)
                 store_limbs8(a.B.m[p][0], col, i0, snd);
                 store_limbs8(a.B.m[p][1], col, i0, rcv);
             }
+            __syncthreads();                            // the message region is rewritten next
         }
     }
 }
@@ -346,6 +353,7 @@ struct GridArgs {
     int epi;
     LimbSet L;      // GM_STORE: limb tiles of (own+next, own), row = column k
     u32 nkc, kchunk;// column ranges per tile and their length
+    int lgs;        // GM_STORE: log2 of the lanes that share a column in one step (6 or 4)
     u64 *dacc;      // [2][3][N8] partial inner products when nkc > 1
     int ndot;
 };
@@ -390,7 +398,8 @@ __device__ __forceinline__ void eq_round8(Wire &W, Sh (&t)[8], const u64 (&A)[8]
 // The six AND rounds of eight equality tests held by one lane, in 32-bit registers.
 // Round 0 folds the high word onto the low word; afterwards everything fits 32 bits.
 // to/tn: the lane's two Boolean components; A: the lane's mask words (own xor next key).
-__device__ __forceinline__ void eq_rounds8_32(Wire &W, const Sh (&t)[8], const u64 (&A)[8], u32 (&to)[8], u32 (&tn)[8])
+template <class WireT>
+__device__ __forceinline__ void eq_rounds8_32(WireT &W, const Sh (&t)[8], const u64 (&A)[8], u32 (&to)[8], u32 (&tn)[8])
 {
     {   // width 32: 8 x 32 bits = 4 words
         u64 snd[4], rcv[4];
@@ -401,7 +410,7 @@ __device__ __forceinline__ void eq_rounds8_32(Wire &W, const Sh (&t)[8], const u
         }
 #pragma unroll
         for (int j = 0; j < 4; j++) snd[j] = (u64)to[2 * j] | ((u64)to[2 * j + 1] << 32);
-        W.reshare<4>(snd, rcv);
+        W.template reshare<4>(snd, rcv);
 #pragma unroll
         for (int j = 0; j < 4; j++) { tn[2 * j] = (u32)rcv[j]; tn[2 * j + 1] = (u32)(rcv[j] >> 32); }
     }
@@ -418,7 +427,7 @@ __device__ __forceinline__ void eq_rounds8_32(Wire &W, const Sh (&t)[8], const u
 #pragma unroll
         for (int j = 0; j < 2; j++)
             snd[j] = (u64)(to[4 * j] | (to[4 * j + 1] << 16)) | ((u64)(to[4 * j + 2] | (to[4 * j + 3] << 16)) << 32);
-        W.reshare<2>(snd, rcv);
+        W.template reshare<2>(snd, rcv);
 #pragma unroll
         for (int j = 0; j < 2; j++) {
             const u32 lo = (u32)rcv[j], hi = (u32)(rcv[j] >> 32);
@@ -434,7 +443,7 @@ __device__ __forceinline__ void eq_rounds8_32(Wire &W, const Sh (&t)[8], const u
             to[s] = ((to[s] & (bo ^ bn)) ^ (tn[s] & bo) ^ (Ah[s] >> OFF)) & ((1u << WB) - 1);    \
             snd[0] |= (u64)to[s] << (s * WB);                                                   \
         }                                                                                       \
-        W.reshare<1>(snd, rcv);                                                                 \
+        W.template reshare<1>(snd, rcv);                                                                 \
         _Pragma("unroll") for (int s = 0; s < 8; s++) tn[s] = (u32)(rcv[0] >> (s * WB)) & ((1u << WB) - 1); \
     }
     GT_EQ_SMALL_ROUND(8, 16)
@@ -460,33 +469,47 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     // rows 3-5: r Boolean components; rows 6-8: beta arithmetic components
     __shared__ u64 s_mat[9][GT_TILE_EL];
     __shared__ unsigned char s_bits[GT_TILE_EL];   // beta Boolean components, bit j = component j
-    const int p = threadIdx.y, lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1;
+    const int p = threadIdx.y, lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1, pp = p == 0 ? 2 : p - 1;
     Wire W; W.init(a.c.wire);
+    // messages of the AND rounds and of the bit conversion pass through the rows of the
+    // Boolean edaBit components, which are dead once t has been formed
+    LWire LW; LW.init(&s_mat[3][0]);
+    static_assert(GT_LWIRE_WORDS <= 3 * GT_TILE_EL, "LDS wire does not fit the rows it reuses");
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u32 op = a.c.op;
     const u64 ngrp = a.N8 / 8;
     const Sh one = pub(p, 1);
     const u64 mo = p == 0 ? ~0ull : 0ull, mn_ = p == 2 ? ~0ull : 0ull;   // who holds component 0
-    // work item = (tile of 512 samples, range of columns); with more than one column
+    // work item = (tile of samples, range of columns); with more than one column
     // range per tile the inner products are completed by atomic adds (exact in the
-    // ring) and the reshare runs in k_dot_fin
-    const u64 nt = (ngrp + GT_LANES - 1) / GT_LANES;
+    // ring) and the reshare runs in k_dot_fin.  A step covers 64 groups of 8 samples
+    // of one column, or (leaf one-hot with a column count that is a multiple of four)
+    // 16 groups of four adjacent columns each: the four 32-byte pieces that one
+    // wavefront then writes per sample block and limb make up whole 128-byte lines of
+    // the tile layout.
+    const int lgs = MODE == GM_STORE ? a.lgs : 6;      // log2 of the lanes per column
+    const u32 lgm = (1u << lgs) - 1, kstep = GT_LANES >> lgs, ro = lane >> lgs;
+    const u64 nt = (ngrp + lgm) >> lgs;
     for (u64 item = blockIdx.x; item < nt * a.nkc; item += gridDim.x) {
         const u64 tile = item / a.nkc;
         const u32 kbeg = (u32)(item % a.nkc) * a.kchunk, kend = kbeg + a.kchunk < a.w ? kbeg + a.kchunk : a.w;
-        const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
-        const bool act = grp < ngrp;
-        const u64 nv = act ? a.N : 0;                  // samples of this lane that exist
+        const u64 grp = (tile << lgs) + (lane & lgm), i0 = grp * 8;
+        const bool actg = grp < ngrp;
+        const u64 nvg = actg ? a.N : 0;
         u64 acc[8], acc2[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) { acc[s] = 0; acc2[s] = 0; }
-        for (u32 k = kbeg; k < kend; k++) {
+        for (u32 k0 = kbeg; k0 < kend; k0 += kstep) {
+            const bool act = MODE == GM_STORE ? actg && k0 + ro < kend : actg;
+            const u32 k = MODE == GM_STORE ? (act ? k0 + ro : kbeg) : k0;   // this lane's column (an existing one when idle)
+            const u64 nv = act ? a.N : 0;              // samples of this lane that exist
             const u64 e0 = (u64)k * a.N8 + i0;
 #pragma unroll 1
             for (int j = 0; j < 3; j++) {
                 const int el = j * 192 + tid;
                 if (el < GT_TILE_EL) {
-                    const u64 e = (u64)k * a.N8 + (tile * GT_LANES + (el & (GT_LANES - 1))) * 8 + (el >> 6);
+                    const u32 ln = el & (GT_LANES - 1);
+                    const u64 e = (u64)(k0 + (ln >> lgs)) * a.N8 + ((tile << lgs) + (ln & lgm)) * 8 + (el >> 6);
                     u64 D[8];
                     chacha8(K.dlr, e, op, 0, D);
                     const u64 beta = D[5] & 1;
@@ -510,9 +533,14 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 snd[s] = (live ? snd[s] - sub.o : 0) + s_mat[p][el];
                 mn[s] = (live ? mn[s] - sub.n : 0) + s_mat[pn][el];
             }
-            W.open<8>(snd, rcv);                       // masked values, 64 bits each
+            // opening of the masked values, 64 bits each: party p's message takes the place
+            // of row p once every party has read the components it needs
+            __syncthreads();
 #pragma unroll
-            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = A[s];
+            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = snd[s];
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) rcv[s] = s_mat[pp][s * GT_LANES + lane];
             Sh t[8];
 #pragma unroll
             for (int s = 0; s < 8; s++) {
@@ -523,9 +551,12 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             }
             __syncthreads();
 #pragma unroll
+            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = A[s];
+            __syncthreads();
+#pragma unroll
             for (int s = 0; s < 8; s++) A[s] ^= s_mat[pn][s * GT_LANES + lane];
             u32 to[8], tn[8];
-            eq_rounds8_32(W, t, A, to, tn);            // six AND rounds, 63 bits
+            eq_rounds8_32(LW, t, A, to, tn);           // six AND rounds, 63 bits
             if (HAS_G) {                               // and with the column's shared bit
                 const Sh gk = ld(a.g, p, k);
                 const u32 go = (u32)gk.o & 1, gn = (u32)gk.n & 1;
@@ -535,7 +566,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                     to[s] = ((to[s] & (go ^ gn)) ^ (tn[s] & go) ^ (u32)(A[s] >> 63)) & 1;
                     s1[0] |= (u64)to[s] << s;
                 }
-                W.reshare<1>(s1, r1);
+                LW.reshare<1>(s1, r1);
 #pragma unroll
                 for (int s = 0; s < 8; s++) tn[s] = (u32)(r1[0] >> s) & 1;
             }
@@ -548,7 +579,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                     fo |= ((to[s] ^ (bb >> p)) & 1) << s;
                     fn |= ((tn[s] ^ (bb >> pn)) & 1) << s;
                 }
-                f = fo ^ fn ^ (u32)W.open1((u64)fo);
+                f = fo ^ fn ^ (u32)LW.open1((u64)fo);
             }
             Sh Wk = { 0, 0 }, Wk2 = { 0, 0 };
             if (MODE == GM_COMMON) {
@@ -564,7 +595,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 Sh E;
                 E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
                 E.n = ((f >> s) & 1) ? one.n - bA.n : bA.n;
-                const bool live = act && i0 + s < a.N;
+                const bool live = i0 + s < nv;
                 if (MODE == GM_STORE) { Es[s] = live ? E.o + E.n : 0; Eo[s] = live ? E.o : 0; }
                 if (MODE == GM_COMMON) { acc[s] += prod3(E, Wk); if (NDOT == 2) acc2[s] += prod3(E, Wk2); }
                 if (MODE == GM_ROWS) { const Sh x = { xo[s], xn[s] }; acc[s] += prod3(E, x); }
@@ -578,7 +609,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
         if (MODE != GM_STORE && a.nkc > 1) {
 #pragma unroll
             for (int s = 0; s < 8; s++)
-                if (i0 + s < nv) {
+                if (i0 + s < nvg) {
                     atomicAdd((unsigned long long *)&a.dacc[(u64)p * a.N8 + i0 + s], (unsigned long long)acc[s]);
                     if (NDOT == 2) atomicAdd((unsigned long long *)&a.dacc[(u64)(3 + p) * a.N8 + i0 + s], (unsigned long long)acc2[s]);
                 }
@@ -592,7 +623,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             W.reshare<8>(snd, rcv);
 #pragma unroll
             for (int s = 0; s < 8; s++) {
-                if (act && i0 + s < a.N) {
+                if (actg && i0 + s < a.N) {
                     Sh z = { snd[s], rcv[s] };
                     if (a.epi == 1) z = scale(ld(a.prev, p, i0 + s), 2) + z + one;
                     st(a.out, p, i0 + s, z);
@@ -606,7 +637,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 W.reshare<8>(snd, rcv);
 #pragma unroll
                 for (int s = 0; s < 8; s++)
-                    if (act && i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.out2, p, i0 + s, z); }
+                    if (actg && i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.out2, p, i0 + s, z); }
             }
         }
     }

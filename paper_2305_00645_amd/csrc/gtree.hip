@@ -336,9 +336,13 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
     const u64 nel = (u64)a.w * a.N;
     if (a.N && a.w) {
         // enough work items to keep every resident workgroup slot busy for several rounds
-        const u64 ntile = (a.N8 / 8 + GT_LANES - 1) / GT_LANES, want = 8ull * g_resident;
-        u64 nkc = std::min<u64>(a.w, std::max<u64>(1, (want + ntile - 1) / ntile));
-        a.kchunk = (u32)((a.w + nkc - 1) / nkc);
+        // the leaf one-hot grid takes four adjacent columns per step when it can (whole
+        // lines of the limb tiles per store); all other grids one column per step
+        a.lgs = (mode == GM_STORE && a.w % 4 == 0) ? 4 : 6;
+        const u64 kstep = GT_LANES >> a.lgs, nsteps = (a.w + kstep - 1) / kstep;
+        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 8ull * g_resident;
+        u64 nkc = std::min<u64>(nsteps, std::max<u64>(1, (want + ntile - 1) / ntile));
+        a.kchunk = (u32)(((nsteps + nkc - 1) / nkc) * kstep);
         a.nkc = (a.w + a.kchunk - 1) / a.kchunk;
         a.dacc = nullptr;
         if (mode != GM_STORE && a.nkc > 1) {
@@ -438,7 +442,8 @@ static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shar
     // one-time products X[i][k] * Y[i][c] and the class columns, as limb tiles
     XyArgs a{}; a.c = kc(c, c->op++); a.XT = t->XT.v; a.YT = t->YT.v; a.B = limbs_B(t); a.N = N; a.N8 = N8; a.K = K;
     a.ncol = d * K;
-    const unsigned gy = std::min(a.ncol, 1024u), gx = std::max(1u, std::min(tiles8(N8), GT_MAX_BLOCKS / gy));
+    const unsigned gy = std::min((a.ncol + 3) / 4, 1024u);
+    const unsigned gx = (unsigned)std::max<u64>(1, std::min<u64>((N8 / 8 + 15) / 16, GT_MAX_BLOCKS / gy));
     GTCHK(launch(c, GT_KC_MULT, k_xy, dim3(gx, gy), GT_BLOCK, a));
     acct_reshare(c, (u64)N * d * K, 1);
     GTCHK(launch(c, GT_KC_LOCAL, k_y_limbs, g1((N8 / 8) * K), B256, t->YT.v, limbs_B(t), (u64)N, (u64)N8, K, (u64)d * K));
