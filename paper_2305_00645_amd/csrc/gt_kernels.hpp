@@ -1,5 +1,6 @@
 // Kernels of the GTree hot path for gfx950.  See gt_device.hpp for the execution
-// model (workgroup = 3 wavefronts = 3 parties; messages through the wire buffer).
+// model (workgroup = 3 wavefronts = 3 parties; messages through the workgroup's region
+// of the wire buffer or through LDS).
 #pragma once
 #include "gt_device.hpp"
 
@@ -357,43 +358,6 @@ struct GridArgs {
     u64 *dacc;      // [2][3][N8] partial inner products when nkc > 1
     int ndot;
 };
-
-template <int W2B>
-__device__ __forceinline__ void pack8(const u64 (&z)[8], u64 (&snd)[(W2B * 8 + 63) / 64])
-{
-    constexpr int NW = (W2B * 8 + 63) / 64;
-#pragma unroll
-    for (int j = 0; j < NW; j++) snd[j] = 0;
-#pragma unroll
-    for (int s = 0; s < 8; s++) snd[(s * W2B) >> 6] |= z[s] << ((s * W2B) & 63);
-}
-template <int W2B>
-__device__ __forceinline__ void unpack8(const u64 (&rcv)[(W2B * 8 + 63) / 64], u64 (&z)[8])
-{
-    constexpr u64 mask = W2B == 64 ? ~0ull : ((1ull << (W2B & 63)) - 1);
-#pragma unroll
-    for (int s = 0; s < 8; s++) z[s] = (rcv[(s * W2B) >> 6] >> ((s * W2B) & 63)) & mask;
-}
-
-template <int W2B>
-__device__ __forceinline__ void eq_round8(Wire &W, Sh (&t)[8], const u64 (&A)[8], u32 off)
-{
-    constexpr int NW = (W2B * 8 + 63) / 64;
-    constexpr u64 mask = (1ull << W2B) - 1;
-    u64 z[8], r[8], snd[NW], rcv[NW];
-#pragma unroll
-    for (int s = 0; s < 8; s++) {
-        Sh a, b;
-        a.o = t[s].o & mask; a.n = t[s].n & mask;
-        b.o = (t[s].o >> W2B) & mask; b.n = (t[s].n >> W2B) & mask;
-        z[s] = (and3(a, b) ^ (A[s] >> off)) & mask;
-    }
-    pack8<W2B>(z, snd);
-    W.reshare<NW>(snd, rcv);
-    unpack8<W2B>(rcv, r);
-#pragma unroll
-    for (int s = 0; s < 8; s++) { t[s].o = z[s]; t[s].n = r[s]; }
-}
 
 // The six AND rounds of eight equality tests held by one lane, in 32-bit registers.
 // Round 0 folds the high word onto the low word; afterwards everything fits 32 bits.
