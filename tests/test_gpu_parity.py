@@ -234,6 +234,26 @@ def test_train_degenerate(mods, seed):
     run_train_pair(mods, seed, dict(X=X1, Y=Y1, y=y1, N=4, d=1, K=2, H=2))
 
 
+def test_train_limits_of_classes_and_precision(mods, seed):
+    """Largest class count and largest number of fractional bits the library accepts."""
+    rng = np.random.default_rng(99)
+    N, d, K = 130, 5, 16
+    X = (rng.random((N, d)) < 0.5).astype(np.uint64)
+    y = (X[:, 0].astype(np.int64) * 8 + X[:, 2].astype(np.int64) * 4 + rng.integers(0, 4, N)) % K
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), tau=20)
+
+
+def test_train_deep_tree_few_samples(mods, seed):
+    """Far more nodes than samples: 2^11 leaves for 40 samples, most nodes empty."""
+    rng = np.random.default_rng(98)
+    N, d, K, H = 40, 12, 2, 11
+    X = (rng.random((N, d)) < 0.5).astype(np.uint64)
+    y = (X[:, 1] ^ X[:, 4] ^ X[:, 7]).astype(np.int64)
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=H), every_level=False)
+
+
 def test_train_errors(mods, seed):
     Oracle, gtree = mods
     from paper_2305_00645_amd import workloads as wl
@@ -252,7 +272,7 @@ def test_train_errors(mods, seed):
 
 
 # ------------------------------------------------------------------ inference
-@pytest.mark.parametrize("binary,NI,H", [(False, 1000, 7), (True, 1000, 7), (False, 77, 3), (True, 1, 2)])
+@pytest.mark.parametrize("binary,NI,H", [(False, 1000, 7), (True, 1000, 7), (False, 77, 3), (True, 1, 2), (True, 5, 16), (False, 9, 13)])
 def test_infer(mods, seed, binary, NI, H):
     import plain_cart
     from paper_2305_00645_amd import workloads as wl
