@@ -359,62 +359,119 @@ struct GridArgs {
     int ndot;
 };
 
-// The six AND rounds of eight equality tests held by one lane, in 32-bit registers.
-// Round 0 folds the high word onto the low word; afterwards everything fits 32 bits.
-// to/tn: the lane's two Boolean components; A: the lane's mask words (own xor next key).
+// The six AND rounds of eight equality tests held by one lane.  From the second round
+// on the eight values stay packed in the format of the messages (fields of 16, 8, 4, 2
+// bits and finally single bits, test s in field s), so that one word operation serves
+// several tests: a round shifts the packed words by the field's half width, forms the
+// three-term AND in every field at once (the upper half of each field then holds
+// garbage that the compaction drops) and compacts the lower halves into the fields of
+// the next message.  t: the lane's two Boolean components of the 64-bit inputs; A: the
+// lane's mask words (own xor next key): bits 0-31 round 0, 32-47 round 1, 48-55 round 2,
+// 56-59 round 3, 60-61 round 4, 62 round 5.  To8/Tn8: result bits, test s in bit s.
+__device__ __forceinline__ u32 and3w(u32 ao, u32 an, u32 bo, u32 bn) { return (ao & (bo ^ bn)) ^ (an & bo); }
+
 template <class WireT>
-__device__ __forceinline__ void eq_rounds8_32(WireT &W, const Sh (&t)[8], const u64 (&A)[8], u32 (&to)[8], u32 (&tn)[8])
+__device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], const u64 (&A)[8], u32 &To8, u32 &Tn8)
 {
-    {   // width 32: 8 x 32 bits = 4 words
+    u32 xo[8], xn[8], Ah[8];
+    {   // round 0, width 32: the high word onto the low word; message 8 x 32 bits
         u64 snd[4], rcv[4];
 #pragma unroll
-        for (int s = 0; s < 8; s++) {
-            const u32 ao = (u32)t[s].o, an = (u32)t[s].n, bo = (u32)(t[s].o >> 32), bn = (u32)(t[s].n >> 32);
-            to[s] = (ao & (bo ^ bn)) ^ (an & bo) ^ (u32)A[s];
-        }
+        for (int s = 0; s < 8; s++)
+            xo[s] = and3w((u32)t[s].o, (u32)t[s].n, (u32)(t[s].o >> 32), (u32)(t[s].n >> 32)) ^ (u32)A[s];
 #pragma unroll
-        for (int j = 0; j < 4; j++) snd[j] = (u64)to[2 * j] | ((u64)to[2 * j + 1] << 32);
+        for (int j = 0; j < 4; j++) snd[j] = (u64)xo[2 * j] | ((u64)xo[2 * j + 1] << 32);
         W.template reshare<4>(snd, rcv);
 #pragma unroll
-        for (int j = 0; j < 4; j++) { tn[2 * j] = (u32)rcv[j]; tn[2 * j + 1] = (u32)(rcv[j] >> 32); }
+        for (int j = 0; j < 4; j++) { xn[2 * j] = (u32)rcv[j]; xn[2 * j + 1] = (u32)(rcv[j] >> 32); }
     }
-    u32 Ah[8];
 #pragma unroll
-    for (int s = 0; s < 8; s++) Ah[s] = (u32)(A[s] >> 32);   // bits 32..62: rounds 1..5
-    {   // width 16: 8 x 16 bits = 2 words
+    for (int s = 0; s < 8; s++) Ah[s] = (u32)(A[s] >> 32);
+    u32 Po[4], Pn[4];
+    {   // round 1, width 16: message 8 x 16 bits, two tests per 32-bit word
         u64 snd[2], rcv[2];
+        u32 z[8];
 #pragma unroll
-        for (int s = 0; s < 8; s++) {
-            const u32 bo = to[s] >> 16, bn = tn[s] >> 16;
-            to[s] = ((to[s] & (bo ^ bn)) ^ (tn[s] & bo) ^ Ah[s]) & 0xffffu;
-        }
+        for (int s = 0; s < 8; s++) z[s] = and3w(xo[s], xn[s], xo[s] >> 16, xn[s] >> 16) ^ Ah[s];
 #pragma unroll
-        for (int j = 0; j < 2; j++)
-            snd[j] = (u64)(to[4 * j] | (to[4 * j + 1] << 16)) | ((u64)(to[4 * j + 2] | (to[4 * j + 3] << 16)) << 32);
+        for (int j = 0; j < 4; j++) Po[j] = __builtin_amdgcn_perm(z[2 * j + 1], z[2 * j], 0x05040100u);
+#pragma unroll
+        for (int j = 0; j < 2; j++) snd[j] = (u64)Po[2 * j] | ((u64)Po[2 * j + 1] << 32);
         W.template reshare<2>(snd, rcv);
 #pragma unroll
+        for (int j = 0; j < 2; j++) { Pn[2 * j] = (u32)rcv[j]; Pn[2 * j + 1] = (u32)(rcv[j] >> 32); }
+    }
+    u32 Qo[2], Qn[2];
+    {   // round 2, width 8: fields of 16 bits in, 8 bits out; masks = byte 2 of Ah
+        u32 z[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+            z[j] = and3w(Po[j], Pn[j], Po[j] >> 8, Pn[j] >> 8) ^ __builtin_amdgcn_perm(Ah[2 * j + 1], Ah[2 * j], 0x0c060c02u);
+#pragma unroll
+        for (int j = 0; j < 2; j++) Qo[j] = __builtin_amdgcn_perm(z[2 * j + 1], z[2 * j], 0x06040200u);
+        u64 snd[1] = { (u64)Qo[0] | ((u64)Qo[1] << 32) }, rcv[1];
+        W.template reshare<1>(snd, rcv);
+        Qn[0] = (u32)rcv[0]; Qn[1] = (u32)(rcv[0] >> 32);
+    }
+    // byte 3 of every Ah, test s in byte s: low nibble = masks of round 3, bits 4-5 of
+    // round 4, bit 6 of round 5, bit 7 = mask of a following AND (bit 63 of A)
+    u32 B3[2];
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+        B3[j] = __builtin_amdgcn_perm(Ah[4 * j + 1], Ah[4 * j], 0x0c0c0703u) | __builtin_amdgcn_perm(Ah[4 * j + 3], Ah[4 * j + 2], 0x07030c0cu);
+    u32 Ro, Rn;
+    {   // round 3, width 4: fields of 8 bits in, 4 bits out
+        u32 y[2];
+#pragma unroll
         for (int j = 0; j < 2; j++) {
-            const u32 lo = (u32)rcv[j], hi = (u32)(rcv[j] >> 32);
-            tn[4 * j] = lo & 0xffffu; tn[4 * j + 1] = lo >> 16; tn[4 * j + 2] = hi & 0xffffu; tn[4 * j + 3] = hi >> 16;
+            const u32 z = (and3w(Qo[j], Qn[j], Qo[j] >> 4, Qn[j] >> 4) ^ B3[j]) & 0x0f0f0f0fu;
+            y[j] = z | (z >> 4);
         }
+        Ro = __builtin_amdgcn_perm(y[1], y[0], 0x06040200u);
+        u64 snd[1] = { (u64)Ro }, rcv[1];
+        W.template reshare<1>(snd, rcv);
+        Rn = (u32)rcv[0];
     }
-    // widths 8, 4, 2, 1: all eight values in one word
-#define GT_EQ_SMALL_ROUND(WB, OFF)                                                              \
-    {                                                                                           \
-        u64 snd[1] = { 0 }, rcv[1];                                                             \
-        _Pragma("unroll") for (int s = 0; s < 8; s++) {                                         \
-            const u32 bo = to[s] >> WB, bn = tn[s] >> WB;                                       \
-            to[s] = ((to[s] & (bo ^ bn)) ^ (tn[s] & bo) ^ (Ah[s] >> OFF)) & ((1u << WB) - 1);    \
-            snd[0] |= (u64)to[s] << (s * WB);                                                   \
-        }                                                                                       \
-        W.template reshare<1>(snd, rcv);                                                                 \
-        _Pragma("unroll") for (int s = 0; s < 8; s++) tn[s] = (u32)(rcv[0] >> (s * WB)) & ((1u << WB) - 1); \
+    u32 H;      // bits 28-31 of every Ah, test s in nibble s
+    {
+        u32 h[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) { const u32 x = (B3[j] >> 4) & 0x0f0f0f0fu; h[j] = x | (x >> 4); }
+        H = __builtin_amdgcn_perm(h[1], h[0], 0x06040200u);
     }
-    GT_EQ_SMALL_ROUND(8, 16)
-    GT_EQ_SMALL_ROUND(4, 24)
-    GT_EQ_SMALL_ROUND(2, 28)
-    GT_EQ_SMALL_ROUND(1, 30)
-#undef GT_EQ_SMALL_ROUND
+    u32 So, Sn;
+    {   // round 4, width 2: fields of 4 bits in, 2 bits out
+        u32 z = (and3w(Ro, Rn, Ro >> 2, Rn >> 2) ^ H) & 0x33333333u;
+        z = (z | (z >> 2)) & 0x0f0f0f0fu; z = (z | (z >> 4)) & 0x00ff00ffu; So = (z | (z >> 8)) & 0xffffu;
+        u64 snd[1] = { (u64)So }, rcv[1];
+        W.template reshare<1>(snd, rcv);
+        Sn = (u32)rcv[0];
+    }
+    {   // round 5, width 1: fields of 2 bits in, single bits out
+        u32 m = (H >> 2) & 0x11111111u;
+        m = (m | (m >> 2)) & 0x0f0f0f0fu; m = (m | (m >> 4)) & 0x00ff00ffu; m = (m | (m >> 8)) & 0xffffu;
+        u32 z = (and3w(So, Sn, So >> 1, Sn >> 1) ^ m) & 0x5555u;
+        z = (z | (z >> 1)) & 0x3333u; z = (z | (z >> 2)) & 0x0f0fu; To8 = (z | (z >> 4)) & 0xffu;
+        u64 snd[1] = { (u64)To8 }, rcv[1];
+        W.template reshare<1>(snd, rcv);
+        Tn8 = (u32)rcv[0];
+    }
+}
+
+// bit 63 of the eight mask words, test s in bit s (mask of an AND that follows the rounds)
+__device__ __forceinline__ u32 mask63_packed(const u64 (&A)[8])
+{
+    u32 g[2];
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+        u32 x = 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) x |= (u32)(A[4 * j + i] >> 63) << (8 * i);
+        g[j] = x;
+    }
+#pragma unroll
+    for (int j = 0; j < 2; j++) { g[j] = (g[j] | (g[j] >> 7)) & 0x00030003u; g[j] = (g[j] | (g[j] >> 14)) & 0xfu; }
+    return g[0] | (g[1] << 4);
 }
 
 // Offline and pairwise-key material is produced once per workgroup and handed out
@@ -519,30 +576,26 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             __syncthreads();
 #pragma unroll
             for (int s = 0; s < 8; s++) A[s] ^= s_mat[pn][s * GT_LANES + lane];
-            u32 to[8], tn[8];
-            eq_rounds8_32(LW, t, A, to, tn);           // six AND rounds, 63 bits
+            u32 To8, Tn8;
+            eq_rounds8_packed(LW, t, A, To8, Tn8);     // six AND rounds, 63 bits
             if (HAS_G) {                               // and with the column's shared bit
                 const Sh gk = ld(a.g, p, k);
-                const u32 go = (u32)gk.o & 1, gn = (u32)gk.n & 1;
-                u64 s1[1] = { 0 }, r1[1];
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    to[s] = ((to[s] & (go ^ gn)) ^ (tn[s] & go) ^ (u32)(A[s] >> 63)) & 1;
-                    s1[0] |= (u64)to[s] << s;
-                }
+                const u32 go = 0u - ((u32)gk.o & 1), gn = 0u - ((u32)gk.n & 1);
+                To8 = (and3w(To8, Tn8, go, gn) ^ mask63_packed(A)) & 0xffu;
+                u64 s1[1] = { (u64)To8 }, r1[1];
                 LW.reshare<1>(s1, r1);
-#pragma unroll
-                for (int s = 0; s < 8; s++) tn[s] = (u32)(r1[0] >> s) & 1;
+                Tn8 = (u32)r1[0];
             }
             u32 f;
             {                                          // bit -> arithmetic: open s xor beta
-                u32 fo = 0, fn = 0;
+                u32 bo = 0, bn = 0;
 #pragma unroll
                 for (int s = 0; s < 8; s++) {
                     const u32 bb = s_bits[s * GT_LANES + lane];
-                    fo |= ((to[s] ^ (bb >> p)) & 1) << s;
-                    fn |= ((tn[s] ^ (bb >> pn)) & 1) << s;
+                    bo |= ((bb >> p) & 1) << s;
+                    bn |= ((bb >> pn) & 1) << s;
                 }
+                const u32 fo = To8 ^ bo, fn = Tn8 ^ bn;
                 f = fo ^ fn ^ (u32)LW.open1((u64)fo);
             }
             Sh Wk = { 0, 0 }, Wk2 = { 0, 0 };
