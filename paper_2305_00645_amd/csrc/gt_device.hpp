@@ -127,6 +127,11 @@ __device__ __forceinline__ Sh scale(Sh a, u64 c) { Sh v; v.o = a.o * c; v.n = a.
 __device__ __forceinline__ u64 prod3(Sh x, Sh y) { return x.o * (y.o + y.n) + x.n * y.o; }
 __device__ __forceinline__ u64 and3(Sh x, Sh y) { return (x.o & (y.o ^ y.n)) ^ (x.n & y.o); }
 
+// The party of this wavefront.  All 64 lanes of a wavefront share threadIdx.y (the
+// workgroup is 64 x 3), so the value is read into a scalar register: selections and
+// branches on the party then cost no vector instructions.
+__device__ __forceinline__ int party_of_wave() { return __builtin_amdgcn_readfirstlane((int)threadIdx.y); }
+
 // ---------------------------------------------------------------------------------
 // Message exchange inside the workgroup.  `reshare`: every party sends to its
 // predecessor (after a product, so that the receiver then holds (z_p, z_{p+1}));
@@ -138,12 +143,12 @@ struct Wire {
     __device__ __forceinline__ void init(u64 *wire)
     {
         base = wire + (size_t)blockIdx.x * GT_WIRE_WORDS_PER_BLOCK;
-        slot = 0; p = threadIdx.y; lane = threadIdx.x;
+        slot = 0; p = party_of_wave(); lane = threadIdx.x;
     }
     __device__ __forceinline__ void init2d(u64 *wire)         // grid (x, y): one region per workgroup
     {
         base = wire + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * GT_WIRE_WORDS_PER_BLOCK;
-        slot = 0; p = threadIdx.y; lane = threadIdx.x;
+        slot = 0; p = party_of_wave(); lane = threadIdx.x;
     }
     template <int NW>
     __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
@@ -174,7 +179,7 @@ struct Wire {
 struct LWire {
     u64 *base;
     int slot, p, lane;
-    __device__ __forceinline__ void init(u64 *lds) { base = lds; slot = 0; p = threadIdx.y; lane = threadIdx.x; }
+    __device__ __forceinline__ void init(u64 *lds) { base = lds; slot = 0; p = party_of_wave(); lane = threadIdx.x; }
     template <int NW>
     __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
     {

@@ -218,7 +218,7 @@ struct MultArgs { KCommon c; P6 x, y, z; u64 n, N, N8; u32 K, CW; };
 template <int MODE>
 __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 {
-    const int p = threadIdx.y, lane = threadIdx.x;
+    const int p = party_of_wave(), lane = threadIdx.x;
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = (a.n + 7) / 8;
@@ -264,7 +264,7 @@ struct XyArgs { KCommon c; P6 XT, YT; LimbSet B; u64 N, N8; u32 K, ncol; };
 __global__ __launch_bounds__(192, 3) void k_xy(XyArgs a)
 {
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    const int p = threadIdx.y, lane = threadIdx.x;
+    const int p = party_of_wave(), lane = threadIdx.x;
     LWire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = a.N8 / 8, nq = (a.ncol + 3) / 4, nt = (ngrp + 15) / 16;
@@ -489,8 +489,11 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     // rows 0-2: r arithmetic components, then the mask words under k_0..k_2;
     // rows 3-5: r Boolean components; rows 6-8: beta arithmetic components
     __shared__ u64 s_mat[9][GT_TILE_EL];
-    __shared__ unsigned char s_bits[GT_TILE_EL];   // beta Boolean components, bit j = component j
-    const int p = threadIdx.y, lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1, pp = p == 0 ? 2 : p - 1;
+    // beta Boolean components, packed per lane: bit 8j+s = component j of the lane's test s.
+    // The dealer's lanes OR their bits in; two copies alternate between steps so that
+    // one can be cleared while the other is in use.
+    __shared__ u32 s_bitw[2][GT_LANES];
+    const int p = party_of_wave(), lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1, pp = p == 0 ? 2 : p - 1;
     Wire W; W.init(a.c.wire);
     // messages of the AND rounds and of the bit conversion pass through the rows of the
     // Boolean edaBit components, which are dead once t has been formed
@@ -511,6 +514,9 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     const int lgs = MODE == GM_STORE ? a.lgs : 6;      // log2 of the lanes per column
     const u32 lgm = (1u << lgs) - 1, kstep = GT_LANES >> lgs, ro = lane >> lgs;
     const u64 nt = (ngrp + lgm) >> lgs;
+    if (tid < 2 * GT_LANES) (&s_bitw[0][0])[tid] = 0;
+    __syncthreads();
+    u32 par = 0;
     for (u64 item = blockIdx.x; item < nt * a.nkc; item += gridDim.x) {
         const u64 tile = item / a.nkc;
         const u32 kbeg = (u32)(item % a.nkc) * a.kchunk, kend = kbeg + a.kchunk < a.w ? kbeg + a.kchunk : a.w;
@@ -538,7 +544,8 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                     s_mat[3][el] = D[3]; s_mat[4][el] = D[4]; s_mat[5][el] = D[0] ^ D[3] ^ D[4];
                     s_mat[6][el] = D[6]; s_mat[7][el] = D[7]; s_mat[8][el] = beta - D[6] - D[7];
                     const u32 b0 = (u32)(D[5] >> 1) & 1, b1 = (u32)(D[5] >> 2) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
-                    s_bits[el] = (unsigned char)(b0 | (b1 << 1) | (b2 << 2));
+                    const u32 sh = (u32)el >> 6;
+                    atomicOr(&s_bitw[par][ln], (b0 << sh) | (b1 << (8 + sh)) | (b2 << (16 + sh)));
                 }
             }
             u64 A[8];
@@ -550,10 +557,10 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
-                const bool live = i0 + s < nv;
-                snd[s] = (live ? snd[s] - sub.o : 0) + s_mat[p][el];
-                mn[s] = (live ? mn[s] - sub.n : 0) + s_mat[pn][el];
+                snd[s] = snd[s] - sub.o + s_mat[p][el];    // samples beyond N: any value serves
+                mn[s] = mn[s] - sub.n + s_mat[pn][el];
             }
+            if (p == 0) s_bitw[par ^ 1][lane] = 0;     // the next step's bit words
             // opening of the masked values, 64 bits each: party p's message takes the place
             // of row p once every party has read the components it needs
             __syncthreads();
@@ -588,14 +595,8 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             }
             u32 f;
             {                                          // bit -> arithmetic: open s xor beta
-                u32 bo = 0, bn = 0;
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const u32 bb = s_bits[s * GT_LANES + lane];
-                    bo |= ((bb >> p) & 1) << s;
-                    bn |= ((bb >> pn) & 1) << s;
-                }
-                const u32 fo = To8 ^ bo, fn = Tn8 ^ bn;
+                const u32 bw = s_bitw[par][lane];
+                const u32 fo = To8 ^ ((bw >> (8 * p)) & 0xffu), fn = Tn8 ^ ((bw >> (8 * pn)) & 0xffu);
                 f = fo ^ fn ^ (u32)LW.open1((u64)fo);
             }
             Sh Wk = { 0, 0 }, Wk2 = { 0, 0 };
@@ -621,6 +622,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 store_limbs8(a.L.m[p][0], k, i0, Es);
                 store_limbs8(a.L.m[p][1], k, i0, Eo);
             }
+            par ^= 1;
             __syncthreads();                           // the material in LDS is overwritten next
         }
         if (MODE != GM_STORE && a.nkc > 1) {
@@ -664,7 +666,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 // output stream 3), reshare, epilogue as in k_eqgrid.  Eight rows per lane.
 __global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
 {
-    const int p = threadIdx.y, lane = threadIdx.x;
+    const int p = party_of_wave(), lane = threadIdx.x;
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = a.N8 / 8;
@@ -698,7 +700,7 @@ struct EqArgs { KCommon c; P6 x; const u64 *ypub; u64 ysub; P6 z; u64 n, xoff; }
 template <bool BOOL_OUT>
 __global__ __launch_bounds__(192) void k_eq(EqArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -718,7 +720,7 @@ __global__ __launch_bounds__(192) void k_eq(EqArgs a)
 struct GeArgs { KCommon c; P6 x, y, z; u64 n; };
 __global__ __launch_bounds__(192) void k_ge(GeArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -736,7 +738,7 @@ __global__ __launch_bounds__(192) void k_ge(GeArgs a)
 struct CmpArgs { KCommon c; P6 th, x, tidx; u64 n; };
 __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -755,7 +757,7 @@ __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
 struct DivArgs { KCommon c; P6 S, Q, r, quo; u64 n; int first; };
 __global__ __launch_bounds__(192) void k_div_step(DivArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -779,7 +781,7 @@ __global__ __launch_bounds__(192) void k_div_step(DivArgs a)
 struct PrepArgs { KCommon c; P6 C, S, Q; u64 n; u32 d, K, CW; };
 __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 dK = (u64)a.d * a.K;
@@ -808,7 +810,7 @@ __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
 struct MaskArgs { KCommon c; P6 quo, gamma, score, val; u64 n; u32 d, P2; };
 __global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -829,7 +831,7 @@ __global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
 struct SelArgs { KCommon c; P6 vin, iin, vout, iout, C; u64 n; u32 len, CW; u64 coff, cidx; int mode; };
 __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -860,7 +862,7 @@ __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
 struct GammaArgs { KCommon c; P6 SD, gamma; u64 n; u32 d; };
 __global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -881,7 +883,7 @@ __global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
 struct SplitArgs { KCommon c; P6 C, isLeaf, F, split; u64 n, base; u32 K, CW; u64 dK; };
 __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
@@ -1016,7 +1018,7 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
 struct CountFinArgs { KCommon c; u64 *Zacc; P6 C; u64 n; u32 ncol, CW; u64 colbase; };
 __global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
 {
-    const int p = threadIdx.y;
+    const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
