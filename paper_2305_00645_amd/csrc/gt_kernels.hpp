@@ -503,7 +503,6 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     const u32 op = a.c.op;
     const u64 ngrp = a.N8 / 8;
     const Sh one = pub(p, 1);
-    const u64 mo = p == 0 ? ~0ull : 0ull, mn_ = p == 2 ? ~0ull : 0ull;   // who holds component 0
     // work item = (tile of samples, range of columns); with more than one column
     // range per tile the inner products are completed by atomic adds (exact in the
     // ring) and the reshare runs in k_dot_fin.  A step covers 64 groups of 8 samples
@@ -552,13 +551,13 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             chacha8(K.own, e0 >> 3, op, 1, A);         // mask words under this party's own key
             __syncthreads();
             u64 snd[8], rcv[8], mn[8];
-            const Sh sub = pub(p, a.base + k);
+            const Sh nsub = pub(p, 0 - (a.base + k));  // minus the public column index
             ld8(own_of(a.u, p), i0, nv, snd); ld8(nxt_of(a.u, p), i0, nv, mn);
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const int el = s * GT_LANES + lane;
-                snd[s] = snd[s] - sub.o + s_mat[p][el];    // samples beyond N: any value serves
-                mn[s] = mn[s] - sub.n + s_mat[pn][el];
+                snd[s] = snd[s] + nsub.o + s_mat[p][el];   // samples beyond N: any value serves
+                mn[s] = mn[s] + nsub.n + s_mat[pn][el];
             }
             if (p == 0) s_bitw[par ^ 1][lane] = 0;     // the next step's bit words
             // opening of the masked values, 64 bits each: party p's message takes the place
@@ -569,13 +568,30 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             __syncthreads();
 #pragma unroll
             for (int s = 0; s < 8; s++) rcv[s] = s_mat[pp][s * GT_LANES + lane];
+            // t = rho with the complement of the opened value xored into component 0,
+            // which party 0 holds as its own and party 2 as its next component
             Sh t[8];
+            if (p == 0) {
 #pragma unroll
-            for (int s = 0; s < 8; s++) {
-                const int el = s * GT_LANES + lane;
-                const u64 nc = ~(snd[s] + mn[s] + rcv[s]);
-                t[s].o = s_mat[3 + p][el] ^ (nc & mo);
-                t[s].n = s_mat[3 + pn][el] ^ (nc & mn_);
+                for (int s = 0; s < 8; s++) {
+                    const int el = s * GT_LANES + lane;
+                    t[s].o = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
+                    t[s].n = s_mat[4][el];
+                }
+            } else if (p == 2) {
+#pragma unroll
+                for (int s = 0; s < 8; s++) {
+                    const int el = s * GT_LANES + lane;
+                    t[s].n = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
+                    t[s].o = s_mat[5][el];
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 8; s++) {
+                    const int el = s * GT_LANES + lane;
+                    t[s].o = s_mat[4][el];
+                    t[s].n = s_mat[5][el];
+                }
             }
             __syncthreads();
 #pragma unroll
