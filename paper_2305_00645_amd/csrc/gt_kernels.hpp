@@ -954,7 +954,68 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // bcol0: first column (row of B) of this launch, zcol0: its column in the output
 // rt: row tiles of 32 per workgroup (4, 2 or 1); the other 4/rt wavefronts take further column tiles
 // chunkblk: sample blocks of 32 per workgroup (at most CT_CHUNK_BLOCKS, the int32 accumulator bound)
-struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles; };   // ncoltiles: column tiles of 32*NB in this launch
+// narrow: 1 if one more column group of at most 16 columns (first column nbcol0 of B,
+// column nzcol0 of the output) is handled by the same launch with 16-wide tiles
+struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles;   // ncoltiles: column tiles of 32*NB in this launch
+                   u32 narrow; u64 nbcol0; u32 nzcol0; };
+
+// A remainder of at most 16 columns: 32 rows x 16 columns per wavefront with
+// v_mfma_i32_16x16x64_i8 (lane l holds row or column l%16 and the 16 samples
+// 16*(l/16).. of a pair of sample blocks; result C[4*(l/16)+v][l%16]).  It runs inside
+// the launch of the wide groups, as one more column group of each sample chunk, so that
+// its rows of L are found in the L2 cache that the wide groups of the chunk have filled.
+__device__ __forceinline__ void count_narrow(const CountArgs &a, int p, const LimbMat &LA0, const LimbMat &LA1,
+                                             const LimbMat &LB0, const LimbMat &LB1, u64 r0, u64 ib0, u64 ib1, int lane)
+{
+    const u32 lr = lane & 15, kq = lane >> 4;
+    v4i acc[8][2];
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+#pragma unroll
+        for (int hh = 0; hh < 2; hh++) acc[u][hh] = v4i{ 0, 0, 0, 0 };
+    const u64 rA0 = r0 + lr, rA1 = r0 + 16 + lr;     // below the padded row count of L, a multiple of 32
+    // the lane's sample block of a pair; the second block of an odd tail does not belong
+    // to this chunk: its lanes load the first block again and multiply zeros
+    const u32 half = (kq & 1) * 16;
+    v4i av0[8][2], bv0[8], av1[8][2], bv1[8];
+#define CN_LOAD(AV, BV, LA, LB, IB)                                                           \
+    {                                                                                         \
+        const bool tail = (IB) + (kq >> 1) >= ib1;                                            \
+        const u64 ibl = tail ? (IB) : (IB) + (kq >> 1);                                       \
+        _Pragma("unroll") for (int sl = 0; sl < 8; sl++) {                                    \
+            AV[sl][0] = *(const v4i *)(LA.base + limb_addr(LA, ibl, sl, rA0) + half);         \
+            AV[sl][1] = *(const v4i *)(LA.base + limb_addr(LA, ibl, sl, rA1) + half);         \
+            BV[sl] = *(const v4i *)(LB.base + limb_addr(LB, ibl, sl, a.nbcol0 + lr) + half);  \
+            if (tail) BV[sl] = v4i{ 0, 0, 0, 0 };                                             \
+        }                                                                                     \
+    }
+#define CN_MMA(AV, BV)                                                                        \
+    _Pragma("unroll") for (int u = 0; u < 8; u++)                                             \
+        _Pragma("unroll") for (int sl = 0; sl <= u; sl++)                                     \
+            _Pragma("unroll") for (int hh = 0; hh < 2; hh++)                                  \
+                acc[u][hh] = __builtin_amdgcn_mfma_i32_16x16x64_i8(AV[sl][hh], BV[u - sl], acc[u][hh], 0, 0, 0);
+    CN_LOAD(av0, bv0, LA0, LB0, ib0)
+    for (u64 ib = ib0; ib < ib1; ib += 2) {
+        CN_LOAD(av1, bv1, LA1, LB1, ib)
+        CN_MMA(av0, bv0)
+        if (ib + 2 < ib1) { CN_LOAD(av0, bv0, LA0, LB0, ib + 2) }
+        CN_MMA(av1, bv1)
+    }
+#undef CN_LOAD
+#undef CN_MMA
+    u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
+#pragma unroll
+    for (int hh = 0; hh < 2; hh++)
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+            const u64 r = r0 + hh * 16 + 4 * kq + v;
+            const u64 c = a.nzcol0 + lr;
+            u64 z = 0;
+#pragma unroll
+            for (int u = 0; u < 8; u++) z += (u64)(long long)acc[u][hh][v] << (8 * u);
+            if (r < a.nh && c < a.ncol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)z);
+        }
+}
 
 // Workgroup = 4 wavefronts = 128 rows x (32*NB) columns; NB = 2 for full groups of 64
 // columns, NB = 1 for a remainder of at most 32.  The kernel is limited by the rate at
@@ -972,14 +1033,23 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
     // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The column
     // groups of one sample chunk read the same rows of L, so they are given
     // consecutive slots of the same XCD: id = slot*8 + xcd, chunk = (slot / ncg)*8 + xcd.
-    const u32 ncg = a.ncg, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const u32 ncg = a.ncg + a.narrow, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
     const u32 cg = slot % ncg, chunk = (slot / ncg) * 8 + xcd;
     if (chunk >= a.nchunk) return;
+    const u64 ib0 = (u64)chunk * a.chunkblk;
+    const u64 ib1 = ib0 + a.chunkblk < a.nblk ? ib0 + a.chunkblk : a.nblk;
+    // product 0: (L_p + L_{p+1}) x B_p, product 1: L_p x B_{p+1}
+    const LimbMat LA0 = p == 0 ? a.L.m[0][0] : (p == 1 ? a.L.m[1][0] : a.L.m[2][0]);
+    const LimbMat LA1 = p == 0 ? a.L.m[0][1] : (p == 1 ? a.L.m[1][1] : a.L.m[2][1]);
+    const LimbMat LB0 = p == 0 ? a.B.m[0][0] : (p == 1 ? a.B.m[1][0] : a.B.m[2][0]);
+    const LimbMat LB1 = p == 0 ? a.B.m[0][1] : (p == 1 ? a.B.m[1][1] : a.B.m[2][1]);
+    if (a.narrow && cg == a.ncg) {                            // the narrow column group of this chunk
+        if (wc == 0) count_narrow(a, p, LA0, LA1, LB0, LB1, r0, ib0, ib1, lane);
+        return;
+    }
     const u64 ctile = (u64)cg * cper + wc;                   // column tile of 32*NB
     if (ctile >= a.ncoltiles) return;                         // whole wavefront
     const u64 c0 = a.bcol0 + ctile * (32 * NB);
-    const u64 ib0 = (u64)chunk * a.chunkblk;
-    const u64 ib1 = ib0 + a.chunkblk < a.nblk ? ib0 + a.chunkblk : a.nblk;
     const u32 lr = lane & 31;
     v16i acc[8][NB];
 #pragma unroll
@@ -988,11 +1058,6 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
         for (int nb = 0; nb < NB; nb++)
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[u][nb][v] = 0;
-    // product 0: (L_p + L_{p+1}) x B_p, product 1: L_p x B_{p+1}
-    const LimbMat LA0 = p == 0 ? a.L.m[0][0] : (p == 1 ? a.L.m[1][0] : a.L.m[2][0]);
-    const LimbMat LA1 = p == 0 ? a.L.m[0][1] : (p == 1 ? a.L.m[1][1] : a.L.m[2][1]);
-    const LimbMat LB0 = p == 0 ? a.B.m[0][0] : (p == 1 ? a.B.m[1][0] : a.B.m[2][0]);
-    const LimbMat LB1 = p == 0 ? a.B.m[0][1] : (p == 1 ? a.B.m[1][1] : a.B.m[2][1]);
     // addresses = wave-uniform base (scalar registers) + a 32-bit lane offset
     const u32 offA = (u32)((r0 + lr) * 32 + (lane >> 5) * 16), offB = (u32)(lr * 32 + (lane >> 5) * 16);
     v4i av0[8], bv0[NB][8], av1[8], bv1[NB][8];

@@ -539,22 +539,26 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     a.rt = nh > 64 ? 4 : (nh > 32 ? 2 : 1);
     a.nrowgrp = (u32)((nh + 32 * a.rt - 1) / (32 * a.rt));
     const u32 cper = 4 / a.rt;
-    // groups of 64 columns; a remainder of at most 32 columns runs with a 32-wide tile
+    // groups of 64 columns; a remainder of at most 16 columns joins their launch as a
+    // narrow group, one of 17 to 32 columns runs in a launch of its own with a 32-wide tile
     const u32 rem = ncol % 64, nfull = ncol / 64 + (rem > 32 ? 1 : 0);
-    const u32 ncg2 = (nfull + cper - 1) / cper, ncg1 = (rem && rem <= 32) ? 1 : 0;
+    const u32 narrow = (nfull && rem && rem <= 16) ? 1 : 0;   // alone it would only re-read L: no gain over the 32-wide tile
+    const u32 ncg2 = (nfull + cper - 1) / cper, ncg1 = (rem && rem <= 32 && !narrow) ? 1 : 0;
     // sample chunk per workgroup: as long as the int32 accumulators allow, shorter when
     // that is needed to give every compute unit several workgroups
-    const u64 wgs_per_chunk = (u64)(ncg2 + ncg1) * 3 * a.nrowgrp;
+    const u64 wgs_per_chunk = (u64)(ncg2 + ncg1 + narrow) * 3 * a.nrowgrp;
     u64 want_chunks = (4ull * g_resident / 4 + wgs_per_chunk - 1) / wgs_per_chunk;
     u64 cb = (t->nblk + want_chunks - 1) / want_chunks;
     cb = std::max<u64>(8, std::min<u64>(CT_CHUNK_BLOCKS, cb));
     a.chunkblk = (u32)cb;
     a.nchunk = (u32)((t->nblk + cb - 1) / cb);
-    if (nfull) {
+    if (nfull || narrow) {
         a.ncg = ncg2; a.ncoltiles = nfull; a.bcol0 = colbase; a.zcol0 = 0;
-        GTCHK(launch(c, GT_KC_COUNT, k_count<2>, dim3(((a.nchunk + 7) / 8) * a.ncg * 8, 1, 3 * a.nrowgrp), B256, a));
+        a.narrow = narrow; a.nbcol0 = colbase + (u64)nfull * 64; a.nzcol0 = nfull * 64;
+        GTCHK(launch(c, GT_KC_COUNT, k_count<2>, dim3(((a.nchunk + 7) / 8) * (a.ncg + narrow) * 8, 1, 3 * a.nrowgrp), B256, a));
     }
     if (ncg1) {
+        a.narrow = 0;
         a.ncg = 1; a.ncoltiles = 1; a.bcol0 = colbase + (u64)nfull * 64; a.zcol0 = nfull * 64;
         GTCHK(launch(c, GT_KC_COUNT, k_count<1>, dim3(((a.nchunk + 7) / 8) * 8, 1, 3 * a.nrowgrp), B256, a));
     }
