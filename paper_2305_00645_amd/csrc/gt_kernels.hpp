@@ -261,33 +261,41 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 // that one wavefront writes per sample block and limb make up a whole 128-byte line
 // of the tile layout.
 struct XyArgs { KCommon c; P6 XT, YT; LimbSet B; u64 N, N8; u32 K, ncol; };
-__global__ __launch_bounds__(192, 3) void k_xy(XyArgs a)
+__global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
 {
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    const int p = party_of_wave(), lane = threadIdx.x;
+    // the zero-sharing words under key k_j are evaluated by party j's wavefront and read
+    // through LDS by party j-1, the other holder of k_j
+    __shared__ u64 s_prf[3][8 * GT_LANES];
+    const int p = party_of_wave(), lane = threadIdx.x, pn = p == 2 ? 0 : p + 1;
     LWire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = a.N8 / 8, nq = (a.ncol + 3) / 4, nt = (ngrp + 15) / 16;
-    for (u64 q = blockIdx.y; q < nq; q += gridDim.y) {
-        const u64 colq = q * 4 + (lane >> 4);
-        const bool cok = colq < a.ncol;
-        const u64 col = cok ? colq : 0, kx = col / a.K, cy = col % a.K;
-        for (u64 tile = blockIdx.x; tile < nt; tile += gridDim.x) {
-            const u64 g = tile * 16 + (lane & 15), i0 = g * 8;
-            const bool act = cok && g < ngrp;
+    // tiles outside, column quads inside: a workgroup meets the same class columns of Y
+    // again and again for one tile of samples (cache hits) and each value of X once
+    for (u64 tile = blockIdx.x; tile < nt; tile += gridDim.x) {
+        const u64 g = tile * 16 + (lane & 15), i0 = g * 8;
+        for (u64 q = blockIdx.y; q < nq; q += gridDim.y) {
+            const u64 colq = q * 4 + (lane >> 4);
+            const bool act = colq < a.ncol && g < ngrp;
+            const u64 col = act ? colq : 0, kx = col / a.K, cy = col % a.K;
             const u64 nv = act ? a.N : 0;               // rows start at multiples of 8
-            u64 ao[8], an[8], snd[8], rcv[8];
+            u64 ao[8], snd[8], rcv[8];
             const u64 blk = (col * a.N8 + i0) >> 3;
             chacha8(K.own, blk, a.c.op, 0, ao);
-            chacha8(K.nxt, blk, a.c.op, 0, an);
+#pragma unroll
+            for (int s = 0; s < 8; s++) s_prf[p][s * GT_LANES + lane] = ao[s];
             u64 xo[8], xn[8], yo[8], yn[8];
             ld8(own_of(a.XT, p) + kx * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + kx * a.N8, i0, nv, xn);
             ld8(own_of(a.YT, p) + cy * a.N8, i0, nv, yo); ld8(nxt_of(a.YT, p) + cy * a.N8, i0, nv, yn);
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const Sh x = { xo[s], xn[s] }, y = { yo[s], yn[s] };
-                snd[s] = prod3(x, y) + (ao[s] - an[s]);
+                snd[s] = prod3(x, y) + ao[s];
             }
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) snd[s] -= s_prf[pn][s * GT_LANES + lane];
             W.reshare<8>(snd, rcv);
             if (act) {
 #pragma unroll

@@ -442,7 +442,7 @@ static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shar
     // one-time products X[i][k] * Y[i][c] and the class columns, as limb tiles
     XyArgs a{}; a.c = kc(c, c->op++); a.XT = t->XT.v; a.YT = t->YT.v; a.B = limbs_B(t); a.N = N; a.N8 = N8; a.K = K;
     a.ncol = d * K;
-    const unsigned gy = std::min((a.ncol + 3) / 4, 1024u);
+    const unsigned gy = std::min((a.ncol + 3) / 4, 4u);
     const unsigned gx = (unsigned)std::max<u64>(1, std::min<u64>((N8 / 8 + 15) / 16, GT_MAX_BLOCKS / gy));
     GTCHK(launch(c, GT_KC_MULT, k_xy, dim3(gx, gy), GT_BLOCK, a));
     acct_reshare(c, (u64)N * d * K, 1);
