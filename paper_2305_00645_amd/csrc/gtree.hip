@@ -340,7 +340,7 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
         // lines of the limb tiles per store); all other grids one column per step
         a.lgs = (mode == GM_STORE && a.w % 4 == 0) ? 4 : 6;
         const u64 kstep = GT_LANES >> a.lgs, nsteps = (a.w + kstep - 1) / kstep;
-        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 8ull * g_resident;
+        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 4ull * g_resident;
         u64 nkc = std::min<u64>(nsteps, std::max<u64>(1, (want + ntile - 1) / ntile));
         a.kchunk = (u32)(((nsteps + nkc - 1) / nkc) * kstep);
         a.nkc = (a.w + a.kchunk - 1) / a.kchunk;
