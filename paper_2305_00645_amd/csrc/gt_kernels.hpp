@@ -494,8 +494,9 @@ __device__ __forceinline__ u32 mask63_packed(const u64 (&A)[8])
 template <int MODE, bool HAS_G, int NDOT>
 __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 {
-    // rows 0-2: r arithmetic components, then the mask words under k_0..k_2;
-    // rows 3-5: r Boolean components; rows 6-8: beta arithmetic components
+    // rows 0-2: r arithmetic components, then the messages of the opening, then the mask
+    // words under k_0..k_2; rows 3-5: r Boolean components, then the messages of the AND
+    // rounds and of the bit conversion; rows 6-8: beta arithmetic components
     __shared__ u64 s_mat[9][GT_TILE_EL];
     // beta Boolean components, packed per lane: bit 8j+s = component j of the lane's test s.
     // The dealer's lanes OR their bits in; two copies alternate between steps so that

@@ -335,11 +335,11 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
     a.ndot = ndot;
     const u64 nel = (u64)a.w * a.N;
     if (a.N && a.w) {
-        // enough work items to keep every resident workgroup slot busy for several rounds
         // the leaf one-hot grid takes four adjacent columns per step when it can (whole
         // lines of the limb tiles per store); all other grids one column per step
         a.lgs = (mode == GM_STORE && a.w % 4 == 0) ? 4 : 6;
         const u64 kstep = GT_LANES >> a.lgs, nsteps = (a.w + kstep - 1) / kstep;
+        // enough work items (tile, column range) to keep every resident workgroup slot busy for several rounds
         const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 4ull * g_resident;
         u64 nkc = std::min<u64>(nsteps, std::max<u64>(1, (want + ntile - 1) / ntile));
         a.kchunk = (u32)(((nsteps + nkc - 1) / nkc) * kstep);
