@@ -999,16 +999,20 @@ __device__ __forceinline__ void count_narrow(const CountArgs &a, int p, const Li
         }                                                                                     \
     }
 #define CN_MMA(AV, BV)                                                                        \
-    _Pragma("unroll") for (int u = 0; u < 8; u++)                                             \
-        _Pragma("unroll") for (int sl = 0; sl <= u; sl++)                                     \
+    _Pragma("unroll") for (int sl = 0; sl < 8; sl++)                                          \
+        _Pragma("unroll") for (int t = 0; t < 8 - sl; t++)                                    \
             _Pragma("unroll") for (int hh = 0; hh < 2; hh++)                                  \
-                acc[u][hh] = __builtin_amdgcn_mfma_i32_16x16x64_i8(AV[sl][hh], BV[u - sl], acc[u][hh], 0, 0, 0);
+                acc[sl + t][hh] = __builtin_amdgcn_mfma_i32_16x16x64_i8(AV[sl][hh], BV[t], acc[sl + t][hh], 0, 0, 0);
     CN_LOAD(av0, bv0, LA0, LB0, ib0)
     for (u64 ib = ib0; ib < ib1; ib += 2) {
         CN_LOAD(av1, bv1, LA1, LB1, ib)
+        __builtin_amdgcn_sched_barrier(0);
         CN_MMA(av0, bv0)
-        if (ib + 2 < ib1) { CN_LOAD(av0, bv0, LA0, LB0, ib + 2) }
+        __builtin_amdgcn_sched_barrier(0);
+        CN_LOAD(av0, bv0, LA0, LB0, (ib + 2 < ib1 ? ib + 2 : ib))   // always issued, see k_count
+        __builtin_amdgcn_sched_barrier(0);
         CN_MMA(av1, bv1)
+        __builtin_amdgcn_sched_barrier(0);
     }
 #undef CN_LOAD
 #undef CN_MMA
@@ -1076,17 +1080,27 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
         _Pragma("unroll") for (int nb = 0; nb < NB; nb++)                                     \
             BV[nb][s] = *(const v4i *)(LB.base + limb_addr(LB, IB, s, c0 + nb * 32) + offB);  \
     }
+    // limb s of the left operand against limbs 0..7-s of the right one: successive MFMAs
+    // go to different accumulators (level s+t), none waits for the one before it
 #define CT_MMA(AV, BV)                                                                        \
-    _Pragma("unroll") for (int u = 0; u < 8; u++)                                             \
-        _Pragma("unroll") for (int s = 0; s <= u; s++)                                        \
+    _Pragma("unroll") for (int s = 0; s < 8; s++)                                             \
+        _Pragma("unroll") for (int t = 0; t < 8 - s; t++)                                     \
             _Pragma("unroll") for (int nb = 0; nb < NB; nb++)                                 \
-                acc[u][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[nb][u - s], acc[u][nb], 0, 0, 0);
+                acc[s + t][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[nb][t], acc[s + t][nb], 0, 0, 0);
+    // the scheduling barriers keep the order loads-of-the-next-product, then this product's
+    // MFMAs: the scheduler would otherwise sink the loads to their uses to save registers
     CT_LOAD(av0, bv0, LA0, LB0, ib0)
     for (u64 ib = ib0; ib < ib1; ib++) {
         CT_LOAD(av1, bv1, LA1, LB1, ib)
+        __builtin_amdgcn_sched_barrier(0);
         CT_MMA(av0, bv0)
-        if (ib + 1 < ib1) { CT_LOAD(av0, bv0, LA0, LB0, ib + 1) }
+        __builtin_amdgcn_sched_barrier(0);
+        // always issued (the last one re-reads the chunk's last block and is not used): with a
+        // fixed number of loads in flight the wait before the next product leaves them pending
+        CT_LOAD(av0, bv0, LA0, LB0, (ib + 1 < ib1 ? ib + 1 : ib))
+        __builtin_amdgcn_sched_barrier(0);
         CT_MMA(av1, bv1)
+        __builtin_amdgcn_sched_barrier(0);
     }
 #undef CT_LOAD
 #undef CT_MMA
