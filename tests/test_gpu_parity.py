@@ -305,11 +305,14 @@ def test_infer_depth0(mods, seed):
     assert g.rec(Rg).tolist() == [3, 3]
 
 
-def test_single_level_from_imported_state(mods, seed):
+# the shapes reach the variants of the statistics contraction: few nodes; 128 nodes with a
+# remainder of 4 columns beside a full group of 64; 256 nodes with a remainder of 18 columns
+@pytest.mark.parametrize("N,d,K,h", [(5000, 12, 4, 3), (1500, 16, 4, 7), (700, 40, 2, 8)])
+def test_single_level_from_imported_state(mods, seed, N, d, K, h):
     """One split-scoring level started from a synthetic state (reduced C5 recipe)."""
     from oracle import X_M, X_C, X_SD, X_SCORE, X_F
     from paper_2305_00645_amd import workloads as wl
-    w = wl.c5_level(N=5000, d=12, K=4, h=3)
+    w = wl.c5_level(N=N, d=d, K=K, h=h)
     N, d, K, h = w["N"], w["d"], w["K"], w["h"]
     o, g = pair(mods, seed, K=K)
     xo, yo = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
