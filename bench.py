@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
 EQ_ALU_OPS = 700                # algorithmic 32-bit ALU ops per equality test, three parties: one dealer ChaCha8 block (400 ops) + 3 mask blocks per 8 tests = 550, protocol steps 3 x 50 on packed fields
-EQ_HBM_BYTES_MEASURED = 34.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
+EQ_HBM_BYTES_MEASURED = 29.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
 
 
 def paper_literal_ol_bytes(N, d, K, h, H, l=64):
