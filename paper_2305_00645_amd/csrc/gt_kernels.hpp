@@ -777,10 +777,11 @@ __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
     }
 }
 
-// One step of restoring division: b = [r >= Q]; r <- r - b Q; quo <- 2 quo + b.
-// first: r starts as S and quo as 0; otherwise r is doubled first.
-struct DivArgs { KCommon c; P6 S, Q, r, quo; u64 n; int first; };
-__global__ __launch_bounds__(192) void k_div_step(DivArgs a)
+// Restoring division, all steps of an element in one launch (the steps of different
+// elements do not interact): step t uses operation id op + t; b = [r >= Q]; r <- r - b Q;
+// quo <- 2 quo + b; r starts as S and is doubled between steps.
+struct DivArgs { KCommon c; P6 S, Q, r, quo; u64 n; u32 nsteps; };
+__global__ __launch_bounds__(192) void k_div(DivArgs a)
 {
     const int p = party_of_wave();
     Wire W; W.init(a.c.wire);
@@ -789,15 +790,17 @@ __global__ __launch_bounds__(192) void k_div_step(DivArgs a)
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
         Sh r = { 0, 0 }, Q = { 0, 0 }, quo = { 0, 0 };
-        if (act) {
-            Q = ld(a.Q, p, e);
-            if (a.first) r = ld(a.S, p, e);
-            else { r = scale(ld(a.r, p, e), 2); quo = ld(a.quo, p, e); }
+        if (act) { Q = ld(a.Q, p, e); r = ld(a.S, p, e); }
+        for (u32 t = 0; t < a.nsteps; t++) {
+            const u32 op = a.c.op + t;
+            if (t) r = scale(r, 2);
+            const Dealer D = dealer_of(K, p, op, e);
+            const Sh b = b2a(W, p, ge_bit(W, K, p, op, e, r - Q, D), D);
+            const Sh bq = mult_sh(W, b, Q, zero_a(K, op, 3, e));
+            r = r - bq;
+            quo = scale(quo, 2) + b;
         }
-        const Dealer D = dealer_of(K, p, a.c.op, e);
-        const Sh b = b2a(W, p, ge_bit(W, K, p, a.c.op, e, r - Q, D), D);
-        const Sh bq = mult_sh(W, b, Q, zero_a(K, a.c.op, 3, e));
-        if (act) { st(a.r, p, e, r - bq); st(a.quo, p, e, scale(quo, 2) + b); }
+        if (act) { st(a.r, p, e, r); st(a.quo, p, e, quo); }
     }
 }
 

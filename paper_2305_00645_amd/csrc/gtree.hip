@@ -386,11 +386,11 @@ extern "C" int gt_oaa(gt_ctx *c, const gt_shares *W, size_t w, const gt_shares *
 
 static int div_steps(gt_ctx *c, P6 S, P6 Q, P6 rem, P6 quo, u64 n)
 {
-    for (u32 t = 0; t <= c->tau; t++) {
-        DivArgs a{}; a.c = kc(c, c->op++); a.S = S; a.Q = Q; a.r = rem; a.quo = quo; a.n = n; a.first = t == 0;
-        if (n) GTCHK(launch(c, GT_KC_SMALL, k_div_step, dim3(tiles(n)), GT_BLOCK, a));
-        acct_ge(c, n); acct_b2a(c, n); acct_reshare(c, n, 1);
-    }
+    // tau+1 protocol steps, one operation id each, in one launch
+    DivArgs a{}; a.c = kc(c, c->op); a.S = S; a.Q = Q; a.r = rem; a.quo = quo; a.n = n; a.nsteps = c->tau + 1;
+    c->op += c->tau + 1;
+    if (n) GTCHK(launch(c, GT_KC_SMALL, k_div, dim3(tiles(n)), GT_BLOCK, a));
+    for (u32 t = 0; t <= c->tau; t++) { acct_ge(c, n); acct_b2a(c, n); acct_reshare(c, n, 1); }
     return GT_OK;
 }
 
