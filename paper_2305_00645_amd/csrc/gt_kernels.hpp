@@ -704,7 +704,14 @@ __global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
             chacha8(K.own, grp, a.c.op, 2 + q, ao);
             chacha8(K.nxt, grp, a.c.op, 2 + q, an);
 #pragma unroll
-            for (int s = 0; s < 8; s++) snd[s] = (i0 + s < nv ? a.dacc[(u64)(3 * q + p) * a.N8 + i0 + s] : 0) + (ao[s] - an[s]);
+            for (int s = 0; s < 8; s++) {
+                u64 part = 0;
+                if (i0 + s < nv) {                     // take the partial sum and leave zero for the next grid
+                    u64 *d = &a.dacc[(u64)(3 * q + p) * a.N8 + i0 + s];
+                    part = *d; *d = 0;
+                }
+                snd[s] = part + (ao[s] - an[s]);
+            }
             W.reshare<8>(snd, rcv);
 #pragma unroll
             for (int s = 0; s < 8; s++)
@@ -1132,7 +1139,9 @@ __global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
         const u64 o = GT_ELEM();
         const bool act = o < a.n;
         Sh z;
-        z.o = (act ? a.Zacc[(u64)p * a.n + o] : 0) + zero_a(K, a.c.op, 0, o);
+        u64 part = 0;
+        if (act) { part = a.Zacc[(u64)p * a.n + o]; a.Zacc[(u64)p * a.n + o] = 0; }   // zero again for the next contraction
+        z.o = part + zero_a(K, a.c.op, 0, o);
         z.n = W.reshare1(z.o);
         if (act) {
             const u64 idx = (o / a.ncol) * a.CW + a.colbase + o % a.ncol;

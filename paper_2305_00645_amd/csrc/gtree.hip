@@ -353,9 +353,10 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
                 c->dacc = nullptr; c->dacc_words = 0;
                 if (hipMalloc(&c->dacc, need * 8) != hipSuccess) return GT_ENOMEM;
                 c->dacc_words = need;
+                // zero once: k_dot_fin leaves every word it has read at zero again
+                HIPCHK(hipMemsetAsync(c->dacc, 0, need * 8, c->stream));
             }
             a.dacc = c->dacc;
-            HIPCHK(hipMemsetAsync(c->dacc, 0, (size_t)3 * ndot * a.N8 * 8, c->stream));
         }
         // more workgroups than fit at once: the hardware balances them over the compute units
         dim3 g((unsigned)std::min<u64>(ntile * a.nkc, GT_MAX_BLOCKS));
@@ -483,6 +484,8 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     };
     for (auto &pl : plan) { rc = dsh_alloc(*pl.v, pl.n, s); if (rc != GT_OK) break; }
     if (rc == GT_OK && hipMalloc(&t->Zacc, 3 * nmax * CW * 8) != hipSuccess) rc = GT_ENOMEM;
+    // zero once: k_count_fin leaves every word it has read at zero again
+    if (rc == GT_OK && hipMemsetAsync(t->Zacc, 0, 3 * nmax * CW * 8, s) != hipSuccess) rc = GT_EHIP;
     t->nblk = (N + 31) / 32;
     t->Lrows = std::max<size_t>(32, (nmax + 31) / 32 * 32);
     t->Brows = (CW + 63) / 64 * 64 + 64;
@@ -532,7 +535,6 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     const u32 ncol = totals_only ? t->K : t->CW;
     const u64 colbase = totals_only ? dK : 0;
     const u32 op = c->op++;
-    HIPCHK(hipMemsetAsync(t->Zacc, 0, 3 * nh * ncol * 8, c->stream));
     CountArgs a{}; a.L = limbs_L(t); a.B = limbs_B(t); a.nblk = t->nblk; a.nh = (u32)nh; a.ncol = ncol;
     a.Zacc = t->Zacc;
     // wavefront arrangement: 4, 2 or 1 row tiles of 32 per workgroup, the rest over columns
