@@ -202,6 +202,20 @@ def test_train_c1(mods, seed):
     same_stats(o, g)
 
 
+@pytest.mark.parametrize("keyseed", [1, 2])
+def test_other_protocol_keys(mods, keyseed):
+    """Fresh keys for all five roles: training, then inference with the trained tree."""
+    from paper_2305_00645_amd import workloads as wl
+    keys = np.random.default_rng(1000 + keyseed).integers(0, 1 << 63, size=(5, 4), dtype=np.uint64) * np.uint64(2) + np.uint64(keyseed & 1)
+    w = wl.c1_train(N=300, d=10, depth=3)
+    o, g, tree, (fo, lo) = run_train_pair(mods, keys, w, every_level=False)
+    I = (np.random.default_rng(keyseed).random((129, w["d"])) < 0.5).astype(np.uint64)
+    Ro = o.infer(fo, None, lo, w["H"], o.share(I.reshape(-1)), 129, w["d"])
+    Rg = g.infer_batch(tree, g.share_a(I.reshape(-1)), 129, w["d"])
+    same(Rg, Ro, "inference with other keys")
+    same_stats(o, g)
+
+
 def test_train_c2_depth7(mods, seed):
     from paper_2305_00645_amd import workloads as wl
     run_train_pair(mods, seed, wl.c2_train(), H=7, every_level=False)
