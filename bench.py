@@ -120,6 +120,8 @@ def main():
     ap.add_argument("--cpu-samples", type=int, default=500000, help="oracle sample for cpu_baseline (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the C3 training / C4 inference timings")
+    ap.add_argument("--only-paper-shapes", action="store_true",
+                    help="only the C3 training / C4 inference timings (for a kernel trace of those workloads)")
     ap.add_argument("--micro", action="store_true",
                     help="one launch of each hot kernel plus a calibration kernel of known traffic, for rocprofv3 --pmc")
     args = ap.parse_args()
@@ -136,6 +138,9 @@ def main():
 
     if args.micro:
         return micro(args, np, torch, gtree, wl)
+    if args.only_paper_shapes:
+        print(json.dumps({"paper_shape_workloads": paper_shapes(np, torch, gtree, wl)}))
+        return
     N, NI, d, K, h, Hinf = args.samples, args.instances, 64, 4, 7, 10
     H = h + 1
     CW = d * K + K

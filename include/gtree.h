@@ -5,8 +5,7 @@
  *
  * All three computing parties are simulated on ONE GPU.  Each party has its own
  * share buffers and keys; a message between parties is a store into a message
- * region on the device (a buffer in device memory, or the workgroup's LDS in the
- * two kernels that carry most messages) that the receiving party's wavefront
+ * region on the device (the workgroup's LDS) that the receiving party's wavefront
  * loads after a barrier; rounds and wire bytes are counted.  Offline material (edaBits, daBits) is derived from a
  * dealer key inside the kernels, because the paper times only the online phase
  * (Sec. VI).  This is a performance simulation, not a deployable secure system.

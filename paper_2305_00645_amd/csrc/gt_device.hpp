@@ -4,9 +4,8 @@
 // Execution model.  A workgroup is 3 wavefronts of 64 lanes: wavefront p IS party p
 // (threadIdx.y = p).  Lane l of each of the three wavefronts works on the same
 // element(s), each on its own party's two components.  A protocol message is a
-// store into the workgroup's message region (its part of the wire buffer in device
-// memory, or LDS in the kernels that carry most messages); the receiving wavefront
-// loads it after a workgroup barrier.  A party's lanes never
+// store into the workgroup's message region in LDS; the receiving wavefront loads it
+// after a workgroup barrier.  A party's lanes never
 // read another party's shares or keys, only the words sent to it.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -16,9 +15,6 @@ typedef uint64_t u64;
 typedef uint32_t u32;
 
 #define GT_LANES 64
-#define GT_XW 8                                   // max words per lane per message
-#define GT_SLOT_WORDS (3 * GT_XW * GT_LANES)      // one message slot: 3 senders
-#define GT_WIRE_WORDS_PER_BLOCK (2 * GT_SLOT_WORDS)
 #define GT_KEY_DEALER 3
 #define GT_KEY_OWNER 4
 
@@ -136,44 +132,11 @@ __device__ __forceinline__ int party_of_wave() { return __builtin_amdgcn_readfir
 // Message exchange inside the workgroup.  `reshare`: every party sends to its
 // predecessor (after a product, so that the receiver then holds (z_p, z_{p+1}));
 // `open`: every party sends to its successor (it hands over its first component).
-// Two slots alternate so that one barrier per message suffices.
-struct Wire {
-    u64 *base;   // this workgroup's region
-    int slot, p, lane;
-    __device__ __forceinline__ void init(u64 *wire)
-    {
-        base = wire + (size_t)blockIdx.x * GT_WIRE_WORDS_PER_BLOCK;
-        slot = 0; p = party_of_wave(); lane = threadIdx.x;
-    }
-    __device__ __forceinline__ void init2d(u64 *wire)         // grid (x, y): one region per workgroup
-    {
-        base = wire + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * GT_WIRE_WORDS_PER_BLOCK;
-        slot = 0; p = party_of_wave(); lane = threadIdx.x;
-    }
-    template <int NW>
-    __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
-    {
-        static_assert(NW <= GT_XW, "message too wide");
-        u64 *buf = base + slot * GT_SLOT_WORDS;
-        slot ^= 1;
-#pragma unroll
-        for (int j = 0; j < NW; j++) buf[(p * GT_XW + j) * GT_LANES + lane] = snd[j];
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < NW; j++) rcv[j] = buf[(from * GT_XW + j) * GT_LANES + lane];
-    }
-    template <int NW>
-    __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }
-    template <int NW>
-    __device__ __forceinline__ void open(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 0 ? 2 : p - 1); }
-    __device__ __forceinline__ u64 reshare1(u64 v) { u64 s[1] = { v }, r[1]; reshare<1>(s, r); return r[0]; }
-    __device__ __forceinline__ u64 open1(u64 v) { u64 s[1] = { v }, r[1]; open<1>(s, r); return r[0]; }
-};
-
-// The same message exchange through a region of LDS of GT_LWIRE_WORDS words that the
-// workgroup owns: two alternating slots for messages of up to four words per lane; a
-// message of eight words takes the whole region (the caller separates it from its
-// neighbours by barriers of its own).
+// The message region is GT_LWIRE_WORDS words of LDS that the workgroup owns: two
+// alternating slots for messages of up to four words per lane, so that one barrier per
+// message suffices (a slot is rewritten only after the barrier of the message that
+// followed it); a message of more than four words takes the whole region and is
+// followed by a second barrier, after which the region may be written again.
 #define GT_LWIRE_SLOT (3 * 4 * GT_LANES)
 #define GT_LWIRE_WORDS (2 * GT_LWIRE_SLOT)
 struct LWire {
@@ -192,6 +155,7 @@ struct LWire {
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < NW; j++) rcv[j] = buf[(from * XW + j) * GT_LANES + lane];
+        if (NW > 4) __syncthreads();
     }
     template <int NW>
     __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }
@@ -200,6 +164,7 @@ struct LWire {
     __device__ __forceinline__ u64 reshare1(u64 v) { u64 s[1] = { v }, r[1]; reshare<1>(s, r); return r[0]; }
     __device__ __forceinline__ u64 open1(u64 v) { u64 s[1] = { v }, r[1]; open<1>(s, r); return r[0]; }
 };
+typedef LWire Wire;
 
 // ---------------------------------------------------------------------------------
 // Offline material of one element, party p's components (dealer stream 0, block e).

@@ -1,6 +1,5 @@
 // Kernels of the GTree hot path for gfx950.  See gt_device.hpp for the execution
-// model (workgroup = 3 wavefronts = 3 parties; messages through the workgroup's region
-// of the wire buffer or through LDS).
+// model (workgroup = 3 wavefronts = 3 parties; messages through LDS).
 #pragma once
 #include "gt_device.hpp"
 
@@ -12,7 +11,7 @@
     for (u64 tile_ = blockIdx.x, ntiles_ = ((u64)(n) + GT_LANES - 1) / GT_LANES; tile_ < ntiles_; tile_ += gridDim.x)
 #define GT_ELEM() (tile_ * GT_LANES + threadIdx.x)
 
-struct KCommon { const u32 *keys; u64 *wire; u32 op; };
+struct KCommon { const u32 *keys; u32 op; };
 
 __device__ __forceinline__ P6 p6_off(P6 a, size_t off)
 {
@@ -219,7 +218,8 @@ template <int MODE>
 __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 {
     const int p = party_of_wave(), lane = threadIdx.x;
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = (a.n + 7) / 8;
     for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
@@ -303,7 +303,6 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
                 store_limbs8(a.B.m[p][0], col, i0, snd);
                 store_limbs8(a.B.m[p][1], col, i0, rcv);
             }
-            __syncthreads();                            // the message region is rewritten next
         }
     }
 }
@@ -503,9 +502,9 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     // one can be cleared while the other is in use.
     __shared__ u32 s_bitw[2][GT_LANES];
     const int p = party_of_wave(), lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1, pp = p == 0 ? 2 : p - 1;
-    Wire W; W.init(a.c.wire);
     // messages of the AND rounds and of the bit conversion pass through the rows of the
-    // Boolean edaBit components, which are dead once t has been formed
+    // Boolean edaBit components, which are dead once t has been formed; so do the
+    // reshared inner products at the end of a work item
     LWire LW; LW.init(&s_mat[3][0]);
     static_assert(GT_LWIRE_WORDS <= 3 * GT_TILE_EL, "LDS wire does not fit the rows it reuses");
     const PartyKeys K = load_party_keys(a.c.keys, p);
@@ -664,7 +663,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             chacha8(K.nxt, grp, op, 2, an);
 #pragma unroll
             for (int s = 0; s < 8; s++) snd[s] = acc[s] + (ao[s] - an[s]);
-            W.reshare<8>(snd, rcv);
+            LW.reshare<8>(snd, rcv);
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 if (actg && i0 + s < a.N) {
@@ -678,7 +677,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 chacha8(K.nxt, grp, op, 3, an);
 #pragma unroll
                 for (int s = 0; s < 8; s++) snd[s] = acc2[s] + (ao[s] - an[s]);
-                W.reshare<8>(snd, rcv);
+                LW.reshare<8>(snd, rcv);
 #pragma unroll
                 for (int s = 0; s < 8; s++)
                     if (actg && i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.out2, p, i0 + s, z); }
@@ -692,7 +691,8 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 __global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
 {
     const int p = party_of_wave(), lane = threadIdx.x;
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = a.N8 / 8;
     const Sh one = pub(p, 1);
@@ -733,7 +733,8 @@ template <bool BOOL_OUT>
 __global__ __launch_bounds__(192) void k_eq(EqArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -753,7 +754,8 @@ struct GeArgs { KCommon c; P6 x, y, z; u64 n; };
 __global__ __launch_bounds__(192) void k_ge(GeArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -771,7 +773,8 @@ struct CmpArgs { KCommon c; P6 th, x, tidx; u64 n; };
 __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -791,7 +794,8 @@ struct DivArgs { KCommon c; P6 S, Q, r, quo; u64 n; u32 nsteps; };
 __global__ __launch_bounds__(192) void k_div(DivArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -817,7 +821,8 @@ struct PrepArgs { KCommon c; P6 C, S, Q; u64 n; u32 d, K, CW; };
 __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 dK = (u64)a.d * a.K;
     GT_FOR_TILES(a.n) {
@@ -846,7 +851,8 @@ struct MaskArgs { KCommon c; P6 quo, gamma, score, val; u64 n; u32 d, P2; };
 __global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -867,7 +873,8 @@ struct SelArgs { KCommon c; P6 vin, iin, vout, iout, C; u64 n; u32 len, CW; u64 
 __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -898,7 +905,8 @@ struct GammaArgs { KCommon c; P6 SD, gamma; u64 n; u32 d; };
 __global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
@@ -919,7 +927,8 @@ struct SplitArgs { KCommon c; P6 C, isLeaf, F, split; u64 n, base; u32 K, CW; u6
 __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 r = GT_ELEM();
@@ -1133,7 +1142,8 @@ struct CountFinArgs { KCommon c; u64 *Zacc; P6 C; u64 n; u32 ncol, CW; u64 colba
 __global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
 {
     const int p = party_of_wave();
-    Wire W; W.init(a.c.wire);
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    Wire W; W.init(s_wire);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     GT_FOR_TILES(a.n) {
         const u64 o = GT_ELEM();

@@ -28,7 +28,6 @@ struct gt_ctx {
     u32 op;
     hipStream_t stream;
     u32 *keys_d;
-    u64 *wire;
     gt_stats acc;
     hipEvent_t ev0, ev1;
     bool timing;
@@ -154,7 +153,7 @@ struct Timed {                // times one API call with events on the context's
     ~Timed() { if (on) { c->timing = false; } }
 };
 
-static KCommon kc(gt_ctx *c, u32 op) { KCommon k; k.keys = c->keys_d; k.wire = c->wire; k.op = op; return k; }
+static KCommon kc(gt_ctx *c, u32 op) { KCommon k; k.keys = c->keys_d; k.op = op; return k; }
 
 // Every kernel goes through here.  With GT_FLAG_PROFILE the launch is bracketed by a
 // pair of events of its kernel class; the pairs are resolved when the API call ends.
@@ -197,7 +196,7 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (prm->K < 1 || prm->K > GT_MAX_K || prm->tau < 1 || prm->tau > GT_MAX_TAU) return GT_EINVAL;
     gt_ctx *c = new (std::nothrow) gt_ctx();
     if (!c) return GT_ENOMEM;
-    c->op = 0; c->timing = false; c->ev_used = 0; c->keys_d = nullptr; c->wire = nullptr; c->dacc = nullptr; c->dacc_words = 0;
+    c->op = 0; c->timing = false; c->ev_used = 0; c->keys_d = nullptr; c->dacc = nullptr; c->dacc_words = 0;
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     c->profile = (prm->flags & GT_FLAG_PROFILE) != 0;
     c->tau = prm->tau; c->K = prm->K; c->stream = (hipStream_t)prm->hip_stream;
@@ -208,10 +207,9 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
         g_resident = std::min<unsigned>(GT_MAX_BLOCKS, 4u * (unsigned)cus);
     if (hipMalloc(&c->keys_d, sizeof keys) != hipSuccess) { delete c; return GT_ENOMEM; }
-    if (hipMalloc(&c->wire, (size_t)GT_MAX_BLOCKS * GT_WIRE_WORDS_PER_BLOCK * 8) != hipSuccess) { (void)hipFree(c->keys_d); delete c; return GT_ENOMEM; }
     if (hipMemcpy(c->keys_d, keys, sizeof keys, hipMemcpyHostToDevice) != hipSuccess ||
         hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) {
-        (void)hipFree(c->keys_d); (void)hipFree(c->wire); delete c; return GT_EHIP;
+        (void)hipFree(c->keys_d); delete c; return GT_EHIP;
     }
     *out = c;
     return GT_OK;
@@ -225,7 +223,7 @@ extern "C" int gt_ctx_destroy(gt_ctx *c)
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (DSh &w : c->ws) dsh_free(w);
     if (c->dacc) (void)hipFree(c->dacc);
-    (void)hipFree(c->keys_d); (void)hipFree(c->wire);
+    (void)hipFree(c->keys_d);
     delete c;
     return GT_OK;
 }
