@@ -45,7 +45,7 @@ extern "C" {
 #define GT_MAX_K 16u           /* classes */
 #define GT_MAX_TAU 20u         /* fractional bits of the Gini quotients */
 
-typedef struct gt_ctx gt_ctx;     /* keys, operation counter, stream, message buffers */
+typedef struct gt_ctx gt_ctx;     /* keys, operation counter, stream, scratch for partial sums */
 typedef struct gt_train gt_train; /* per-party shares of T, F, M, C, gamma and the data */
 typedef struct gt_tree gt_tree;   /* per-party shares of feature ids [, thresholds], labels */
 
