@@ -71,14 +71,18 @@ __device__ __forceinline__ Key load_key(const u32 *keys, int idx)
 
 // The keys one party may use: its two pairwise keys (Sec. III) and, in this
 // simulation, the dealer key from which the offline material is derived.
-struct PartyKeys { Key own, nxt, dlr; };
+// scr: this wavefront's 8 x 64 words of LDS for handing PRF words round its lanes
+// (kernels with one element per lane, see prf_tile), else null.
+struct PartyKeys { Key own, nxt, dlr; u64 *scr; };
+#define GT_PRF_SCRATCH_WORDS (8 * GT_LANES)
 
-__device__ __forceinline__ PartyKeys load_party_keys(const u32 *keys, int p)
+__device__ __forceinline__ PartyKeys load_party_keys(const u32 *keys, int p, u64 *scr = nullptr)
 {
     PartyKeys K;
     K.own = load_key(keys, p);
     K.nxt = load_key(keys, p == 2 ? 0 : p + 1);
     K.dlr = load_key(keys, GT_KEY_DEALER);
+    K.scr = scr;
     return K;
 }
 
@@ -90,14 +94,62 @@ __device__ __forceinline__ u64 prf_word(const Key &k, u32 op, u32 stream, u64 j)
     return sel8(w, (u32)j & 7);
 }
 
+// Words of NS streams under the own and the next key for a tile of 64 consecutive
+// elements, element 64*tile + lane in lane `lane` (every kernel with one element per
+// lane indexes that way, and all 64 lanes call together).  A block of the PRF holds
+// the words of 8 consecutive elements, so the tile needs 8 blocks per key and stream:
+// lane l < 16*NS evaluates block l%8 of stream (l/16), own key if (l/8) is even, next key
+// otherwise, and leaves its 8 words in the wavefront's scratch; then every lane picks
+// its own.  One pass of the block function instead of 2*NS.  LDS operations of one
+// wavefront complete in order, so no barrier is needed.
+template <int NS>
+__device__ __forceinline__ void prf_tile(const PartyKeys &K, u32 op, const u32 (&st)[NS], u64 e, u64 (&wo)[NS], u64 (&wn)[NS])
+{
+    static_assert(NS >= 1 && NS <= 4, "at most 8 key/stream pairs per pass");
+    const u32 lane = threadIdx.x, c = lane >> 3;
+    if (c < 2 * NS) {
+        // selections by masks: plain ALU work on the scalar key words
+        const u32 mk = 0u - (c & 1);
+        Key kv;
+#pragma unroll
+        for (int i = 0; i < 8; i++) kv.k[i] = K.own.k[i] ^ ((K.own.k[i] ^ K.nxt.k[i]) & mk);
+        u32 stream = 0;
+#pragma unroll
+        for (int q = 0; q < NS; q++) stream |= st[q] & (0u - (u32)((c >> 1) == (u32)q));
+        u64 blk[8];
+        chacha8(kv, (e >> 6) * 8 + (lane & 7), op, stream, blk);
+#pragma unroll
+        for (int i = 0; i < 8; i++) K.scr[c * GT_LANES + (lane & 7) * 8 + i] = blk[i];
+    }
+#pragma unroll
+    for (int q = 0; q < NS; q++) { wo[q] = K.scr[(2 * q) * GT_LANES + lane]; wn[q] = K.scr[(2 * q + 1) * GT_LANES + lane]; }
+}
+
 // party p's component of the zero sharing of element e: arithmetic / Boolean
 __device__ __forceinline__ u64 zero_a(const PartyKeys &K, u32 op, u32 stream, u64 e)
 {
-    return prf_word(K.own, op, stream, e) - prf_word(K.nxt, op, stream, e);
+    const u32 st[1] = { stream }; u64 wo[1], wn[1];
+    prf_tile<1>(K, op, st, e, wo, wn);
+    return wo[0] - wn[0];
 }
 __device__ __forceinline__ u64 zero_b(const PartyKeys &K, u32 op, u32 stream, u64 e)
 {
-    return prf_word(K.own, op, stream, e) ^ prf_word(K.nxt, op, stream, e);
+    const u32 st[1] = { stream }; u64 wo[1], wn[1];
+    prf_tile<1>(K, op, st, e, wo, wn);
+    return wo[0] ^ wn[0];
+}
+// two streams in one pass
+__device__ __forceinline__ void zero_a2(const PartyKeys &K, u32 op, u32 s0, u32 s1, u64 e, u64 &z0, u64 &z1)
+{
+    const u32 st[2] = { s0, s1 }; u64 wo[2], wn[2];
+    prf_tile<2>(K, op, st, e, wo, wn);
+    z0 = wo[0] - wn[0]; z1 = wo[1] - wn[1];
+}
+__device__ __forceinline__ void zero_b2(const PartyKeys &K, u32 op, u32 s0, u32 s1, u64 e, u64 &z0, u64 &z1)
+{
+    const u32 st[2] = { s0, s1 }; u64 wo[2], wn[2];
+    prf_tile<2>(K, op, st, e, wo, wn);
+    z0 = wo[0] ^ wn[0]; z1 = wo[1] ^ wn[1];
 }
 
 // ---------------------------------------------------------------------------------
@@ -249,7 +301,8 @@ __device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op,
     E.o = D.rho.o & LOW63;      E.n = D.rho.n & LOW63;
     if (p == 0) E.o = ((D.rho.o ^ nc) & LOW63) | TOP;
     if (p == 2) E.n = ((D.rho.n ^ nc) & LOW63) | TOP;
-    const u64 AG = zero_b(K, op, 1, e), AE = zero_b(K, op, 2, e);
+    u64 AG, AE;
+    zero_b2(K, op, 1, 2, e, AG, AE);
 #pragma unroll
     for (int k = 0; k < 6; k++) {
         const int s = 1 << k;

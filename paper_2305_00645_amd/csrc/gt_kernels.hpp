@@ -735,7 +735,8 @@ __global__ __launch_bounds__(192) void k_eq(EqArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -756,7 +757,8 @@ __global__ __launch_bounds__(192) void k_ge(GeArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -775,7 +777,8 @@ __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -796,7 +799,8 @@ __global__ __launch_bounds__(192) void k_div(DivArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -823,7 +827,8 @@ __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     const u64 dK = (u64)a.d * a.K;
     GT_FOR_TILES(a.n) {
         const u64 q = GT_ELEM();
@@ -839,7 +844,9 @@ __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
                 s += prod3(njc, njc);
             }
         }
-        u64 snd[2] = { s + zero_a(K, a.c.op, 0, q), prod3(nj, n) + zero_a(K, a.c.op, 1, q) }, rcv[2];
+        u64 z0, z1;
+        zero_a2(K, a.c.op, 0, 1, q, z0, z1);
+        u64 snd[2] = { s + z0, prod3(nj, n) + z1 }, rcv[2];
         W.reshare<2>(snd, rcv);
         if (act) { Sh S = { snd[0], rcv[0] }, Q = { snd[1], rcv[1] }; st(a.S, p, q, S); st(a.Q, p, q, Q); }
     }
@@ -853,7 +860,8 @@ __global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -875,7 +883,8 @@ __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -891,7 +900,9 @@ __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
         }
         const Dealer D = dealer_of(K, p, a.c.op, e);
         const Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, L - R, D)), D);
-        u64 snd[2] = { prod3(b, R - L) + zero_a(K, a.c.op, 3, e), prod3(b, IR - IL) + zero_a(K, a.c.op, 4, e) }, rcv[2];
+        u64 z3, z4;
+        zero_a2(K, a.c.op, 3, 4, e, z3, z4);
+        u64 snd[2] = { prod3(b, R - L) + z3, prod3(b, IR - IL) + z4 }, rcv[2];
         W.reshare<2>(snd, rcv);
         if (act) {
             Sh dv = { snd[0], rcv[0] }, di = { snd[1], rcv[1] };
@@ -907,7 +918,8 @@ __global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 e = GT_ELEM();
         const bool act = e < a.n;
@@ -929,7 +941,8 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 r = GT_ELEM();
         const bool act = r < a.n;
@@ -1144,7 +1157,8 @@ __global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
     Wire W; W.init(s_wire);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
         const u64 o = GT_ELEM();
         const bool act = o < a.n;
