@@ -320,8 +320,11 @@ def test_infer_depth0(mods, seed):
 
 
 # the shapes reach the variants of the statistics contraction: few nodes; 128 nodes with a
-# remainder of 4 columns beside a full group of 64; 256 nodes with a remainder of 18 columns
-@pytest.mark.parametrize("N,d,K,h", [(5000, 12, 4, 3), (1500, 16, 4, 7), (700, 40, 2, 8)])
+# remainder of 4 columns beside a full group of 64; 256 nodes with a remainder of 18 columns;
+# exactly 64 columns; 64 nodes (two row tiles per workgroup) with a remainder above 32
+# columns; 32 nodes (one row tile per workgroup) with exactly 64 columns
+@pytest.mark.parametrize("N,d,K,h", [(5000, 12, 4, 3), (1500, 16, 4, 7), (700, 40, 2, 8),
+                                     (900, 15, 4, 7), (900, 24, 4, 6), (600, 31, 2, 5)])
 def test_single_level_from_imported_state(mods, seed, N, d, K, h):
     """One split-scoring level started from a synthetic state (reduced C5 recipe)."""
     from oracle import X_M, X_C, X_SD, X_SCORE, X_F
