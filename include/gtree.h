@@ -15,8 +15,14 @@
  *    caller, of `n` 64-bit words.  party[p].own holds component p, party[p].next
  *    component p+1 mod 3 (Sec. II-B: P_i holds (x_i, x_{i+1})).
  *  - `plain` buffers are device memory too.
- *  - Calls are enqueued on the context's HIP stream; gt_stats_get and the
- *    destroy calls synchronise with it.  Calls on one context must not overlap.
+ *  - Calls only enqueue work on the context's HIP stream and return; gt_stats_get,
+ *    gt_prof_get, gt_stats_reset and the destroy calls wait for it.  Calls on one
+ *    context must not overlap.  Device memory is allocated by the create/import calls;
+ *    gt_train_level, gt_train_finish and gt_train_reset allocate nothing (the tree that
+ *    gt_train_finish returns uses buffers made by gt_train_create, unless the tree of an
+ *    earlier finish of the same object is still alive); gt_infer_batch, gt_oaa and
+ *    gt_div keep a workspace in the context that grows on first use or for a larger
+ *    batch (then they wait for the stream and allocate).
  *  - Return value 0 = success, negative = error; nothing is thrown or aborted.
  *    After an error the output buffers are unspecified; the context stays usable
  *    unless the error is GT_EHIP.
@@ -53,9 +59,12 @@ typedef struct { uint64_t *own, *next; } gt_plane2;
 typedef struct { gt_plane2 party[3]; size_t n; } gt_shares;
 
 /* rounds: protocol rounds; wire_bytes[a][b]: bytes party a sent to party b, each
- * message of n elements of w bits counted as ceil(n*w/8); kernel_ms: GPU time of
- * the calls, from HIP events on the context's stream. */
-typedef struct { uint64_t rounds; uint64_t wire_bytes[3][3]; double kernel_ms; } gt_stats;
+ * message of n elements of w bits counted as ceil(n*w/8) from the public sizes on the
+ * host; wire_bits_dev[a][b]: payload bits of the same messages counted by the kernels
+ * where they store them (per element that exists, so padding lanes count nothing);
+ * kernel_ms: GPU time of the launches, from HIP events on the context's stream
+ * (only with GT_FLAG_PROFILE, otherwise 0). */
+typedef struct { uint64_t rounds; uint64_t wire_bytes[3][3]; uint64_t wire_bits_dev[3][3]; double kernel_ms; } gt_stats;
 
 /* tau: fractional bits of the fixed-point Gini quotients (Sec. V-B); K: classes;
  * seed[0..2]: pairwise keys k1..k3 (party p uses seed[p], seed[p+1 mod 3], Sec. III),
@@ -69,16 +78,20 @@ typedef struct {
 } gt_params;
 
 /* GT_FLAG_PROFILE: bracket every kernel launch with a pair of HIP events on the
- * context's stream and accumulate time and launch count per kernel class. */
+ * context's stream and accumulate time and launch count per kernel class; the pairs
+ * are read when the times are asked for (gt_prof_get, gt_stats_get). */
 #define GT_FLAG_PROFILE 1u
 enum {
     GT_KC_SHARE = 0, /* share / reconstruct */
     GT_KC_MULT = 1,  /* elementwise products with reshare */
-    GT_KC_EQGRID = 2,/* equality grid (+ conversion, + inner product) of the array access */
+    GT_KC_EQGRID = 2,/* equality grid with inner product against a shared array (array access over a
+                        tree level or the leaf labels) */
     GT_KC_COUNT = 3, /* statistics contraction */
     GT_KC_SMALL = 4, /* per-node protocols: division, arg-max, updates */
     GT_KC_LOCAL = 5, /* copies, transposes, fills (no messages) */
-    GT_KC_N = 6
+    GT_KC_EQGRID_ROWS = 6,  /* equality grid with inner product against the sample's own row */
+    GT_KC_EQGRID_STORE = 7, /* equality grid that stores the per-sample leaf one-hot */
+    GT_KC_N = 8
 };
 typedef struct { double ms[GT_KC_N]; uint64_t launches[GT_KC_N]; } gt_prof;
 

@@ -29,6 +29,7 @@ struct orc_ctx {
     u32 op;          /* operation counter, one per protocol invocation */
     u64 rounds;
     u64 wire[3][3];  /* bytes sent from party a to party b */
+    u64 bits[3][3];  /* the same messages in payload bits, n*bits per message with no rounding */
 };
 
 /* ------------------------------------------------------------------------- */
@@ -163,7 +164,10 @@ void orc_dealer(const orc_ctx *c, uint32_t op, uint64_t e, uint64_t out[14])
 static void wire(orc_ctx *c, int dir, u64 n, u64 bits)
 {
     u64 bytes = (n * bits + 7) / 8;
-    for (int p = 0; p < 3; p++) c->wire[p][(p + dir + 3) % 3] += bytes;
+    for (int p = 0; p < 3; p++) {
+        c->wire[p][(p + dir + 3) % 3] += bytes;
+        c->bits[p][(p + dir + 3) % 3] += n * bits;
+    }
 }
 
 /* ------------------------------------------------------------------------- */
@@ -330,7 +334,11 @@ void orc_stats(const orc_ctx *c, uint64_t *rounds, uint64_t wire_bytes[9])
     *rounds = c->rounds;
     for (int a = 0; a < 3; a++) for (int b = 0; b < 3; b++) wire_bytes[3 * a + b] = c->wire[a][b];
 }
-void orc_stats_reset(orc_ctx *c) { c->rounds = 0; memset(c->wire, 0, sizeof c->wire); }
+void orc_stats_bits(const orc_ctx *c, uint64_t wire_bits[9])
+{
+    for (int a = 0; a < 3; a++) for (int b = 0; b < 3; b++) wire_bits[3 * a + b] = c->bits[a][b];
+}
+void orc_stats_reset(orc_ctx *c) { c->rounds = 0; memset(c->wire, 0, sizeof c->wire); memset(c->bits, 0, sizeof c->bits); }
 uint32_t orc_op_counter(const orc_ctx *c) { return c->op; }
 void orc_set_threads(int n)
 {
@@ -632,6 +640,7 @@ struct orc_train {
     sh SD, split;          /* n_h */
     sh Clast, Glast, Slast;/* copies kept for export */
     u32 last;              /* level the copies belong to */
+    int fresh_import;      /* state was imported and no level has run since: the copies are not valid */
 };
 
 static size_t nodes_upto(u32 H) { return ((size_t)2 << H) - 1; }
@@ -941,6 +950,7 @@ int orc_train_level(orc_ctx *c, orc_train *t, uint32_t h)
     heuristic(c, t, h);
     update(c, t, h);
     t->level = h + 1;
+    t->fresh_import = 0;
     return 0;
 }
 
@@ -968,6 +978,7 @@ int orc_train_finish(orc_ctx *c, orc_train *t, uint64_t *feat, uint64_t *leaf)
     for (int j = 0; j < 3; j++) memcpy(t->Clast.c[j], t->C.c[j], nh * CW * 8);
     t->last = H;
     t->level = H + 1;
+    t->fresh_import = 0;
     for (int j = 0; j < 3; j++) {
         if (feat) memcpy(feat + (size_t)j * base, t->T.c[j], base * 8);
         if (leaf) memcpy(leaf + (size_t)j * nh, t->T.c[j] + base, nh * 8);
@@ -976,8 +987,15 @@ int orc_train_finish(orc_ctx *c, orc_train *t, uint64_t *feat, uint64_t *leaf)
     return 0;
 }
 
+static int of_last_level(int what)
+{
+    return what == ORC_X_C || what == ORC_X_GAMMA || what == ORC_X_SD || what == ORC_X_L ||
+           what == ORC_X_SCORE || what == ORC_X_C_PAPER;
+}
+
 size_t orc_train_export_size(const orc_train *t, int what)
 {
+    if (t->fresh_import && of_last_level(what)) return 0;
     size_t nh = (size_t)1 << t->last;
     switch (what) {
     case ORC_X_T: case ORC_X_F: return nodes_upto(t->H);
@@ -993,6 +1011,7 @@ size_t orc_train_export_size(const orc_train *t, int what)
 
 int orc_train_export(const orc_train *t, int what, uint64_t *comp)
 {
+    if (t->fresh_import && of_last_level(what)) return -1;
     size_t n = orc_train_export_size(t, what);
     const sh *src = NULL;
     switch (what) {
@@ -1043,6 +1062,7 @@ int orc_train_import(orc_train *t, uint32_t h, const uint64_t *M, const uint64_t
         memcpy(t->gamma.c[j], gamma + (size_t)j * nh * t->d, nh * t->d * 8);
     }
     t->level = h;
+    t->fresh_import = 1;
     return 0;
 }
 

@@ -55,6 +55,8 @@ enum {
 orc_ctx *orc_ctx_create(const uint64_t seed[5][4], uint32_t tau, uint32_t K);
 void orc_ctx_destroy(orc_ctx *);
 void orc_stats(const orc_ctx *, uint64_t *rounds, uint64_t wire_bytes[9]);
+/* payload bits of the same messages, n*bits per message without rounding up to bytes */
+void orc_stats_bits(const orc_ctx *c, uint64_t wire_bits[9]);
 void orc_stats_reset(orc_ctx *);
 uint32_t orc_op_counter(const orc_ctx *);
 void orc_set_threads(int n); /* OpenMP threads for the element loops; 0 = default */

@@ -48,6 +48,7 @@ def _load():
         "orc_ctx_create": (vp, [_u64p, u32, u32]),
         "orc_ctx_destroy": (None, [vp]),
         "orc_stats": (None, [vp, _u64p, _u64p]),
+        "orc_stats_bits": (None, [vp, _u64p]),
         "orc_stats_reset": (None, [vp]),
         "orc_op_counter": (u32, [vp]),
         "orc_set_threads": (None, [i]),
@@ -138,6 +139,12 @@ class Oracle:
         w = np.zeros(9, dtype=np.uint64)
         self.L.orc_stats(self.ctx, C.byref(r), _p(w))
         return int(r.value), w.reshape(3, 3).copy()
+
+    def wire_bits(self):
+        """(3, 3) payload bits per directed pair."""
+        w = np.zeros(9, dtype=np.uint64)
+        self.L.orc_stats_bits(self.ctx, _p(w))
+        return w.reshape(3, 3).copy()
 
     def stats_reset(self):
         self.L.orc_stats_reset(self.ctx)

@@ -101,12 +101,15 @@ __device__ __forceinline__ u64 prf_word(const Key &k, u32 op, u32 stream, u64 j)
 // lane l < 16*NS evaluates block l%8 of stream (l/16), own key if (l/8) is even, next key
 // otherwise, and leaves its 8 words in the wavefront's scratch; then every lane picks
 // its own.  One pass of the block function instead of 2*NS.  LDS operations of one
-// wavefront complete in order, so no barrier is needed.
+// wavefront complete in order, so no hardware barrier is needed; the wavefront-scope
+// fences keep the compiler from moving the loads of other lanes' words across the stores.
 template <int NS>
 __device__ __forceinline__ void prf_tile(const PartyKeys &K, u32 op, const u32 (&st)[NS], u64 e, u64 (&wo)[NS], u64 (&wn)[NS])
 {
     static_assert(NS >= 1 && NS <= 4, "at most 8 key/stream pairs per pass");
     const u32 lane = threadIdx.x, c = lane >> 3;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the previous call's loads come first
+    __builtin_amdgcn_wave_barrier();
     if (c < 2 * NS) {
         // selections by masks: plain ALU work on the scalar key words
         const u32 mk = 0u - (c & 1);
@@ -121,6 +124,8 @@ __device__ __forceinline__ void prf_tile(const PartyKeys &K, u32 op, const u32 (
 #pragma unroll
         for (int i = 0; i < 8; i++) K.scr[c * GT_LANES + (lane & 7) * 8 + i] = blk[i];
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int q = 0; q < NS; q++) { wo[q] = K.scr[(2 * q) * GT_LANES + lane]; wn[q] = K.scr[(2 * q + 1) * GT_LANES + lane]; }
 }
@@ -191,10 +196,24 @@ __device__ __forceinline__ int party_of_wave() { return __builtin_amdgcn_readfir
 // followed by a second barrier, after which the region may be written again.
 #define GT_LWIRE_SLOT (3 * 4 * GT_LANES)
 #define GT_LWIRE_WORDS (2 * GT_LWIRE_SLOT)
+// Every send states how many payload bits the lane's message carries (0 for a lane whose
+// element does not exist); the lane adds them up per direction, the sums are collected
+// per party in six words of LDS (drain) and handed to the context's counters when the
+// kernel ends (flush), so that the bytes reported for a call are counted where the
+// messages are stored, not derived from the sizes on the host.  Party p's wavefront is the
+// only one that touches words 2p and 2p+1 of the LDS counters, and the LDS operations of
+// one wavefront complete in order, so the counting needs no barrier.
 struct LWire {
-    u64 *base;
+    u64 *base, *cnt;
     int slot, p, lane;
-    __device__ __forceinline__ void init(u64 *lds) { base = lds; slot = 0; p = party_of_wave(); lane = threadIdx.x; }
+    u32 nopen, nresh;            // payload bits this lane has sent to its successor / predecessor since the last drain
+    __device__ __forceinline__ void init(u64 *lds, u64 *s_cnt)
+    {
+        base = lds; cnt = s_cnt; slot = 0; p = party_of_wave(); lane = threadIdx.x; nopen = 0; nresh = 0;
+        if (lane < 2) cnt[2 * p + lane] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
     template <int NW>
     __device__ __forceinline__ void exchange(const u64 (&snd)[NW], u64 (&rcv)[NW], int from)
     {
@@ -202,6 +221,7 @@ struct LWire {
         constexpr int XW = NW <= 4 ? 4 : 8;
         u64 *buf = NW <= 4 ? base + slot * GT_LWIRE_SLOT : base;
         if (NW <= 4) slot ^= 1;
+        else __syncthreads();    // a wide message overwrites both slots: the last slot message must have been read
 #pragma unroll
         for (int j = 0; j < NW; j++) buf[(p * XW + j) * GT_LANES + lane] = snd[j];
         __syncthreads();
@@ -210,11 +230,31 @@ struct LWire {
         if (NW > 4) __syncthreads();
     }
     template <int NW>
-    __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }
+    __device__ __forceinline__ void reshare(const u64 (&snd)[NW], u64 (&rcv)[NW], u32 bits) { nresh += bits; exchange<NW>(snd, rcv, p == 2 ? 0 : p + 1); }
     template <int NW>
-    __device__ __forceinline__ void open(const u64 (&snd)[NW], u64 (&rcv)[NW]) { exchange<NW>(snd, rcv, p == 0 ? 2 : p - 1); }
-    __device__ __forceinline__ u64 reshare1(u64 v) { u64 s[1] = { v }, r[1]; reshare<1>(s, r); return r[0]; }
-    __device__ __forceinline__ u64 open1(u64 v) { u64 s[1] = { v }, r[1]; open<1>(s, r); return r[0]; }
+    __device__ __forceinline__ void open(const u64 (&snd)[NW], u64 (&rcv)[NW], u32 bits) { nopen += bits; exchange<NW>(snd, rcv, p == 0 ? 2 : p - 1); }
+    __device__ __forceinline__ u64 reshare1(u64 v, u32 bits) { u64 s[1] = { v }, r[1]; reshare<1>(s, r, bits); return r[0]; }
+    __device__ __forceinline__ u64 open1(u64 v, u32 bits) { u64 s[1] = { v }, r[1]; open<1>(s, r, bits); return r[0]; }
+    // move the lane's sums into the party's LDS counters (long loops call it once per work
+    // item, before the 32-bit sums could overflow)
+    __device__ __forceinline__ void drain()
+    {
+        if (nopen) atomicAdd((unsigned long long *)&cnt[2 * p], (unsigned long long)nopen);
+        if (nresh) atomicAdd((unsigned long long *)&cnt[2 * p + 1], (unsigned long long)nresh);
+        nopen = 0; nresh = 0;
+    }
+    // end of the kernel: add the party's sums to g[2p] (bits sent to the successor) and
+    // g[2p+1] (to the predecessor); every lane calls it once
+    __device__ __forceinline__ void flush(u64 *g)
+    {
+        drain();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < 2) {
+            const u64 v = cnt[2 * p + lane];
+            if (v) atomicAdd((unsigned long long *)&g[2 * p + lane], (unsigned long long)v);
+        }
+    }
 };
 typedef LWire Wire;
 
@@ -247,20 +287,20 @@ __device__ __forceinline__ Dealer dealer_of(const PartyKeys &K, int p, u32 op, u
 // call them together (they contain barriers); inactive lanes pass zeros.
 
 // product with reshare: returns (z_p, z_{p+1})
-__device__ __forceinline__ Sh mult_sh(Wire &W, Sh x, Sh y, u64 alpha)
+__device__ __forceinline__ Sh mult_sh(Wire &W, Sh x, Sh y, u64 alpha, bool act)
 {
     Sh z;
     z.o = prod3(x, y) + alpha;
-    z.n = W.reshare1(z.o);
+    z.n = W.reshare1(z.o, act ? 64u : 0u);
     return z;
 }
 
 // Equality test [v == 0] -> Boolean bit sharing.  A receives the Boolean
 // zero-sharing word of stream 1 (bits 0..62 used here, bit 63 free for a following AND).
-__device__ __forceinline__ Sh eq_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D, u64 &A)
+__device__ __forceinline__ Sh eq_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D, u64 &A, bool act)
 {
     Sh m = v + D.rA;
-    const u64 c = m.o + m.n + W.open1(m.o);
+    const u64 c = m.o + m.n + W.open1(m.o, act ? 64u : 0u);
     Sh t = D.rho;
     if (p == 0) t.o ^= ~c;
     if (p == 2) t.n ^= ~c;
@@ -274,27 +314,27 @@ __device__ __forceinline__ Sh eq_bit(Wire &W, const PartyKeys &K, int p, u32 op,
         a.o = t.o & mask; a.n = t.n & mask;
         b.o = (t.o >> w) & mask; b.n = (t.n >> w) & mask;
         t.o = (and3(a, b) ^ (A >> off)) & mask;
-        t.n = W.reshare1(t.o);
+        t.n = W.reshare1(t.o, act ? w : 0u);
         off += w;
     }
     return t;
 }
 
 // one-bit AND with reshare; alpha is the mask bit
-__device__ __forceinline__ Sh and_bit(Wire &W, Sh x, Sh y, u64 alpha)
+__device__ __forceinline__ Sh and_bit(Wire &W, Sh x, Sh y, u64 alpha, bool act)
 {
     Sh z;
     z.o = (and3(x, y) ^ alpha) & 1;
-    z.n = W.reshare1(z.o);
+    z.n = W.reshare1(z.o, act ? 1u : 0u);
     return z;
 }
 
 // Comparison [v >= 0] (v signed, |v| < 2^63) -> Boolean bit sharing.
-__device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D)
+__device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D, bool act)
 {
     const u64 LOW63 = 0x7fffffffffffffffull, TOP = 0x8000000000000000ull;
     Sh m = v + D.rA;
-    const u64 c = m.o + m.n + W.open1(m.o);
+    const u64 c = m.o + m.n + W.open1(m.o, act ? 64u : 0u);
     const u64 nc = ~c;
     Sh G, E;
     G.o = nc & D.rho.o & LOW63; G.n = nc & D.rho.n & LOW63;
@@ -316,11 +356,11 @@ __device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op,
         if (k < 5) {
             const u64 ze = (and3(Eh, E) ^ (AE >> (s - 1))) & sm;
             u64 snd[2] = { zg, ze }, rcv[2];
-            W.reshare<2>(snd, rcv);
+            W.reshare<2>(snd, rcv, act ? 2u * (32u >> k) : 0u);   // one bit per block start, G and E
             G.o = (Gh.o & sm) ^ zg; G.n = (Gh.n & sm) ^ rcv[0];
             E.o = ze; E.n = rcv[1];
         } else {
-            const u64 r = W.reshare1(zg);
+            const u64 r = W.reshare1(zg, act ? 1u : 0u);
             G.o = (Gh.o & sm) ^ zg; G.n = (Gh.n & sm) ^ r;
         }
     }
@@ -333,10 +373,10 @@ __device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op,
 }
 
 // bit -> arithmetic: open f = s xor beta; s = beta if f = 0 else 1 - beta
-__device__ __forceinline__ Sh b2a(Wire &W, int p, Sh s, const Dealer &D)
+__device__ __forceinline__ Sh b2a(Wire &W, int p, Sh s, const Dealer &D, bool act)
 {
     const u64 fo = (s.o ^ D.bBo) & 1, fn = (s.n ^ D.bBn) & 1;
-    const u64 f = (fo ^ fn ^ W.open1(fo)) & 1;
+    const u64 f = (fo ^ fn ^ W.open1(fo, act ? 1u : 0u)) & 1;
     Sh one = pub(p, 1), out;
     out.o = f ? one.o - D.bA.o : D.bA.o;
     out.n = f ? one.n - D.bA.n : D.bA.n;

@@ -11,7 +11,12 @@
     for (u64 tile_ = blockIdx.x, ntiles_ = ((u64)(n) + GT_LANES - 1) / GT_LANES; tile_ < ntiles_; tile_ += gridDim.x)
 #define GT_ELEM() (tile_ * GT_LANES + threadIdx.x)
 
-struct KCommon { const u32 *keys; u32 op; };
+// keys: the five keys; op: operation id; wire: the context's six message counters
+// (payload bits sent by party p to its successor [2p] and to its predecessor [2p+1])
+struct KCommon { const u32 *keys; u32 op; u64 *wire; };
+
+// number of the lane's 8 consecutive elements (first one i0) that exist below n
+__device__ __forceinline__ u32 live8(u64 i0, u64 n) { return i0 >= n ? 0u : (n - i0 >= 8 ? 8u : (u32)(n - i0)); }
 
 __device__ __forceinline__ P6 p6_off(P6 a, size_t off)
 {
@@ -109,6 +114,12 @@ __global__ __launch_bounds__(256) void k_fill_const(P6 dst, u64 off, u64 n, u64 
             dst.o[j][off + e] = j == 0 ? c : 0;
             dst.n[j][off + e] = j == 2 ? c : 0;
         }
+}
+
+// plain words := c
+__global__ __launch_bounds__(256) void k_fill_words(u64 *dst, u64 n, u64 c)
+{
+    for (u64 e = (u64)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (u64)gridDim.x * blockDim.x) dst[e] = c;
 }
 
 // dst += src (local)
@@ -219,7 +230,8 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 {
     const int p = party_of_wave(), lane = threadIdx.x;
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = (a.n + 7) / 8;
     for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
@@ -237,7 +249,7 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
             }
             snd[s] = prod3(x, y) + (ao[s] - an[s]);
         }
-        W.reshare<8>(snd, rcv);
+        W.reshare<8>(snd, rcv, 64u * live8(e0, a.n));
 #pragma unroll
         for (int s = 0; s < 8; s++) {
             const u64 e = e0 + s;
@@ -252,6 +264,7 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
             }
         }
     }
+    W.flush(a.c.wire);
 }
 
 // One-time products of the learning protocol (Sec. V-B): column col = k*K + c,
@@ -267,8 +280,9 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
     // the zero-sharing words under key k_j are evaluated by party j's wavefront and read
     // through LDS by party j-1, the other holder of k_j
     __shared__ u64 s_prf[3][8 * GT_LANES];
+    __shared__ u64 s_cnt[6];
     const int p = party_of_wave(), lane = threadIdx.x, pn = p == 2 ? 0 : p + 1;
-    LWire W; W.init(s_wire);
+    LWire W; W.init(s_wire, s_cnt);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = a.N8 / 8, nq = (a.ncol + 3) / 4, nt = (ngrp + 15) / 16;
     // tiles outside, column quads inside: a workgroup meets the same class columns of Y
@@ -296,7 +310,7 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
             __syncthreads();
 #pragma unroll
             for (int s = 0; s < 8; s++) snd[s] -= s_prf[pn][s * GT_LANES + lane];
-            W.reshare<8>(snd, rcv);
+            W.reshare<8>(snd, rcv, 64u * live8(i0, nv));
             if (act) {
 #pragma unroll
                 for (int s = 0; s < 8; s++) if (i0 + s >= a.N) { snd[s] = 0; rcv[s] = 0; }
@@ -305,6 +319,7 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
             }
         }
     }
+    W.flush(a.c.wire);
 }
 
 // class indicator columns into limb tiles: row = rowbase + c
@@ -374,11 +389,12 @@ struct GridArgs {
 // garbage that the compaction drops) and compacts the lower halves into the fields of
 // the next message.  t: the lane's two Boolean components of the 64-bit inputs; A: the
 // lane's mask words (own xor next key): bits 0-31 round 0, 32-47 round 1, 48-55 round 2,
-// 56-59 round 3, 60-61 round 4, 62 round 5.  To8/Tn8: result bits, test s in bit s.
+// 56-59 round 3, 60-61 round 4, 62 round 5.  nl: how many of the eight tests exist (their
+// bits are what the messages carry).  To8/Tn8: result bits, test s in bit s.
 __device__ __forceinline__ u32 and3w(u32 ao, u32 an, u32 bo, u32 bn) { return (ao & (bo ^ bn)) ^ (an & bo); }
 
 template <class WireT>
-__device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], const u64 (&A)[8], u32 &To8, u32 &Tn8)
+__device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], const u64 (&A)[8], u32 nl, u32 &To8, u32 &Tn8)
 {
     u32 xo[8], xn[8], Ah[8];
     {   // round 0, width 32: the high word onto the low word; message 8 x 32 bits
@@ -388,7 +404,7 @@ __device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], co
             xo[s] = and3w((u32)t[s].o, (u32)t[s].n, (u32)(t[s].o >> 32), (u32)(t[s].n >> 32)) ^ (u32)A[s];
 #pragma unroll
         for (int j = 0; j < 4; j++) snd[j] = (u64)xo[2 * j] | ((u64)xo[2 * j + 1] << 32);
-        W.template reshare<4>(snd, rcv);
+        W.template reshare<4>(snd, rcv, 32u * nl);
 #pragma unroll
         for (int j = 0; j < 4; j++) { xn[2 * j] = (u32)rcv[j]; xn[2 * j + 1] = (u32)(rcv[j] >> 32); }
     }
@@ -404,7 +420,7 @@ __device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], co
         for (int j = 0; j < 4; j++) Po[j] = __builtin_amdgcn_perm(z[2 * j + 1], z[2 * j], 0x05040100u);
 #pragma unroll
         for (int j = 0; j < 2; j++) snd[j] = (u64)Po[2 * j] | ((u64)Po[2 * j + 1] << 32);
-        W.template reshare<2>(snd, rcv);
+        W.template reshare<2>(snd, rcv, 16u * nl);
 #pragma unroll
         for (int j = 0; j < 2; j++) { Pn[2 * j] = (u32)rcv[j]; Pn[2 * j + 1] = (u32)(rcv[j] >> 32); }
     }
@@ -417,7 +433,7 @@ __device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], co
 #pragma unroll
         for (int j = 0; j < 2; j++) Qo[j] = __builtin_amdgcn_perm(z[2 * j + 1], z[2 * j], 0x06040200u);
         u64 snd[1] = { (u64)Qo[0] | ((u64)Qo[1] << 32) }, rcv[1];
-        W.template reshare<1>(snd, rcv);
+        W.template reshare<1>(snd, rcv, 8u * nl);
         Qn[0] = (u32)rcv[0]; Qn[1] = (u32)(rcv[0] >> 32);
     }
     // byte 3 of every Ah, test s in byte s: low nibble = masks of round 3, bits 4-5 of
@@ -436,7 +452,7 @@ __device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], co
         }
         Ro = __builtin_amdgcn_perm(y[1], y[0], 0x06040200u);
         u64 snd[1] = { (u64)Ro }, rcv[1];
-        W.template reshare<1>(snd, rcv);
+        W.template reshare<1>(snd, rcv, 4u * nl);
         Rn = (u32)rcv[0];
     }
     u32 H;      // bits 28-31 of every Ah, test s in nibble s
@@ -451,7 +467,7 @@ __device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], co
         u32 z = (and3w(Ro, Rn, Ro >> 2, Rn >> 2) ^ H) & 0x33333333u;
         z = (z | (z >> 2)) & 0x0f0f0f0fu; z = (z | (z >> 4)) & 0x00ff00ffu; So = (z | (z >> 8)) & 0xffffu;
         u64 snd[1] = { (u64)So }, rcv[1];
-        W.template reshare<1>(snd, rcv);
+        W.template reshare<1>(snd, rcv, 2u * nl);
         Sn = (u32)rcv[0];
     }
     {   // round 5, width 1: fields of 2 bits in, single bits out
@@ -460,7 +476,7 @@ __device__ __forceinline__ void eq_rounds8_packed(WireT &W, const Sh (&t)[8], co
         u32 z = (and3w(So, Sn, So >> 1, Sn >> 1) ^ m) & 0x5555u;
         z = (z | (z >> 1)) & 0x3333u; z = (z | (z >> 2)) & 0x0f0fu; To8 = (z | (z >> 4)) & 0xffu;
         u64 snd[1] = { (u64)To8 }, rcv[1];
-        W.template reshare<1>(snd, rcv);
+        W.template reshare<1>(snd, rcv, nl);
         Tn8 = (u32)rcv[0];
     }
 }
@@ -501,11 +517,12 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     // The dealer's lanes OR their bits in; two copies alternate between steps so that
     // one can be cleared while the other is in use.
     __shared__ u32 s_bitw[2][GT_LANES];
+    __shared__ u64 s_cnt[6];
     const int p = party_of_wave(), lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1, pp = p == 0 ? 2 : p - 1;
     // messages of the AND rounds and of the bit conversion pass through the rows of the
     // Boolean edaBit components, which are dead once t has been formed; so do the
     // reshared inner products at the end of a work item
-    LWire LW; LW.init(&s_mat[3][0]);
+    LWire LW; LW.init(&s_mat[3][0], s_cnt);
     static_assert(GT_LWIRE_WORDS <= 3 * GT_TILE_EL, "LDS wire does not fit the rows it reuses");
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u32 op = a.c.op;
@@ -537,6 +554,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             const bool act = MODE == GM_STORE ? actg && k0 + ro < kend : actg;
             const u32 k = MODE == GM_STORE ? (act ? k0 + ro : kbeg) : k0;   // this lane's column (an existing one when idle)
             const u64 nv = act ? a.N : 0;              // samples of this lane that exist
+            const u32 nl = live8(i0, nv);              // how many of the lane's eight tests exist
             const u64 e0 = (u64)k * a.N8 + i0;
 #pragma unroll 1
             for (int j = 0; j < 3; j++) {
@@ -573,6 +591,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             __syncthreads();
 #pragma unroll
             for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = snd[s];
+            LW.nopen += 64u * nl;
             __syncthreads();
 #pragma unroll
             for (int s = 0; s < 8; s++) rcv[s] = s_mat[pp][s * GT_LANES + lane];
@@ -608,20 +627,20 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 #pragma unroll
             for (int s = 0; s < 8; s++) A[s] ^= s_mat[pn][s * GT_LANES + lane];
             u32 To8, Tn8;
-            eq_rounds8_packed(LW, t, A, To8, Tn8);     // six AND rounds, 63 bits
+            eq_rounds8_packed(LW, t, A, nl, To8, Tn8); // six AND rounds, 63 bits
             if (HAS_G) {                               // and with the column's shared bit
                 const Sh gk = ld(a.g, p, k);
                 const u32 go = 0u - ((u32)gk.o & 1), gn = 0u - ((u32)gk.n & 1);
                 To8 = (and3w(To8, Tn8, go, gn) ^ mask63_packed(A)) & 0xffu;
                 u64 s1[1] = { (u64)To8 }, r1[1];
-                LW.reshare<1>(s1, r1);
+                LW.reshare<1>(s1, r1, nl);
                 Tn8 = (u32)r1[0];
             }
             u32 f;
             {                                          // bit -> arithmetic: open s xor beta
                 const u32 bw = s_bitw[par][lane];
                 const u32 fo = To8 ^ ((bw >> (8 * p)) & 0xffu), fn = Tn8 ^ ((bw >> (8 * pn)) & 0xffu);
-                f = fo ^ fn ^ (u32)LW.open1((u64)fo);
+                f = fo ^ fn ^ (u32)LW.open1((u64)fo, nl);
             }
             Sh Wk = { 0, 0 }, Wk2 = { 0, 0 };
             if (MODE == GM_COMMON) {
@@ -663,7 +682,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             chacha8(K.nxt, grp, op, 2, an);
 #pragma unroll
             for (int s = 0; s < 8; s++) snd[s] = acc[s] + (ao[s] - an[s]);
-            LW.reshare<8>(snd, rcv);
+            LW.reshare<8>(snd, rcv, 64u * live8(i0, nvg));
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 if (actg && i0 + s < a.N) {
@@ -677,13 +696,15 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 chacha8(K.nxt, grp, op, 3, an);
 #pragma unroll
                 for (int s = 0; s < 8; s++) snd[s] = acc2[s] + (ao[s] - an[s]);
-                LW.reshare<8>(snd, rcv);
+                LW.reshare<8>(snd, rcv, 64u * live8(i0, nvg));
 #pragma unroll
                 for (int s = 0; s < 8; s++)
                     if (actg && i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.out2, p, i0 + s, z); }
             }
         }
+        LW.drain();
     }
+    LW.flush(a.c.wire);
 }
 
 // Completion of split inner products: z_p = partial sum + alpha (stream 2, second
@@ -692,7 +713,8 @@ __global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
 {
     const int p = party_of_wave(), lane = threadIdx.x;
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u64 ngrp = a.N8 / 8;
     const Sh one = pub(p, 1);
@@ -712,7 +734,7 @@ __global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
                 }
                 snd[s] = part + (ao[s] - an[s]);
             }
-            W.reshare<8>(snd, rcv);
+            W.reshare<8>(snd, rcv, 64u * live8(i0, nv));
 #pragma unroll
             for (int s = 0; s < 8; s++)
                 if (i0 + s < nv) {
@@ -722,6 +744,7 @@ __global__ __launch_bounds__(192) void k_dot_fin(GridArgs a)
                 }
         }
     }
+    W.flush(a.c.wire);
 }
 
 // ---------------------------------------------------------------------------------
@@ -734,7 +757,8 @@ __global__ __launch_bounds__(192) void k_eq(EqArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -744,10 +768,11 @@ __global__ __launch_bounds__(192) void k_eq(EqArgs a)
         if (act) v = ld(a.x, p, a.xoff + e) - pub(p, a.ysub + (a.ypub ? a.ypub[e] : 0));
         const Dealer D = dealer_of(K, p, a.c.op, e);
         u64 A;
-        Sh b = eq_bit(W, K, p, a.c.op, e, v, D, A);
-        if (!BOOL_OUT) b = b2a(W, p, b, D);
+        Sh b = eq_bit(W, K, p, a.c.op, e, v, D, A, act);
+        if (!BOOL_OUT) b = b2a(W, p, b, D, act);
         if (act) st(a.z, p, e, b);
     }
+    W.flush(a.c.wire);
 }
 
 // z = B2A([x >= y])
@@ -756,7 +781,8 @@ __global__ __launch_bounds__(192) void k_ge(GeArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -765,9 +791,10 @@ __global__ __launch_bounds__(192) void k_ge(GeArgs a)
         Sh v = { 0, 0 };
         if (act) v = ld(a.x, p, e) - ld(a.y, p, e);
         const Dealer D = dealer_of(K, p, a.c.op, e);
-        Sh b = b2a(W, p, ge_bit(W, K, p, a.c.op, e, v, D), D);
+        Sh b = b2a(W, p, ge_bit(W, K, p, a.c.op, e, v, D, act), D, act);
         if (act) st(a.z, p, e, b);
     }
+    W.flush(a.c.wire);
 }
 
 // Inference, threshold mode: bit = [x > theta]; Tidx <- 2 Tidx + bit + 1.
@@ -776,7 +803,8 @@ __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -785,9 +813,10 @@ __global__ __launch_bounds__(192) void k_cmp_step(CmpArgs a)
         Sh v = { 0, 0 };
         if (act) v = ld(a.th, p, e) - ld(a.x, p, e);
         const Dealer D = dealer_of(K, p, a.c.op, e);
-        Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, v, D)), D);
+        Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, v, D, act)), D, act);
         if (act) st(a.tidx, p, e, scale(ld(a.tidx, p, e), 2) + b + pub(p, 1));
     }
+    W.flush(a.c.wire);
 }
 
 // Restoring division, all steps of an element in one launch (the steps of different
@@ -798,7 +827,8 @@ __global__ __launch_bounds__(192) void k_div(DivArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -810,13 +840,14 @@ __global__ __launch_bounds__(192) void k_div(DivArgs a)
             const u32 op = a.c.op + t;
             if (t) r = scale(r, 2);
             const Dealer D = dealer_of(K, p, op, e);
-            const Sh b = b2a(W, p, ge_bit(W, K, p, op, e, r - Q, D), D);
-            const Sh bq = mult_sh(W, b, Q, zero_a(K, op, 3, e));
+            const Sh b = b2a(W, p, ge_bit(W, K, p, op, e, r - Q, D, act), D, act);
+            const Sh bq = mult_sh(W, b, Q, zero_a(K, op, 3, e), act);
             r = r - bq;
             quo = scale(quo, 2) + b;
         }
         if (act) { st(a.r, p, e, r); st(a.quo, p, e, quo); }
     }
+    W.flush(a.c.wire);
 }
 
 // Gini numerator/denominator terms (Sec. V-B, Eq. (1)): element q = (r*d+k)*2 + j,
@@ -826,7 +857,8 @@ __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     const u64 dK = (u64)a.d * a.K;
@@ -847,9 +879,10 @@ __global__ __launch_bounds__(192) void k_score_prep(PrepArgs a)
         u64 z0, z1;
         zero_a2(K, a.c.op, 0, 1, q, z0, z1);
         u64 snd[2] = { s + z0, prod3(nj, n) + z1 }, rcv[2];
-        W.reshare<2>(snd, rcv);
+        W.reshare<2>(snd, rcv, act ? 128u : 0u);
         if (act) { Sh S = { snd[0], rcv[0] }, Q = { snd[1], rcv[1] }; st(a.S, p, q, S); st(a.Q, p, q, Q); }
     }
+    W.flush(a.c.wire);
 }
 
 // score = quo[2e] + quo[2e+1]; masked = score * gamma[e]; written to the export copy
@@ -859,7 +892,8 @@ __global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -867,9 +901,10 @@ __global__ __launch_bounds__(192) void k_mask_score(MaskArgs a)
         const bool act = e < a.n;
         Sh s = { 0, 0 }, g = { 0, 0 };
         if (act) { s = ld(a.quo, p, 2 * e) + ld(a.quo, p, 2 * e + 1); g = ld(a.gamma, p, e); }
-        const Sh z = mult_sh(W, s, g, zero_a(K, a.c.op, 0, e));
+        const Sh z = mult_sh(W, s, g, zero_a(K, a.c.op, 0, e), act);
         if (act) { st(a.score, p, e, z); st(a.val, p, (e / a.d) * a.P2 + e % a.d, z); }
     }
+    W.flush(a.c.wire);
 }
 
 // Compare-and-select: b = [right > left]; val = left + b (right-left); idx likewise.
@@ -882,7 +917,8 @@ __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -899,16 +935,17 @@ __global__ __launch_bounds__(192) void k_select_max(SelArgs a)
             }
         }
         const Dealer D = dealer_of(K, p, a.c.op, e);
-        const Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, L - R, D)), D);
+        const Sh b = b2a(W, p, not_bit(p, ge_bit(W, K, p, a.c.op, e, L - R, D, act)), D, act);
         u64 z3, z4;
         zero_a2(K, a.c.op, 3, 4, e, z3, z4);
         u64 snd[2] = { prod3(b, R - L) + z3, prod3(b, IR - IL) + z4 }, rcv[2];
-        W.reshare<2>(snd, rcv);
+        W.reshare<2>(snd, rcv, act ? 128u : 0u);
         if (act) {
             Sh dv = { snd[0], rcv[0] }, di = { snd[1], rcv[1] };
             st(a.vout, p, e, L + dv); st(a.iout, p, e, IL + di);
         }
     }
+    W.flush(a.c.wire);
 }
 
 // gamma[r][k] <- gamma[r][k] * (1 - [SD[r] == k])
@@ -917,7 +954,8 @@ __global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -927,10 +965,11 @@ __global__ __launch_bounds__(192) void k_gamma(GammaArgs a)
         if (act) { v = ld(a.SD, p, e / a.d) - pub(p, e % a.d); g = ld(a.gamma, p, e); }
         const Dealer D = dealer_of(K, p, a.c.op, e);
         u64 A;
-        const Sh oh = b2a(W, p, eq_bit(W, K, p, a.c.op, e, v, D, A), D);
-        const Sh z = mult_sh(W, g, pub(p, 1) - oh, zero_a(K, a.c.op, 2, e));
+        const Sh oh = b2a(W, p, eq_bit(W, K, p, a.c.op, e, v, D, A, act), D, act);
+        const Sh z = mult_sh(W, g, pub(p, 1) - oh, zero_a(K, a.c.op, 2, e), act);
         if (act) st(a.gamma, p, e, z);
     }
+    W.flush(a.c.wire);
 }
 
 // Node r: pure = [n^2 - sum_c tot_c^2 == 0]; split = isLeaf and not pure;
@@ -940,7 +979,8 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -960,13 +1000,13 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
         }
         Sh d;
         d.o = dv + zero_a(K, a.c.op, 2, r);
-        d.n = W.reshare1(d.o);
+        d.n = W.reshare1(d.o, act ? 64u : 0u);
         const Dealer D = dealer_of(K, p, a.c.op, r);
         u64 A;
-        const Sh npure = not_bit(p, eq_bit(W, K, p, a.c.op, r, d, D, A));
-        const Sh sA = b2a(W, p, and_bit(W, leaf, npure, A >> 63), D);
+        const Sh npure = not_bit(p, eq_bit(W, K, p, a.c.op, r, d, D, A, act));
+        const Sh sA = b2a(W, p, and_bit(W, leaf, npure, A >> 63, act), D, act);
         const Sh keep = pub(p, 1) - sA;
-        const Sh fz = mult_sh(W, f, keep, zero_a(K, a.c.op, 3, r));
+        const Sh fz = mult_sh(W, f, keep, zero_a(K, a.c.op, 3, r), act);
         if (act) {
             st(a.split, p, r, sA);
             st(a.F, p, a.base + r, fz);
@@ -975,6 +1015,7 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
             st(a.F, p, 2 * (a.base + r) + 2, ch);
         }
     }
+    W.flush(a.c.wire);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1156,7 +1197,8 @@ __global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
 {
     const int p = party_of_wave();
     __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    Wire W; W.init(s_wire);
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
     __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
     const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
     GT_FOR_TILES(a.n) {
@@ -1166,12 +1208,13 @@ __global__ __launch_bounds__(192) void k_count_fin(CountFinArgs a)
         u64 part = 0;
         if (act) { part = a.Zacc[(u64)p * a.n + o]; a.Zacc[(u64)p * a.n + o] = 0; }   // zero again for the next contraction
         z.o = part + zero_a(K, a.c.op, 0, o);
-        z.n = W.reshare1(z.o);
+        z.n = W.reshare1(z.o, act ? 64u : 0u);
         if (act) {
             const u64 idx = (o / a.ncol) * a.CW + a.colbase + o % a.ncol;
             st(a.C, p, idx, ld(a.C, p, idx) + z);
         }
     }
+    W.flush(a.c.wire);
 }
 
 // counter-array layout of Sec. V-B for export: per node (1+K) x 2d, local linear ops

@@ -28,29 +28,39 @@ struct gt_ctx {
     u32 op;
     hipStream_t stream;
     u32 *keys_d;
+    u64 *wire_d;              // six counters filled by the kernels: payload bits party p sent to p+1 [2p], to p-1 [2p+1]
+    unsigned resident;        // workgroups of 192 lanes that fit on the device at once
     gt_stats acc;
-    hipEvent_t ev0, ev1;
-    bool timing;
     bool profile;
-    std::vector<hipEvent_t> ev_pool;
+    std::vector<hipEvent_t> ev_pool;   // GT_FLAG_PROFILE: a pair of events per launch, resolved when the times are read
     size_t ev_used;
     std::vector<int> ev_cls;
     gt_prof prof;
     DSh ws[5];                // inference workspace, grown on demand, kept between calls
+    DSh divrem;               // remainders of gt_div, grown on demand, kept between calls
     u64 *dacc;                // partial inner products of split equality grids
     size_t dacc_words;
+    bool noalloc;             // set by entry points that may not allocate
 };
+
+// Buffers of the tree that gt_train_finish hands out, allocated with the training
+// object so that finishing a job allocates nothing.  The slot is shared by the training
+// object and the tree made from it; whoever is destroyed last frees it.
+struct TreeSlot { DSh feat, leaf; bool in_use = false, orphan = false; };
 
 struct gt_tree {
     u32 H;
     bool has_thr;
     DSh feat, thr, leaf;
+    TreeSlot *slot;           // non-null: feat and leaf are the slot's buffers
 };
 
 struct gt_train {
     size_t N, N8;
     u32 d, K, H, CW, level, last, P2;
     bool finished;
+    bool fresh_import;               // state was imported and no level has run since: nothing to export for "last"
+    TreeSlot *slot;
     DSh XT, YT;                      // [k][i], [c][i]: sample-contiguous copies of the inputs
     unsigned char *LQ, *BQ;          // limb tiles: leaf one-hot (own+next, own), columns (own, next)
     size_t nblk, Lrows, Brows;       // sample blocks of 32, row strides of the limb planes
@@ -98,7 +108,6 @@ static unsigned blocks_for(u64 n, unsigned per)
     return (unsigned)std::min<u64>(b, GT_MAX_BLOCKS);
 }
 static unsigned tiles(u64 n) { return blocks_for(n, GT_LANES); }          // one element per lane
-static unsigned g_resident = 1024;   // workgroups that fit on the device at once (set at context creation)
 // eight elements per lane
 static unsigned tiles8(u64 n) { return blocks_for((n + 7) / 8, GT_LANES); }
 
@@ -126,34 +135,34 @@ static void acct_b2a(gt_ctx *c, u64 n) { wire_add(c, +1, n, 1); c->acc.rounds +=
 static void acct_and1(gt_ctx *c, u64 n) { wire_add(c, -1, n, 1); c->acc.rounds += 1; }
 static void acct_reshare(gt_ctx *c, u64 n, u64 words) { wire_add(c, -1, n, 64 * words); c->acc.rounds += 1; }
 
-struct Timed {                // times one API call with events on the context's stream
-    gt_ctx *c; bool on;
-    explicit Timed(gt_ctx *ctx) : c(ctx), on(!ctx->timing)
-    {
-        if (on) { c->timing = true; (void)hipEventRecord(c->ev0, c->stream); }
+// Sum up the event pairs recorded so far (GT_FLAG_PROFILE).  Waits for the stream.
+static int resolve_events(gt_ctx *c)
+{
+    if (c->ev_cls.empty()) return GT_OK;
+    HIPCHK(hipStreamSynchronize(c->stream));
+    for (size_t i = 0; i < c->ev_cls.size(); i++) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) == hipSuccess) {
+            c->prof.ms[c->ev_cls[i]] += t; c->prof.launches[c->ev_cls[i]] += 1; c->acc.kernel_ms += t;
+        }
     }
+    c->ev_cls.clear(); c->ev_used = 0;
+    return GT_OK;
+}
+
+// End of an API call: the work is enqueued, nothing waits for it.  Launch errors that the
+// runtime has already noticed are reported.
+struct Timed {
+    gt_ctx *c;
+    explicit Timed(gt_ctx *ctx) : c(ctx) {}
     int finish(int rc)
     {
-        if (!on) return rc;
-        on = false; c->timing = false;
-        if (hipEventRecord(c->ev1, c->stream) != hipSuccess) return rc ? rc : GT_EHIP;
-        if (hipEventSynchronize(c->ev1) != hipSuccess) return rc ? rc : GT_EHIP;
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->acc.kernel_ms += ms;
-        for (size_t i = 0; i < c->ev_cls.size(); i++) {
-            float t = 0.f;
-            if (hipEventElapsedTime(&t, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) == hipSuccess) {
-                c->prof.ms[c->ev_cls[i]] += t; c->prof.launches[c->ev_cls[i]] += 1;
-            }
-        }
-        c->ev_cls.clear(); c->ev_used = 0;
-        if (rc == GT_OK && hipGetLastError() != hipSuccess) return GT_EHIP;
+        if (rc == GT_OK && hipPeekAtLastError() != hipSuccess) { (void)hipGetLastError(); return GT_EHIP; }
         return rc;
     }
-    ~Timed() { if (on) { c->timing = false; } }
 };
 
-static KCommon kc(gt_ctx *c, u32 op) { KCommon k; k.keys = c->keys_d; k.op = op; return k; }
+static KCommon kc(gt_ctx *c, u32 op) { KCommon k; k.keys = c->keys_d; k.op = op; k.wire = c->wire_d; return k; }
 
 // Every kernel goes through here.  With GT_FLAG_PROFILE the launch is bracketed by a
 // pair of events of its kernel class; the pairs are resolved when the API call ends.
@@ -162,6 +171,8 @@ static int launch(gt_ctx *c, int cls, Kern kern, dim3 grid, dim3 block, Args... 
 {
     hipEvent_t e1 = nullptr;
     if (c->profile) {
+        if (c->ev_used >= 16384) GTCHK(resolve_events(c));    // bound the pool
+        if (c->ev_used + 2 > c->ev_pool.size() && c->noalloc) goto plain;   // no new events: this launch goes untimed
         if (c->ev_used + 2 > c->ev_pool.size())
             for (int i = 0; i < 64; i++) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) return GT_EHIP; c->ev_pool.push_back(e); }
         hipEvent_t e0 = c->ev_pool[c->ev_used++];
@@ -169,6 +180,7 @@ static int launch(gt_ctx *c, int cls, Kern kern, dim3 grid, dim3 block, Args... 
         c->ev_cls.push_back(cls);
         (void)hipEventRecord(e0, c->stream);
     }
+plain:
     hipLaunchKernelGGL(kern, grid, block, 0, c->stream, args...);
     if (e1) (void)hipEventRecord(e1, c->stream);
     return hipGetLastError() == hipSuccess ? GT_OK : GT_EHIP;
@@ -196,7 +208,8 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (prm->K < 1 || prm->K > GT_MAX_K || prm->tau < 1 || prm->tau > GT_MAX_TAU) return GT_EINVAL;
     gt_ctx *c = new (std::nothrow) gt_ctx();
     if (!c) return GT_ENOMEM;
-    c->op = 0; c->timing = false; c->ev_used = 0; c->keys_d = nullptr; c->dacc = nullptr; c->dacc_words = 0;
+    c->noalloc = false;
+    c->op = 0; c->ev_used = 0; c->keys_d = nullptr; c->wire_d = nullptr; c->dacc = nullptr; c->dacc_words = 0; c->resident = 1024;
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     c->profile = (prm->flags & GT_FLAG_PROFILE) != 0;
     c->tau = prm->tau; c->K = prm->K; c->stream = (hipStream_t)prm->hip_stream;
@@ -204,12 +217,14 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     for (int k = 0; k < 5; k++)
         for (int i = 0; i < 4; i++) { keys[k][2 * i] = (u32)prm->seed[k][i]; keys[k][2 * i + 1] = (u32)(prm->seed[k][i] >> 32); }
     int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-        g_resident = std::min<unsigned>(GT_MAX_BLOCKS, 4u * (unsigned)cus);
+    if (hipGetDevice(&dev) != hipSuccess) { delete c; return GT_EHIP; }
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        c->resident = std::min<unsigned>(GT_MAX_BLOCKS, 4u * (unsigned)cus);
     if (hipMalloc(&c->keys_d, sizeof keys) != hipSuccess) { delete c; return GT_ENOMEM; }
+    if (hipMalloc(&c->wire_d, 8 * sizeof(u64)) != hipSuccess) { (void)hipFree(c->keys_d); delete c; return GT_ENOMEM; }
     if (hipMemcpy(c->keys_d, keys, sizeof keys, hipMemcpyHostToDevice) != hipSuccess ||
-        hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) {
-        (void)hipFree(c->keys_d); delete c; return GT_EHIP;
+        hipMemset(c->wire_d, 0, 8 * sizeof(u64)) != hipSuccess) {
+        (void)hipFree(c->keys_d); (void)hipFree(c->wire_d); delete c; return GT_EHIP;
     }
     *out = c;
     return GT_OK;
@@ -219,10 +234,11 @@ extern "C" int gt_ctx_destroy(gt_ctx *c)
 {
     if (!c) return GT_EINVAL;
     (void)hipStreamSynchronize(c->stream);
-    (void)hipEventDestroy(c->ev0); (void)hipEventDestroy(c->ev1);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (DSh &w : c->ws) dsh_free(w);
+    dsh_free(c->divrem);
     if (c->dacc) (void)hipFree(c->dacc);
+    (void)hipFree(c->wire_d);
     (void)hipFree(c->keys_d);
     delete c;
     return GT_OK;
@@ -232,12 +248,19 @@ extern "C" int gt_stats_get(gt_ctx *c, gt_stats *out)
 {
     if (!c || !out) return GT_EINVAL;
     HIPCHK(hipStreamSynchronize(c->stream));
+    GTCHK(resolve_events(c));
+    u64 bits[6];
+    HIPCHK(hipMemcpy(bits, c->wire_d, sizeof bits, hipMemcpyDeviceToHost));
+    memset(c->acc.wire_bits_dev, 0, sizeof c->acc.wire_bits_dev);
+    for (int p = 0; p < 3; p++) { c->acc.wire_bits_dev[p][(p + 1) % 3] = bits[2 * p]; c->acc.wire_bits_dev[p][(p + 2) % 3] = bits[2 * p + 1]; }
     *out = c->acc;
     return GT_OK;
 }
 extern "C" int gt_stats_reset(gt_ctx *c)
 {
     if (!c) return GT_EINVAL;
+    GTCHK(resolve_events(c));
+    HIPCHK(hipMemsetAsync(c->wire_d, 0, 8 * sizeof(u64), c->stream));
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     return GT_OK;
 }
@@ -245,6 +268,7 @@ extern "C" int gt_prof_get(gt_ctx *c, gt_prof *out)
 {
     if (!c || !out) return GT_EINVAL;
     HIPCHK(hipStreamSynchronize(c->stream));
+    GTCHK(resolve_events(c));
     *out = c->prof;
     return GT_OK;
 }
@@ -327,7 +351,7 @@ extern "C" int gt_ge_a(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t
 }
 
 // the equality grid with its accounting
-static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
+static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a, u64 *ext = nullptr, size_t ext_words = 0)
 {
     a.c = kc(c, c->op++);
     a.ndot = ndot;
@@ -338,14 +362,18 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
         a.lgs = (mode == GM_STORE && a.w % 4 == 0) ? 4 : 6;
         const u64 kstep = GT_LANES >> a.lgs, nsteps = (a.w + kstep - 1) / kstep;
         // enough work items (tile, column range) to keep every resident workgroup slot busy for several rounds
-        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 4ull * g_resident;
+        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 4ull * c->resident;
         u64 nkc = std::min<u64>(nsteps, std::max<u64>(1, (want + ntile - 1) / ntile));
         a.kchunk = (u32)(((nsteps + nkc - 1) / nkc) * kstep);
         a.nkc = (a.w + a.kchunk - 1) / a.kchunk;
         a.dacc = nullptr;
         if (mode != GM_STORE && a.nkc > 1) {
             const size_t need = (size_t)6 * a.N8;
-            if (c->dacc_words < need) {
+            if (ext) {                         // caller-provided scratch: cleared by a fill kernel, never grown
+                if (need > ext_words) return GT_EINVAL;
+                GTCHK(launch(c, GT_KC_LOCAL, k_fill_words, g1(need), B256, ext, (u64)need, (u64)0));
+                a.dacc = ext;
+            } else if (c->dacc_words < need) {
                 (void)hipStreamSynchronize(c->stream);
                 if (c->dacc) (void)hipFree(c->dacc);
                 c->dacc = nullptr; c->dacc_words = 0;
@@ -354,16 +382,16 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a)
                 // zero once: k_dot_fin leaves every word it has read at zero again
                 HIPCHK(hipMemsetAsync(c->dacc, 0, need * 8, c->stream));
             }
-            a.dacc = c->dacc;
+            if (!ext) a.dacc = c->dacc;
         }
         // more workgroups than fit at once: the hardware balances them over the compute units
         dim3 g((unsigned)std::min<u64>(ntile * a.nkc, GT_MAX_BLOCKS));
         int rc;
-        if (mode == GM_STORE && has_g) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, true, 1>, g, GT_BLOCK, a);
-        else if (mode == GM_STORE) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_STORE, false, 1>, g, GT_BLOCK, a);
+        if (mode == GM_STORE && has_g) rc = launch(c, GT_KC_EQGRID_STORE, k_eqgrid<GM_STORE, true, 1>, g, GT_BLOCK, a);
+        else if (mode == GM_STORE) rc = launch(c, GT_KC_EQGRID_STORE, k_eqgrid<GM_STORE, false, 1>, g, GT_BLOCK, a);
         else if (mode == GM_COMMON && ndot == 2) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_COMMON, false, 2>, g, GT_BLOCK, a);
         else if (mode == GM_COMMON) rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_COMMON, false, 1>, g, GT_BLOCK, a);
-        else rc = launch(c, GT_KC_EQGRID, k_eqgrid<GM_ROWS, false, 1>, g, GT_BLOCK, a);
+        else rc = launch(c, GT_KC_EQGRID_ROWS, k_eqgrid<GM_ROWS, false, 1>, g, GT_BLOCK, a);
         GTCHK(rc);
         if (a.dacc) GTCHK(launch(c, GT_KC_SMALL, k_dot_fin, dim3(tiles8(a.N8)), GT_BLOCK, a));
     }
@@ -397,12 +425,14 @@ extern "C" int gt_div(gt_ctx *c, const gt_shares *S, const gt_shares *Q, size_t 
 {
     if (!c || !shares_ok(S, n) || !shares_ok(Q, n) || !shares_ok(q, n)) return GT_EINVAL;
     Timed T(c);
-    DSh rem;
-    int rc = dsh_alloc(rem, n, c->stream);
-    if (rc == GT_OK) rc = div_steps(c, to_p6(S), to_p6(Q), rem.v, to_p6(q), n);
-    rc = T.finish(rc);
-    dsh_free(rem);
-    return rc;
+    int rc = GT_OK;
+    if (c->divrem.n < n) {                      // first use or a larger batch: grow the kept scratch
+        (void)hipStreamSynchronize(c->stream);
+        dsh_free(c->divrem);
+        rc = dsh_alloc(c->divrem, n, c->stream);
+    }
+    if (rc == GT_OK) rc = div_steps(c, to_p6(S), to_p6(Q), c->divrem.v, to_p6(q), n);
+    return T.finish(rc);
 }
 
 // ---- training -------------------------------------------------------------------------
@@ -415,6 +445,10 @@ static void train_free(gt_train *t)
                    &t->tval, &t->best, &t->lab, &t->Clast, &t->Glast, &t->Slast };
     for (DSh *s : all) dsh_free(*s);
     if (t->Zacc) (void)hipFree(t->Zacc);
+    if (t->slot) {
+        if (t->slot->in_use) t->slot->orphan = true;     // the tree made from it frees it
+        else { dsh_free(t->slot->feat); dsh_free(t->slot->leaf); delete t->slot; }
+    }
     delete t;
 }
 
@@ -453,7 +487,7 @@ static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shar
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(nmax * t->CW), B256, t->C.v, (u64)0, (u64)(nmax * t->CW), (u64)0));
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, dim3(1), B256, t->F.v, (u64)0, (u64)1, (u64)1));
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(d), B256, t->gamma.v, (u64)0, (u64)d, (u64)1));
-    t->level = 0; t->last = 0; t->finished = false;
+    t->level = 0; t->last = 0; t->finished = false; t->fresh_import = false;
     return GT_OK;
 }
 
@@ -469,7 +503,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     const size_t N8 = pad8(N), nmax = (size_t)1 << H, nodes = ((size_t)2 << H) - 1, CW = (size_t)d * K + K;
     size_t P2 = 1; while (P2 < d) P2 *= 2;
     t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
-    t->finished = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr;
+    t->finished = false; t->fresh_import = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr; t->slot = nullptr;
     hipStream_t s = c->stream;
     int rc = GT_OK;
     struct { DSh *v; size_t n; } plan[] = {
@@ -481,6 +515,12 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
         { &t->Clast, nmax * CW }, { &t->Glast, nmax * d }, { &t->Slast, nmax * d },
     };
     for (auto &pl : plan) { rc = dsh_alloc(*pl.v, pl.n, s); if (rc != GT_OK) break; }
+    if (rc == GT_OK) {
+        t->slot = new (std::nothrow) TreeSlot();
+        if (!t->slot) rc = GT_ENOMEM;
+        if (rc == GT_OK) rc = dsh_alloc(t->slot->feat, nmax - 1, s);
+        if (rc == GT_OK) rc = dsh_alloc(t->slot->leaf, nmax, s);
+    }
     if (rc == GT_OK && hipMalloc(&t->Zacc, 3 * nmax * CW * 8) != hipSuccess) rc = GT_ENOMEM;
     // zero once: k_count_fin leaves every word it has read at zero again
     if (rc == GT_OK && hipMemsetAsync(t->Zacc, 0, 3 * nmax * CW * 8, s) != hipSuccess) rc = GT_EHIP;
@@ -547,7 +587,7 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     // sample chunk per workgroup: as long as the int32 accumulators allow, shorter when
     // that is needed to give every compute unit several workgroups
     const u64 wgs_per_chunk = (u64)(ncg2 + ncg1 + narrow) * 3 * a.nrowgrp;
-    u64 want_chunks = (4ull * g_resident / 4 + wgs_per_chunk - 1) / wgs_per_chunk;
+    u64 want_chunks = ((u64)c->resident + wgs_per_chunk - 1) / wgs_per_chunk;
     u64 cb = (t->nblk + want_chunks - 1) / want_chunks;
     cb = std::max<u64>(8, std::min<u64>(CT_CHUNK_BLOCKS, cb));
     a.chunkblk = (u32)cb;
@@ -639,7 +679,7 @@ extern "C" int gt_train_level(gt_ctx *c, gt_train *t, uint32_t h)
     if (rc == GT_OK) rc = count(c, t, h, false);
     if (rc == GT_OK) rc = heuristic(c, t, h);
     if (rc == GT_OK) rc = update(c, t, h);
-    if (rc == GT_OK) t->level = h + 1;
+    if (rc == GT_OK) { t->level = h + 1; t->fresh_import = false; }
     return T.finish(rc);
 }
 
@@ -647,7 +687,7 @@ static int tree_alloc(gt_ctx *c, u32 H, bool thr, gt_tree **out)
 {
     gt_tree *tr = new (std::nothrow) gt_tree();
     if (!tr) return GT_ENOMEM;
-    tr->H = H; tr->has_thr = thr;
+    tr->H = H; tr->has_thr = thr; tr->slot = nullptr;
     const size_t nint = ((size_t)1 << H) - 1, nleaf = (size_t)1 << H;
     int rc = dsh_alloc(tr->feat, nint, c->stream);
     if (rc == GT_OK) rc = dsh_alloc(tr->leaf, nleaf, c->stream);
@@ -679,19 +719,28 @@ extern "C" int gt_train_finish(gt_ctx *c, gt_train *t, gt_tree **out)
     if (rc == GT_OK) rc = copy6(c, t->T.v, base, t->lab.v, 0, 1, nh);
     if (rc == GT_OK) rc = copy6(c, t->Clast.v, 0, t->C.v, 0, 1, nh * t->CW);
     gt_tree *tr = nullptr;
-    if (rc == GT_OK) rc = tree_alloc(c, H, false, &tr);
+    if (rc == GT_OK) {
+        if (t->slot && !t->slot->in_use) {       // the buffers allocated with the training object
+            tr = new (std::nothrow) gt_tree();
+            if (!tr) rc = GT_ENOMEM;
+            else { tr->H = H; tr->has_thr = false; tr->feat = t->slot->feat; tr->leaf = t->slot->leaf; tr->slot = t->slot; t->slot->in_use = true; }
+        } else rc = tree_alloc(c, H, false, &tr);  // the previous tree of this object is still alive
+    }
     if (rc == GT_OK) rc = copy6(c, tr->feat.v, 0, t->T.v, 0, 1, base);
     if (rc == GT_OK) rc = copy6(c, tr->leaf.v, 0, t->T.v, base, 1, nh);
-    if (rc == GT_OK) { t->last = H; t->level = H + 1; t->finished = true; }
+    if (rc == GT_OK) { t->last = H; t->level = H + 1; t->finished = true; t->fresh_import = false; }
     rc = T.finish(rc);
     if (rc != GT_OK) { if (tr) gt_tree_destroy(tr); return rc; }
     *out = tr;
     return GT_OK;
 }
 
+static bool of_last_level(int what) { return what == GT_X_C || what == GT_X_GAMMA || what == GT_X_SD || what == GT_X_L || what == GT_X_SCORE || what == GT_X_C_PAPER; }
+
 extern "C" size_t gt_train_export_size(const gt_train *t, int what)
 {
     if (!t) return 0;
+    if (t->fresh_import && of_last_level(what)) return 0;     // no level has run on the imported state yet
     const size_t nh = (size_t)1 << t->last;
     switch (what) {
     case GT_X_T: case GT_X_F: return ((size_t)2 << t->H) - 1;
@@ -708,8 +757,10 @@ extern "C" size_t gt_train_export_size(const gt_train *t, int what)
 extern "C" int gt_train_export(gt_ctx *c, const gt_train *t, int what, const gt_shares *out)
 {
     if (!c || !t) return GT_EINVAL;
+    if (what < GT_X_T || what > GT_X_C_PAPER) return GT_EINVAL;
+    if (t->fresh_import && of_last_level(what)) return GT_ESTATE;
     const size_t n = gt_train_export_size(t, what);
-    if (what < GT_X_T || what > GT_X_C_PAPER || !shares_ok(out, n)) return GT_EINVAL;
+    if (!shares_ok(out, n)) return GT_EINVAL;
     Timed T(c);
     const DSh *src = nullptr;
     switch (what) {
@@ -746,7 +797,7 @@ extern "C" int gt_train_import(gt_ctx *c, gt_train *t, uint32_t h, const gt_shar
     if (rc == GT_OK) rc = copy6(c, t->F.v, base, to_p6(Fl), 0, 1, nh);
     if (rc == GT_OK) rc = copy6(c, t->C.v, 0, to_p6(Cc), 0, 1, nh * t->CW);
     if (rc == GT_OK) rc = copy6(c, t->gamma.v, 0, to_p6(gm), 0, 1, nh * t->d);
-    if (rc == GT_OK) { t->level = h; t->finished = false; }
+    if (rc == GT_OK) { t->level = h; t->finished = false; t->fresh_import = true; }
     return T.finish(rc);
 }
 
@@ -783,8 +834,14 @@ extern "C" int gt_tree_export(gt_ctx *c, const gt_tree *tr, const gt_shares *fea
 extern "C" int gt_tree_destroy(gt_tree *tr)
 {
     if (!tr) return GT_EINVAL;
+    if (tr->slot && !tr->slot->orphan) {         // buffers go back to the training object: nothing is freed
+        tr->slot->in_use = false;
+        delete tr;
+        return GT_OK;
+    }
     (void)hipDeviceSynchronize();
     dsh_free(tr->feat); dsh_free(tr->thr); dsh_free(tr->leaf);
+    if (tr->slot) delete tr->slot;
     delete tr;
     return GT_OK;
 }

@@ -33,15 +33,16 @@ class _Shares(C.Structure):
 
 
 class _Stats(C.Structure):
-    _fields_ = [("rounds", C.c_uint64), ("wire_bytes", (C.c_uint64 * 3) * 3), ("kernel_ms", C.c_double)]
+    _fields_ = [("rounds", C.c_uint64), ("wire_bytes", (C.c_uint64 * 3) * 3), ("wire_bits_dev", (C.c_uint64 * 3) * 3),
+                ("kernel_ms", C.c_double)]
 
 
 GT_FLAG_PROFILE = 1
-KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local")
+KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local", "eqgrid_rows", "eqgrid_store")
 
 
 class _Prof(C.Structure):
-    _fields_ = [("ms", C.c_double * 6), ("launches", C.c_uint64 * 6)]
+    _fields_ = [("ms", C.c_double * 8), ("launches", C.c_uint64 * 8)]
 
 
 class _Params(C.Structure):
@@ -205,11 +206,17 @@ class GTree:
         wire = np.array([[st.wire_bytes[a][b] for b in range(3)] for a in range(3)], dtype=np.uint64)
         return int(st.rounds), wire, float(st.kernel_ms)
 
+    def wire_bits_dev(self):
+        """(3, 3) payload bits per directed pair, counted by the kernels at their message stores."""
+        st = _Stats()
+        _chk(self.L.gt_stats_get(self.ctx, C.byref(st)), "gt_stats_get")
+        return np.array([[st.wire_bits_dev[a][b] for b in range(3)] for a in range(3)], dtype=np.uint64)
+
     def prof(self):
         """{class name: (milliseconds, launches)} since the last stats_reset (profile=True)."""
         pr = _Prof()
         _chk(self.L.gt_prof_get(self.ctx, C.byref(pr)), "gt_prof_get")
-        return {KC_NAMES[k]: (float(pr.ms[k]), int(pr.launches[k])) for k in range(6)}
+        return {KC_NAMES[k]: (float(pr.ms[k]), int(pr.launches[k])) for k in range(len(KC_NAMES))}
 
     def stats_reset(self):
         _chk(self.L.gt_stats_reset(self.ctx), "gt_stats_reset")

@@ -40,12 +40,13 @@ def test_c5_level_full_size(seed):
     o.train_level(h)
     for what, name in ((X_M, "M"), (X_C, "C"), (X_SCORE, "score"), (X_SD, "SD"), (X_F, "F"), (X_GAMMA, "gamma")):
         _same(g.train_export(what), o.train_export(what), name)
-    # the per-sample leaf one-hot is 128 x 10^6 shares: compare every party's planes on a slab of nodes
+    # the per-sample leaf one-hot is 128 x 10^6 shares: every party's two planes of every node,
+    # one node slab at a time
     Lg = g.train_export(X_L)
     Lo = o.train_export(X_L)
     N8 = (N + 7) // 8 * 8
     pl = Lg.t.view(3, 2, 1 << h, N8)
-    for r in (0, 63, 127):
+    for r in range(1 << h):
         got = pl[:, :, r, :].cpu().numpy().view(np.uint64)
         for p in range(3):
             assert np.array_equal(got[p, 0], Lo[p].reshape(1 << h, N8)[r]), ("L own", r, p)
@@ -53,6 +54,7 @@ def test_c5_level_full_size(seed):
     ro, wo = o.stats()
     rg, wg, _ = g.stats()
     assert ro == rg and np.array_equal(wo, wg)
+    assert np.array_equal(o.wire_bits(), g.wire_bits_dev())      # counted by the kernels at their message stores
     # and the reconstructed counts are the plaintext histogram of the routed samples
     X, y = w["X"].astype(np.int64), w["y"]
     Mi = w["M"].astype(np.int64)
@@ -87,9 +89,17 @@ def test_c5_inference_full_size(seed):
     comp = R.components()                                   # also checks the replicated copies
     T = np.concatenate([w["feat"], w["leaf"]]).astype(np.int64)
     assert np.array_equal(g.rec(R).astype(np.int64), plain_cart.predict(T, H, w["I"]))
-    # sampled rows, share by share: first and last tile, a ragged position, random rows
+    # share by share on more than 2*10^4 rows: whole tiles of 512 rows (what one workgroup
+    # carries) - the first ones, the last full one, the ragged last one, tiles on both sides of
+    # the point where the launch's grid-stride loop starts its second pass (the launch has at
+    # most 4096 workgroups for 1954 tiles x 3 column ranges) - and random rows
     rng = np.random.default_rng(3)
-    rows = np.unique(np.concatenate([[0, 1, 7, 8, 511, 512, NI - 513, NI - 2, NI - 1], rng.integers(0, NI, size=40)]))
+    ntile = (NI + 511) // 512
+    tiles = sorted(set([0, 1, 2, ntile // 3, 1364, 1365, 1366, 1367, ntile - 3, ntile - 2, ntile - 1]
+                       + rng.integers(0, ntile, size=30).tolist()))
+    rows = np.concatenate([np.arange(t * 512, min(NI, (t + 1) * 512)) for t in tiles] + [rng.integers(0, NI, size=1500)])
+    rows = np.unique(rows)
+    assert rows.size >= 20000
     fo, lo = o.share(w["feat"]), o.share(w["leaf"])
     Io = o.share(w["I"].reshape(-1)).reshape(3, NI, d)[:, rows, :].reshape(3, -1)
     Ro = o.infer_rows(fo, None, lo, H, Io, NI, d, rows)
@@ -129,6 +139,7 @@ def test_c3_full_training(seed):
     ro, wo = o.stats()
     rg, wg, _ = g.stats()
     assert ro == rg and np.array_equal(wo, wg) and o.op_counter() == g.op_counter()
+    assert np.array_equal(o.wire_bits(), g.wire_bits_dev())
     # the tree is the plaintext fixed-point Gini CART of the same data
     import plain_cart
     ref = plain_cart.train(w["X"], w["y"], K, H, 16)
@@ -159,4 +170,5 @@ def test_c4_full_inference(seed):
     ro, wo = o.stats()
     rg, wg, _ = g.stats()
     assert ro == rg and np.array_equal(wo, wg)
+    assert np.array_equal(o.wire_bits(), g.wire_bits_dev())
     tree.close(); g.close(); o.close()

@@ -41,6 +41,10 @@ def same_stats(o, g):
     rg, wg, _ = g.stats()
     assert ro == rg and np.array_equal(wo, wg), (ro, rg, wo.tolist(), wg.tolist())
     assert o.op_counter() == g.op_counter()
+    # what the kernels counted at their message stores (payload bits per directed pair)
+    # against what the oracle's protocol steps sent
+    bo, bg = o.wire_bits(), g.wire_bits_dev()
+    assert np.array_equal(bo, bg), (bo.tolist(), bg.tolist())
 
 
 @pytest.mark.parametrize("n", [1, 7, 8, 63, 64, 65, 1000, 4099])
@@ -268,6 +272,69 @@ def test_train_deep_tree_few_samples(mods, seed):
     run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=H), every_level=False)
 
 
+def test_train_reset_starts_an_equal_job(mods, seed):
+    """gt_train_reset reuses every buffer of the object (limb tiles, partial sums, tree):
+    a second job on different data must equal an oracle run started at the same operation
+    counter, share by share, and give the plaintext tree."""
+    import plain_cart
+    from oracle import X_T, X_F, X_M, X_C, X_SD, X_GAMMA
+    from paper_2305_00645_amd import workloads as wl
+    N, d, H = 300, 11, 3
+    wa, wb = wl.c1_train(N=N, d=d, depth=H, seed=31), wl.c1_train(N=N, d=d, depth=H, seed=32)
+    o, g = pair(mods, seed)
+    xa, ya = g.share_a(wa["X"].reshape(-1)), g.share_a(wa["Y"].reshape(-1))
+    oxa, oya = o.share(wa["X"].reshape(-1)), o.share(wa["Y"].reshape(-1))
+    g.train_create(xa, ya, N, d, H)
+    o.train_create(oxa, oya, N, d, H)
+    for h in range(H):
+        g.train_level(h); o.train_level(h)
+    t1 = g.train_finish(); o.train_finish()
+    same(g.train_export(X_T), o.train_export(X_T), "first job T")
+    t1.close()
+    xb, yb = g.share_a(wb["X"].reshape(-1)), g.share_a(wb["Y"].reshape(-1))
+    oxb, oyb = o.share(wb["X"].reshape(-1)), o.share(wb["Y"].reshape(-1))
+    g.train_reset(xb, yb)
+    o.train_create(oxb, oyb, N, d, H)          # the oracle has no reset: a new object, same operation counter
+    assert o.op_counter() == g.op_counter()
+    for h in range(H):
+        g.train_level(h); o.train_level(h)
+        for nm, what in (("M", X_M), ("C", X_C), ("SD", X_SD), ("GAMMA", X_GAMMA), ("F", X_F)):
+            same(g.train_export(what), o.train_export(what), "second job level %d %s" % (h, nm))
+    t2 = g.train_finish()
+    fo, lo = o.train_finish()
+    fg, lg = t2.export()
+    same(fg, fo, "second job features"); same(lg, lo, "second job labels")
+    ref = plain_cart.train(wb["X"], wb["y"], 2, H, 16)
+    assert np.array_equal(g.rec(g.train_export(X_T)).astype(np.int64), ref["T"])
+    same_stats(o, g)
+    # a tree that is still alive when the object finishes again gets buffers of its own
+    g.train_reset(xa, ya)
+    for h in range(H):
+        g.train_level(h)
+    t3 = g.train_finish()
+    assert np.array_equal(g.rec(t2.export()[0]).astype(np.int64), ref["T"][:(1 << H) - 1])
+    ref_a = plain_cart.train(wa["X"], wa["y"], 2, H, 16)
+    assert np.array_equal(g.rec(t3.export()[0]).astype(np.int64), ref_a["T"][:(1 << H) - 1])
+    t2.close(); t3.close()
+
+
+def test_export_after_import_needs_a_level(mods, seed):
+    Oracle, gtree = mods
+    from oracle import X_C, X_M
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c5_level(N=100, d=5, K=2, h=2)
+    g = gtree.GTree(seed, K=2)
+    g.train_create(g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1)), 100, 5, 3)
+    st = [w["M"], w["Tprev"], w["F"], np.zeros(4 * 12, dtype=np.uint64), w["gamma"].reshape(-1)]
+    g.train_import(2, *[g.share_a(a) for a in st])
+    assert np.array_equal(g.rec(g.train_export(X_M)), w["M"])
+    with pytest.raises(gtree.GtError) as e:
+        g.train_export(X_C)
+    assert e.value.code == gtree.GT_ESTATE
+    g.train_level(2)
+    assert g.train_export(X_C).n == 4 * 12
+
+
 def test_train_errors(mods, seed):
     Oracle, gtree = mods
     from paper_2305_00645_amd import workloads as wl
@@ -378,6 +445,40 @@ def test_launch_and_message_pattern_is_data_independent(mods, seed):
         tree.close(); g.close()
     assert seen[0] == seen[1]
     assert seen[0][3]["eqgrid"] > 0 and seen[0][3]["count"] > 0
+
+
+def test_calls_return_before_the_stream_drains(mods, seed):
+    """Calls only enqueue: with a long kernel ahead of it on the context's stream a whole
+    training level returns to the host while that kernel is still running, and the results
+    still equal the oracle's."""
+    import torch
+    from oracle import X_C, X_SD, X_M
+    Oracle, gtree = mods
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c1_train(N=500, d=9, depth=2)
+    N, d, H = w["N"], w["d"], w["H"]
+    o = Oracle(seed)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        g = gtree.GTree(seed, stream=st)
+        xg, yg = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
+        g.train_create(xg, yg, N, d, H)
+        g.train_level(0)
+        st.synchronize()
+        torch.cuda._sleep(int(2.0e9))            # about a second of GPU time on this stream
+        g.train_level(1)
+        tree = g.train_finish()
+        pending = not st.query()                 # the sleep kernel (and everything behind it) has not finished
+        st.synchronize()
+        assert pending, "gt_train_level/gt_train_finish waited for the stream"
+        o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, H)
+        o.train_level(0); o.train_level(1)
+        fo, lo = o.train_finish()
+        fg, lg = tree.export()
+        same(fg, fo, "features"); same(lg, lo, "labels")
+        same(g.train_export(X_M), o.train_export(X_M), "M")
+        same_stats(o, g)
+        tree.close(); g.close()
 
 
 def test_context_on_a_side_stream(mods, seed):

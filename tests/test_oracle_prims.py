@@ -183,3 +183,30 @@ def test_division_is_exact_floor(seed, tau):
     quo = o.div(o.share(u64(S)), o.share(u64(Q)))
     assert np.array_equal(Oracle.rec(quo), want)
     assert o.op_counter() - op0 == 2 + tau + 1
+
+
+def test_payload_bits_follow_the_cost_formulas(seed):
+    """The bit counters (no rounding to bytes) reproduce the paper's per-element costs
+    exactly: equality test 2l-1 = 127 bits per party, comparison 189, bit conversion 1,
+    product l = 64 (Sec. II-B, Sec. V-A)."""
+    o = Oracle(seed)
+    n = 37
+    x = o.share(np.arange(n, dtype=np.uint64))
+    o.stats_reset()
+    o.eq_b(x, None)
+    assert int(o.wire_bits().sum()) == 3 * n * 127
+    assert int(o.wire_bits()[0, 1]) == n * 64 and int(o.wire_bits()[0, 2]) == n * 63
+    o.stats_reset()
+    o.eq_a(x, None)
+    assert int(o.wire_bits().sum()) == 3 * n * 128
+    o.stats_reset()
+    o.ge_a(x, x)
+    assert int(o.wire_bits().sum()) == 3 * n * 190
+    o.stats_reset()
+    o.mult(x, x)
+    assert int(o.wire_bits().sum()) == 3 * n * 64
+    # bytes are the bits of each message rounded up separately
+    o.stats_reset()
+    o.eq_b(o.share(np.arange(3, dtype=np.uint64)), None)
+    assert int(o.stats()[1][0].sum()) == 24 + 12 + 6 + 3 + 2 + 1 + 1      # 3 elements: 64,32,16,8,4,2,1 bits each
+    assert int(o.wire_bits()[0].sum()) == 3 * 127

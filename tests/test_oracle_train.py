@@ -178,6 +178,57 @@ def test_choice_close_to_real_valued_gini_and_exact_rational(seed):
             gam = ngam
 
 
+@pytest.mark.parametrize("N,d,K,h", [(700, 12, 4, 3), (300, 7, 2, 5)])
+def test_level_from_imported_state_matches_plaintext_histogram(seed, N, d, K, h):
+    """The import call (used to start a single level from a synthetic state) holds no
+    arithmetic of its own: after it, one level must route every sample as the plaintext
+    recurrence M <- 2M + X[i][T[M]] + 1 says (Sec. V-B, data partition) and count exactly the
+    plaintext histogram of the routed samples (statistics counting); inherited statistics
+    that are imported are added to, not replaced."""
+    w = wl.c5_level(N=N, d=d, K=K, h=h)
+    CW = d * K + K
+    rng = np.random.default_rng(N)
+    C0 = rng.integers(0, 50, size=(1 << h) * CW).astype(np.uint64)       # inherited statistics
+    o = Oracle(seed, K=K)
+    o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, h + 1)
+    st = [w["M"], w["Tprev"], w["F"], C0, w["gamma"].reshape(-1)]
+    o.train_import(h, *[o.share(a) for a in st])
+    with pytest.raises(RuntimeError):
+        o.train_export(X_C)                    # nothing of a "last level" exists before a level has run
+    assert np.array_equal(Oracle.rec(o.train_export(X_M)), w["M"])       # the state itself is there
+    o.train_level(h)
+    X, y, Mi = w["X"].astype(np.int64), w["y"], w["M"].astype(np.int64)
+    M = 2 * Mi + 1 + X[np.arange(N), w["Tprev"].astype(np.int64)[Mi - ((1 << (h - 1)) - 1)]]
+    assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), M)
+    C = Oracle.rec(o.train_export(X_C)).astype(np.int64).reshape(1 << h, CW)
+    C0 = C0.astype(np.int64).reshape(1 << h, CW)
+    for r in range(1 << h):
+        sel = M == (1 << h) - 1 + r
+        for c in range(K):
+            assert C[r, d * K + c] == C0[r, d * K + c] + (sel & (y == c)).sum()
+            assert np.array_equal(C[r, :d * K].reshape(d, K)[:, c],
+                                  C0[r, :d * K].reshape(d, K)[:, c] + X[sel & (y == c)].sum(axis=0))
+    # all nodes were imported as real leaves: the one-hot of a sample is 1 exactly at its node
+    LT = Oracle.rec(o.train_export(X_L)).astype(np.int64).reshape(1 << h, -1)[:, :N]
+    assert np.array_equal(LT, ((M[None, :] - ((1 << h) - 1)) == np.arange(1 << h)[:, None]).astype(np.int64))
+    # a level started by import consumes the same operations and messages as the same level
+    # reached by training: partition 2 array accesses, leaf flags, grid, count, ...
+    o2 = Oracle(seed, K=K)
+    o2.train_create(o2.share(w["X"].reshape(-1)), o2.share(w["Y"].reshape(-1)), N, d, h + 1)
+    for hh in range(h):
+        o2.train_level(hh)
+    ops0, (r0, w0) = o2.op_counter(), o2.stats()
+    o2.train_level(h)
+    o3 = Oracle(seed, K=K)
+    o3.train_create(o3.share(w["X"].reshape(-1)), o3.share(w["Y"].reshape(-1)), N, d, h + 1)
+    o3.train_import(h, *[o3.share(a) for a in st])
+    ops1, (r1, w1) = o3.op_counter(), o3.stats()
+    o3.train_level(h)
+    assert o2.op_counter() - ops0 == o3.op_counter() - ops1
+    assert o2.stats()[0] - r0 == o3.stats()[0] - r1
+    assert np.array_equal(o2.stats()[1] - w0, o3.stats()[1] - w1)
+
+
 def test_wire_and_rounds_do_not_depend_on_data(seed):
     """Only sizes and depth may show in the message pattern (Sec. I, goals)."""
     res = []
