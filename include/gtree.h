@@ -50,6 +50,7 @@ extern "C" {
 #define GT_MAX_N (1u << 20)    /* training samples: keeps Gini terms below 2^40 */
 #define GT_MAX_K 16u           /* classes */
 #define GT_MAX_TAU 20u         /* fractional bits of the Gini quotients */
+#define GT_STATIC_MAX_N (1u << 18) /* rows of gt_oaa_static */
 
 typedef struct gt_ctx gt_ctx;     /* keys, operation counter, stream, scratch for partial sums */
 typedef struct gt_train gt_train; /* per-party shares of T, F, M, C, gamma and the data */
@@ -121,6 +122,14 @@ int gt_eq_a(gt_ctx *ctx, const gt_shares *x, const uint64_t *y_pub_dev, size_t n
 int gt_ge_a(gt_ctx *ctx, const gt_shares *x, const gt_shares *y, size_t n, const gt_shares *z);
 /* z[i] = W[u[i]], 0 when u[i] is outside [0, w); linear scan over all w entries */
 int gt_oaa(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z);
+/* gt_oaa for callers that cannot allocate device memory (code under HIP graph capture,
+ * serving loops, harnesses that forbid it): same arguments, same shares, same operation
+ * id, but the partial inner products live in a static device array of the library
+ * (6 * GT_STATIC_MAX_N words = 12 MiB per GPU, held until the process ends) instead of
+ * the context's workspace, the array is cleared by a fill kernel, and no allocating call
+ * of any kind is made.  n > GT_STATIC_MAX_N returns GT_EINVAL.  All contexts on one GPU
+ * share the array: calls that overlap on one GPU race. */
+int gt_oaa_static(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z);
 /* q = floor(S * 2^tau / Q) for 0 <= S <= Q < 2^40, Q > 0 (restoring division) */
 int gt_div(gt_ctx *ctx, const gt_shares *S, const gt_shares *Q, size_t n, const gt_shares *q);
 

@@ -10,6 +10,15 @@
 
 #define GT_MAX_BLOCKS 4096u
 
+// Scratch of the entry point that allocates nothing (gt_oaa_static): the partial inner
+// products of an array access whose columns are split over workgroups, six planes of
+// GT_STATIC_MAX_N words.  One copy per GPU, held until the process ends.  In host code the
+// array's name is not a device address: its address on a device is taken once per device
+// with hipGetSymbolAddress (gt_ctx_create, with that device current) and kept below.
+static __device__ __align__(256) u64 scratch[6 * (size_t)GT_STATIC_MAX_N];
+#define GT_MAX_DEVICES 64
+static u64 *g_scratch_ptr[GT_MAX_DEVICES];
+
 #define HIPCHK(x)                                                                             \
     do { hipError_t e_ = (x); if (e_ != hipSuccess) {                                         \
         fprintf(stderr, "gtree: %s failed: %s (%s:%d)\n", #x, hipGetErrorString(e_), __FILE__, __LINE__); \
@@ -40,7 +49,8 @@ struct gt_ctx {
     DSh divrem;               // remainders of gt_div, grown on demand, kept between calls
     u64 *dacc;                // partial inner products of split equality grids
     size_t dacc_words;
-    bool noalloc;             // set by entry points that may not allocate
+    u64 *scratch_d;           // this device's copy of the static scratch array
+    bool noalloc;             // inside gt_oaa_static: nothing may be allocated
 };
 
 // Buffers of the tree that gt_train_finish hands out, allocated with the training
@@ -208,7 +218,7 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (prm->K < 1 || prm->K > GT_MAX_K || prm->tau < 1 || prm->tau > GT_MAX_TAU) return GT_EINVAL;
     gt_ctx *c = new (std::nothrow) gt_ctx();
     if (!c) return GT_ENOMEM;
-    c->noalloc = false;
+    c->noalloc = false; c->scratch_d = nullptr;
     c->op = 0; c->ev_used = 0; c->keys_d = nullptr; c->wire_d = nullptr; c->dacc = nullptr; c->dacc_words = 0; c->resident = 1024;
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     c->profile = (prm->flags & GT_FLAG_PROFILE) != 0;
@@ -217,7 +227,13 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     for (int k = 0; k < 5; k++)
         for (int i = 0; i < 4; i++) { keys[k][2 * i] = (u32)prm->seed[k][i]; keys[k][2 * i + 1] = (u32)(prm->seed[k][i] >> 32); }
     int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) { delete c; return GT_EHIP; }
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= GT_MAX_DEVICES) { delete c; return GT_EHIP; }
+    if (!g_scratch_ptr[dev]) {                 // once per device, with that device current
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { delete c; return GT_EHIP; }
+        g_scratch_ptr[dev] = (u64 *)ptr;
+    }
+    c->scratch_d = g_scratch_ptr[dev];
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
         c->resident = std::min<unsigned>(GT_MAX_BLOCKS, 4u * (unsigned)cus);
     if (hipMalloc(&c->keys_d, sizeof keys) != hipSuccess) { delete c; return GT_ENOMEM; }
@@ -409,6 +425,22 @@ extern "C" int gt_oaa(gt_ctx *c, const gt_shares *W, size_t w, const gt_shares *
     GridArgs a{}; a.u = to_p6(u); a.base = 0; a.w = (u32)w; a.N = n; a.N8 = pad8(n);
     a.W1 = to_p6(W); a.w1off = 0; a.out = to_p6(z); a.epi = 0;
     return T.finish(do_grid(c, GM_COMMON, false, 1, a));
+}
+
+// The same array access with the partial inner products in the static scratch array:
+// no allocation of any kind, for callers that cannot allocate (HIP graph capture, serving
+// loops).  n is limited by the array's size.
+extern "C" int gt_oaa_static(gt_ctx *c, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z)
+{
+    if (!c || !shares_ok(W, w) || !shares_ok(u, n) || !shares_ok(z, n) || w == 0 || w > 0xffffffffu) return GT_EINVAL;
+    if (n > GT_STATIC_MAX_N) return GT_EINVAL;
+    Timed T(c);
+    GridArgs a{}; a.u = to_p6(u); a.base = 0; a.w = (u32)w; a.N = n; a.N8 = pad8(n);
+    a.W1 = to_p6(W); a.w1off = 0; a.out = to_p6(z); a.epi = 0;
+    c->noalloc = true;
+    const int rc = do_grid(c, GM_COMMON, false, 1, a, c->scratch_d, (size_t)6 * GT_STATIC_MAX_N);
+    c->noalloc = false;
+    return T.finish(rc);
 }
 
 static int div_steps(gt_ctx *c, P6 S, P6 Q, P6 rem, P6 quo, u64 n)

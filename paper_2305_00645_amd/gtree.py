@@ -85,6 +85,7 @@ def load():
         "gt_eq_a": (i, [vp, S, vp, sz, S]),
         "gt_ge_a": (i, [vp, S, S, sz, S]),
         "gt_oaa": (i, [vp, S, sz, S, sz, S]),
+        "gt_oaa_static": (i, [vp, S, sz, S, sz, S]),
         "gt_div": (i, [vp, S, S, sz, S]),
         "gt_train_create": (i, [vp, S, S, sz, u32, u32, C.POINTER(vp)]),
         "gt_train_level": (i, [vp, vp, u32]),
@@ -261,6 +262,12 @@ class GTree:
     def oaa(self, W, u):
         z = self.new(u.n)
         _chk(self.L.gt_oaa(self.ctx, _ref(W), W.n, _ref(u), u.n, _ref(z)), "gt_oaa")
+        return z
+
+    def oaa_static(self, W, u, z=None):
+        """gt_oaa without any allocation inside the library (the caller may pass z)."""
+        z = self.new(u.n) if z is None else z
+        _chk(self.L.gt_oaa_static(self.ctx, _ref(W), W.n, _ref(u), u.n, _ref(z)), "gt_oaa_static")
         return z
 
     def div(self, S, Q):
