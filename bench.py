@@ -19,8 +19,19 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
-EQ_ALU_OPS = 700                # algorithmic 32-bit ALU ops per equality test, three parties: one dealer ChaCha8 block (400 ops) + 3 mask blocks per 8 tests = 550, protocol steps 3 x 50 on packed fields
-EQ_HBM_BYTES_MEASURED = 29.0    # HBM bytes per equality test from rocprofv3 FETCH_SIZE/WRITE_SIZE (profiles/pmc_traffic_micro.md)
+# Algorithmic 32-bit ALU ops per equality test, three parties together: one dealer ChaCha8 block
+# (400 ops: the edaBit and daBit of the test, offline material that the paper's timings exclude but
+# that this simulation derives inside the kernel) + 3 mask blocks per 8 tests (150: the zero
+# sharings of the AND rounds, online) + protocol steps 3 x 50 on packed fields (online)
+EQ_ALU_OPS_DEALER, EQ_ALU_OPS_ONLINE = 400, 300
+EQ_ALU_OPS = EQ_ALU_OPS_DEALER + EQ_ALU_OPS_ONLINE
+# HBM bytes per equality test of the three grid variants, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# (table in profiles/pmc_traffic_micro.md): inner product against a shared array, against the
+# sample's own row, leaf one-hot written as limb tiles
+# (the one-launch inference reads the instances once and writes one result per instance; its
+# figure is the counter bytes of the C5 batch over its 2.687e9 tests)
+EQ_HBM_BYTES = {"eqgrid": 7.3, "eqgrid_rows": 81.6, "eqgrid_store": 52.1, "infer": 1.2}
+SHADER_CLOCK_MEASURED_GHZ = 2.1  # under the equality grid's load (profiles/pmc_sq_micro.md); the peak below uses the nominal 2.4
 
 
 def paper_literal_ol_bytes(N, d, K, h, H, l=64):
@@ -49,16 +60,21 @@ def paper_shapes(np, torch, gtree, wl):
     X, Y = g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1))
     g.train_create(X, Y, N, d, H)
     times, per_level = [], None
-    for it in range(6):
+    for it in range(7):
         torch.cuda.synchronize(); t0 = time.perf_counter()
         g.train_reset(X, Y)
         lv = []
         for h in range(H):
-            t1 = time.perf_counter(); g.train_level(h); lv.append(time.perf_counter() - t1)
+            if it == 6:                          # last run only: wait after every level for the per-level figures
+                torch.cuda.synchronize(); t1 = time.perf_counter()
+            g.train_level(h)
+            if it == 6:
+                torch.cuda.synchronize(); lv.append(time.perf_counter() - t1)
         g.train_finish().close()
         torch.cuda.synchronize()
-        if it:
-            times.append(time.perf_counter() - t0); per_level = lv
+        if 0 < it < 6:
+            times.append(time.perf_counter() - t0)
+        per_level = lv
     tm = sorted(times)[len(times) // 2]
     ncand = sum((1 << h) * d for h in range(H))
     res["c3_train_depth7"] = {"samples": N, "columns": d, "seconds": tm, "candidates_per_s": ncand / tm,
@@ -117,7 +133,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--samples", type=int, default=1000000, help="training samples (C5: 10^6)")
     ap.add_argument("--instances", type=int, default=1000000, help="inference batch (C5: 10^6)")
-    ap.add_argument("--cpu-samples", type=int, default=500000, help="oracle sample for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-samples", type=int, default=1000000, help="oracle samples for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-single-samples", type=int, default=62500,
+                    help="samples of the single-threaded oracle timing (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the C3 training / C4 inference timings")
     ap.add_argument("--only-paper-shapes", action="store_true",
@@ -164,7 +182,8 @@ def main():
         t0 = time.perf_counter()
         g.train_reset(st["X"], st["Y"])                                   # a0
         torch.cuda.synchronize(); t1 = time.perf_counter()
-        g.train_import(h, st["M"], st["Tprev"], st["F"], st["C"], st["gamma"])
+        g.train_import(h, st["M"], st["Tprev"], st["F"], st["C"], st["gamma"])   # set-up of the level's state (copies)
+        torch.cuda.synchronize(); t1b = time.perf_counter()
         g.train_level(h)                                                  # a1-a7
         torch.cuda.synchronize(); t2 = time.perf_counter()
         tree = g.train_finish()                                           # a1, a2, a8 at level H
@@ -173,13 +192,14 @@ def main():
         torch.cuda.synchronize(); t4 = time.perf_counter()
         tree.close()
         if t is not None:
-            t["a0"] += t1 - t0; t["level"] += t2 - t1; t["finish"] += t3 - t2; t["infer"] += t4 - t3
+            t["a0"] += t1 - t0; t["import"] += t1b - t1; t["level"] += t2 - t1b; t["finish"] += t3 - t2; t["infer"] += t4 - t3
         return R
 
     g, st = setup(False)
     for _ in range(args.warmup):
         step(g, st, None)
     t = dict(a0=0.0, level=0.0, finish=0.0, infer=0.0)
+    t["import"] = 0.0
     torch.cuda.synchronize()
     T0 = time.perf_counter()
     for _ in range(args.steps):
@@ -196,6 +216,7 @@ def main():
         g.train_level(h)
         lvl_rounds, lvl_wire, _ = g.stats()
         lvl_msgs = {"rounds": lvl_rounds, "bytes_sent_per_party": int(lvl_wire[0].sum()),
+                    "payload_bits_counted_by_the_kernels_per_party": int(g.wire_bits_dev()[0].sum()),
                     "paper_literal_learning_bytes_per_party": paper_literal_ol_bytes(N, d, K, h, H),
                     "note": "the library fuses select-and-accumulate into inner products with one reshare per "
                             "output; the second figure prices the learning protocol as printed (analytic)"}
@@ -220,8 +241,8 @@ def main():
                                "nodes (%d candidates) + depth-%d inference on %d instances; 3 parties on 1 GPU, Z_2^64, tau=16"
                                % (N, d, K, 1 << h, ncand, Hinf, NI),
                    "value_from": "candidates / time of gt_train_level(h=%d)" % h},
-        "breakdown_ms": {"a0_products": ms["a0"], "a1_a7_level": ms["level"], "a1_a2_a8_label_level": ms["finish"],
-                         "b1_b5_inference": ms["infer"]},
+        "breakdown_ms": {"a0_products": ms["a0"], "state_import_copies": ms["import"], "a1_a7_level": ms["level"],
+                         "a1_a2_a8_label_level": ms["finish"], "b1_b5_inference": ms["infer"]},
         "inference_instances_per_s": NI / (ms["infer"] / 1e3), "inference_depth": Hinf,
         "level_messages": lvl_msgs,
     }
@@ -236,26 +257,45 @@ def main():
         prof = g.prof()
         g.close(); del g, st
         torch.cuda.empty_cache()
-        dom = max(prof, key=lambda c: prof[c][0])
-        # per step: equality tests of a1 (N x (2^(h-1) + d)), a2 (N x 2^h), label level (N x (2^h + d) + N x 2^(h+1)),
-        # inference (N_I x (2^Hinf - 1 + Hinf*d + 2^Hinf))
-        n_eq = N * ((1 << (h - 1)) + d + (1 << h)) + N * ((1 << h) + d + (1 << (h + 1))) \
-            + NI * ((1 << Hinf) - 1 + Hinf * d + (1 << Hinf))
-        eq_ms, eq_l = prof["eqgrid"]
+        # equality tests per step and kernel: array access over a shared array (partition over the tree
+        # level), over the sample's own row (feature fetch), leaf one-hot (level and label level), and
+        # the one-launch inference (node lookups, feature fetches, labels of all levels)
+        n_var = {
+            "eqgrid": N * (1 << (h - 1)) + N * (1 << h),
+            "eqgrid_rows": N * d + N * d,
+            "eqgrid_store": N * (1 << h) + N * (1 << (h + 1)),
+            "infer": NI * ((1 << Hinf) - 1 + Hinf * d + (1 << Hinf)),
+        }
+        n_eq = sum(n_var.values())
+        eq_ms = sum(prof[c][0] for c in n_var)
+        eq_l = sum(prof[c][1] for c in n_var)
         cnt_ms, cnt_l = prof["count"]
         macs = 3 * 2 * N * ((1 << h) * CW + (1 << (h + 1)) * K)         # ring MACs per step, all parties
-        eq_per_launch = n_eq * k / max(eq_l, 1)
+        eq_bytes_step = sum(EQ_HBM_BYTES[c] * n_var[c] for c in n_var)
+        per_variant = {c: {"tests_per_step": n_var[c], "ms_per_step": prof[c][0] / k, "launches_per_step": prof[c][1] // k,
+                           "tests_per_s": n_var[c] * k / (prof[c][0] / 1e3) if prof[c][0] else None,
+                           "hbm_bytes_per_test": EQ_HBM_BYTES[c],
+                           "hbm_GBps": EQ_HBM_BYTES[c] * n_var[c] * k / (prof[c][0] / 1e3) / 1e9 if prof[c][0] else None}
+                       for c in n_var}
         kern = {
             "eqgrid": {"bound": "alu", "achieved": EQ_ALU_OPS * n_eq * k / (eq_ms / 1e3) / 1e12, "peak": LANE_OPS_PEAK,
-                       "unit": "Tops/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
-                       "note": "%d 32-bit ALU ops per equality test for the three parties (PRF blocks + protocol); "
-                               "peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; traffic = measured HBM bytes per "
-                               "test (profiles/pmc_traffic_micro.md) x tests per launch; %d tests/step" % (EQ_ALU_OPS, n_eq),
+                       "unit": "Tops/s", "traffic": eq_bytes_step * k / max(eq_l, 1),
+                       "note": "the equality-test kernels together (three grid variants of training and the one-launch inference: most of the step); %d 32-bit ALU ops per "
+                               "test for the three parties, of which %d are the dealer's PRF block (offline material of the test: "
+                               "the paper's timings exclude its generation, this simulation derives it in the kernel) and %d are "
+                               "online work (mask words 150, protocol 150): counting online ops only the figure is %.2f of the "
+                               "peak; peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz nominal (the shader clock under this load "
+                               "reads %.1f GHz); traffic = HBM bytes per launch = per-variant counter bytes per test "
+                               "(profiles/pmc_traffic_micro.md) x this run's tests per variant; the >=50%% HBM target of the "
+                               "workload description is not met and cannot be by this kernel: its messages stay in LDS and it "
+                               "is bound by the PRF (VALU issue share 0.76-0.81, profiles/pmc_sq_micro.md), see eqgrid_hbm_view"
+                               % (EQ_ALU_OPS, EQ_ALU_OPS_DEALER, EQ_ALU_OPS_ONLINE,
+                                  EQ_ALU_OPS_ONLINE * n_eq * k / (eq_ms / 1e3) / 1e12 / LANE_OPS_PEAK, SHADER_CLOCK_MEASURED_GHZ),
                        "avg_launch_ms": eq_ms / max(eq_l, 1), "launches_per_step": eq_l // k,
-                       "eq_tests_per_s": n_eq * k / (eq_ms / 1e3)},
-            "eqgrid_hbm_view": {"bound": "hbm", "achieved": EQ_HBM_BYTES_MEASURED * n_eq * k / (eq_ms / 1e3) / 1e9,
-                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": EQ_HBM_BYTES_MEASURED * eq_per_launch,
-                                "note": "measured HBM bytes per test x tests/s: the protocol messages (200 B per test) pass "
+                       "eq_tests_per_s": n_eq * k / (eq_ms / 1e3), "variants": per_variant},
+            "eqgrid_hbm_view": {"bound": "hbm", "achieved": eq_bytes_step * k / (eq_ms / 1e3) / 1e9,
+                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": eq_bytes_step * k / max(eq_l, 1),
+                                "note": "per-variant HBM bytes per test x tests/s: the protocol messages (200 B per test) pass "
                                         "through LDS, HBM sees the operands and results only, so this is not the binding limit"},
             "count": {"bound": "mfma", "achieved": 72.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": 5000.0,
                       "unit": "TOP/s", "traffic": None,
@@ -265,9 +305,12 @@ def main():
         }
         for v in kern.values():
             v["frac"] = v["achieved"] / v["peak"]
+        cls_ms = {c: prof[c][0] / k for c in prof}
+        dom = "eqgrid" if eq_ms >= max(prof[c][0] for c in prof if c not in n_var) else max(
+            (c for c in prof if c not in n_var), key=lambda c: prof[c][0])
         dom = dom if dom in kern else "eqgrid"
         out["roofline"] = dict(kern[dom], kernel=dom)
-        out["kernel_classes_ms_per_step"] = {c: prof[c][0] / k for c in prof}
+        out["kernel_classes_ms_per_step"] = cls_ms
         out["roofline_other"] = {c: v for c, v in kern.items() if c != dom}
 
     if not args.no_paper_shapes:
@@ -275,21 +318,38 @@ def main():
 
     if args.cpu_samples > 0:
         from oracle import Oracle, orc
+
+        def oracle_level(Ns, threads):
+            ws = wl.c5_level(N=Ns, d=d, K=K, h=h)
+            if threads:
+                orc.set_threads(threads)
+            o = Oracle(wl.PROTOCOL_SEED, tau=16, K=K)
+            xs, ys = o.share(ws["X"].reshape(-1)), o.share(ws["Y"].reshape(-1))
+            sto = [o.share(a) for a in (ws["M"], ws["Tprev"], ws["F"], np.zeros((1 << h) * CW, dtype=np.uint64), ws["gamma"].reshape(-1))]
+            o.train_create(xs, ys, Ns, d, H)
+            o.train_import(h, *sto)
+            c0 = time.perf_counter()
+            o.train_level(h)
+            dt = time.perf_counter() - c0
+            o.close()
+            return dt
+
+        all_threads = orc.get_threads()
         Ns = min(args.cpu_samples, N)
-        ws = wl.c5_level(N=Ns, d=d, K=K, h=h)
-        o = Oracle(wl.PROTOCOL_SEED, tau=16, K=K)
-        xs, ys = o.share(ws["X"].reshape(-1)), o.share(ws["Y"].reshape(-1))
-        sto = [o.share(a) for a in (ws["M"], ws["Tprev"], ws["F"], np.zeros((1 << h) * CW, dtype=np.uint64), ws["gamma"].reshape(-1))]
-        o.train_create(xs, ys, Ns, d, H)
-        o.train_import(h, *sto)
-        c0 = time.perf_counter()
-        o.train_level(h)
-        cpu_s = time.perf_counter() - c0
+        cpu_s = oracle_level(Ns, 0)
+        full = Ns == N
         out["cpu_baseline"] = {
-            "value": ncand / (cpu_s * N / Ns), "unit": "candidates/s", "cores": orc.get_threads(), "kind": "oracle",
-            "sample": "the same level on %d of the %d samples took %.2f s on the host; scaled linearly in the sample count"
-                      % (Ns, N, cpu_s)}
-        o.close()
+            "value": ncand / (cpu_s * N / Ns), "unit": "candidates/s", "cores": all_threads, "kind": "oracle",
+            "sample": ("full size: the same level on all %d samples took %.2f s on the host" % (N, cpu_s)) if full else
+                      ("the same level on %d of the %d samples took %.2f s on the host; scaled linearly in the sample count" % (Ns, N, cpu_s))}
+        if args.cpu_single_samples > 0:
+            N1 = min(args.cpu_single_samples, N)
+            s1 = oracle_level(N1, 1)
+            orc.set_threads(all_threads)
+            out["cpu_baseline"]["single_thread"] = {
+                "value": ncand / (s1 * N / N1), "unit": "candidates/s", "cores": 1,
+                "sample": "the same level on %d of the %d samples took %.2f s on one thread; scaled linearly in the sample "
+                          "count (the level's work is linear in the samples: per-sample equality tests and inner products)" % (N1, N, s1)}
     print(json.dumps(out))
 
 

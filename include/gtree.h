@@ -82,6 +82,14 @@ typedef struct {
  * context's stream and accumulate time and launch count per kernel class; the pairs
  * are read when the times are asked for (gt_prof_get, gt_stats_get). */
 #define GT_FLAG_PROFILE 1u
+/* GT_FLAG_LEVELWISE_INFER: gt_infer_batch runs level by level (two equality-grid launches
+ * per level with the node index in device memory) instead of one launch that carries every
+ * instance through all levels; same shares, kept for comparison. */
+#define GT_FLAG_LEVELWISE_INFER 2u
+/* tuning knob of the one-launch inference: instances per workgroup 16 / 32 / 64 instead of
+ * the choice made from the batch size (flags |= GT_FLAG_INFER_TILE(16)) */
+#define GT_FLAG_INFER_TILE_MASK 0x300u
+#define GT_FLAG_INFER_TILE(n) ((n) == 16 ? 0x100u : (n) == 32 ? 0x200u : (n) == 64 ? 0x300u : 0u)
 enum {
     GT_KC_SHARE = 0, /* share / reconstruct */
     GT_KC_MULT = 1,  /* elementwise products with reshare */
@@ -92,7 +100,8 @@ enum {
     GT_KC_LOCAL = 5, /* copies, transposes, fills (no messages) */
     GT_KC_EQGRID_ROWS = 6,  /* equality grid with inner product against the sample's own row */
     GT_KC_EQGRID_STORE = 7, /* equality grid that stores the per-sample leaf one-hot */
-    GT_KC_N = 8
+    GT_KC_INFER = 8,        /* one-launch inference */
+    GT_KC_N = 9
 };
 typedef struct { double ms[GT_KC_N]; uint64_t launches[GT_KC_N]; } gt_prof;
 

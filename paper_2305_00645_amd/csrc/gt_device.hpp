@@ -330,7 +330,8 @@ __device__ __forceinline__ Sh and_bit(Wire &W, Sh x, Sh y, u64 alpha, bool act)
 }
 
 // Comparison [v >= 0] (v signed, |v| < 2^63) -> Boolean bit sharing.
-__device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D, bool act)
+// AG, AE: the lane's Boolean zero-sharing words of streams 1 and 2 (own xor next key).
+__device__ __forceinline__ Sh ge_bit_masks(Wire &W, int p, Sh v, const Dealer &D, u64 AG, u64 AE, bool act)
 {
     const u64 LOW63 = 0x7fffffffffffffffull, TOP = 0x8000000000000000ull;
     Sh m = v + D.rA;
@@ -341,8 +342,6 @@ __device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op,
     E.o = D.rho.o & LOW63;      E.n = D.rho.n & LOW63;
     if (p == 0) E.o = ((D.rho.o ^ nc) & LOW63) | TOP;
     if (p == 2) E.n = ((D.rho.n ^ nc) & LOW63) | TOP;
-    u64 AG, AE;
-    zero_b2(K, op, 1, 2, e, AG, AE);
 #pragma unroll
     for (int k = 0; k < 6; k++) {
         const int s = 1 << k;
@@ -370,6 +369,15 @@ __device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op,
     if (p == 0) ge.o ^= (c >> 63) ^ 1;
     if (p == 2) ge.n ^= (c >> 63) ^ 1;
     return ge;
+}
+
+// the same with the mask words of element e taken from the wavefront's PRF tile
+// (element 64*tile + lane in every lane)
+__device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op, u64 e, Sh v, const Dealer &D, bool act)
+{
+    u64 AG, AE;
+    zero_b2(K, op, 1, 2, e, AG, AE);
+    return ge_bit_masks(W, p, v, D, AG, AE, act);
 }
 
 // bit -> arithmetic: open f = s xor beta; s = beta if f = 0 else 1 - beta

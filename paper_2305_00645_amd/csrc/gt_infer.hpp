@@ -1,0 +1,267 @@
+// Oblivious inference in one launch (Sec. V-C of the GTree paper).  The H iterations of an
+// instance - array access over the level's slice of the tree, array access into the
+// instance's own features, optional threshold comparison, index update - and the final
+// access over the leaf labels do not interact with any other instance, so a workgroup
+// carries a tile of instances through all of them with the node index and the fetched
+// id / threshold / value in registers: no per-level launches, no partial sums in device
+// memory, no workspace.  Operation ids, element indices (k*N8 + i) and streams are those
+// of the level-by-level path, so every share is the same.
+#pragma once
+#include "gt_kernels.hpp"
+
+struct InferArgs {
+    KCommon c;                 // c.op: first operation id of the batch
+    P6 feat, thr, leaf;        // 2^H-1 ids, 2^H-1 thresholds (has_thr), 2^H labels
+    P6 I, out;                 // NI x d row-major instances, NI results
+    u64 NI, N8;
+    u32 d, H;
+    int has_thr;
+};
+
+// Words of NS streams under the own and the next key for the tile's IT consecutive
+// elements e0 .. e0+IT-1 (e0 a multiple of 8), element e0 + (lane mod IT) in every lane
+// that works on it.  A PRF block holds the words of 8 consecutive elements: IT/8 blocks
+// per key and stream, one lane each, handed round through the wavefront's scratch in LDS.
+template <int NS, int LGI>
+__device__ __forceinline__ void prf_tile_it(const PartyKeys &K, u32 op, const u32 (&st)[NS], u64 e0, u64 (&wo)[NS], u64 (&wn)[NS])
+{
+    constexpr u32 IT = 1u << LGI, NB = IT / 8;
+    static_assert(2 * NS * NB <= GT_LANES, "more blocks than lanes");
+    const u32 lane = threadIdx.x, inst = lane & (IT - 1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane < 2 * NS * NB) {
+        const u32 q = lane / (2 * NB), r = lane % (2 * NB), ks = r / NB, g = r % NB;
+        const u32 mk = 0u - ks;
+        Key kv;
+#pragma unroll
+        for (int i = 0; i < 8; i++) kv.k[i] = K.own.k[i] ^ ((K.own.k[i] ^ K.nxt.k[i]) & mk);
+        u32 stream = 0;
+#pragma unroll
+        for (int j = 0; j < NS; j++) stream |= st[j] & (0u - (u32)(q == (u32)j));
+        u64 blk[8];
+        chacha8(kv, (e0 >> 3) + g, op, stream, blk);
+#pragma unroll
+        for (int i = 0; i < 8; i++) K.scr[(q * 2 + ks) * IT + g * 8 + i] = blk[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < NS; j++) { wo[j] = K.scr[(2 * j) * IT + inst]; wn[j] = K.scr[(2 * j + 1) * IT + inst]; }
+}
+
+// sum over the 64/IT lanes that hold the same instance (lane = cg*IT + inst)
+template <int LGI>
+__device__ __forceinline__ u64 sum_over_column_groups(u64 v)
+{
+#pragma unroll
+    for (int m = 1 << LGI; m < GT_LANES; m <<= 1) v += (u64)__shfl_xor((unsigned long long)v, m, GT_LANES);
+    return v;
+}
+
+// State of one workgroup: LDS rows as in k_eqgrid (rows 0-2: r arithmetic components,
+// then the opening's messages, then the mask words; rows 3-5: r Boolean components, then
+// the messages of the AND rounds, conversions and reshares; rows 6-8: beta arithmetic
+// components, between two steps party p's PRF scratch in row 6+p).
+template <int LGI>
+struct InferWg {
+    static constexpr u32 IT = 1u << LGI, LPI = GT_LANES >> LGI, CS = 8 * LPI;   // instances per tile, lanes per instance, columns per step
+    u64 (*s_mat)[GT_TILE_EL];
+    u32 (*s_bitw)[GT_LANES];
+    LWire LW;
+    PartyKeys K;
+    int p, pn, pp, lane, tid;
+    u32 inst, cg, par;
+    u64 N8, tile0;            // first instance of the tile
+    u64 i;                    // this lane's instance
+    bool valid;
+
+    // One array access: E[k] = [u - base == k] for k < w, converted to arithmetic, and
+    // z = sum_k E[k] * W1[w1off + k] (ROWS: * the instance's own feature k), z2 likewise
+    // with W2 (NDOT = 2); zero sharing of stream 2 (3), word i; one reshare round.
+    template <bool ROWS, int NDOT>
+    __device__ __forceinline__ void access(u32 op, Sh u, u64 base, u32 w, const P6 &W1, u64 w1off, const P6 &W2, u64 w2off,
+                                           const P6 &I, u32 d, Sh &z, Sh &z2)
+    {
+        const Sh one = pub(p, 1);
+        u64 acc = 0, acc2 = 0;
+        for (u32 k0 = 0; k0 < w; k0 += CS) {
+            // the dealer's 512 blocks of the step, spread over the 192 lanes
+#pragma unroll 1
+            for (int j = 0; j < 3; j++) {
+                const int el = j * 192 + tid;
+                if (el < GT_TILE_EL) {
+                    const u32 ln = el & (GT_LANES - 1), sl = (u32)el >> 6;
+                    const u64 e = (u64)(k0 + (ln >> LGI) * 8 + sl) * N8 + tile0 + (ln & (IT - 1));
+                    u64 D[8];
+                    chacha8(K.dlr, e, op, 0, D);
+                    const u64 beta = D[5] & 1;
+                    s_mat[0][el] = D[1]; s_mat[1][el] = D[2]; s_mat[2][el] = D[0] - D[1] - D[2];
+                    s_mat[3][el] = D[3]; s_mat[4][el] = D[4]; s_mat[5][el] = D[0] ^ D[3] ^ D[4];
+                    s_mat[6][el] = D[6]; s_mat[7][el] = D[7]; s_mat[8][el] = beta - D[6] - D[7];
+                    const u32 b0 = (u32)(D[5] >> 1) & 1, b1 = (u32)(D[5] >> 2) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
+                    atomicOr(&s_bitw[par][ln], (b0 << sl) | (b1 << (8 + sl)) | (b2 << (16 + sl)));
+                }
+            }
+            // mask words under the own key: this lane evaluates the block of column
+            // k0 + lane / (IT/8), instances 8 * (lane mod IT/8) .. +7 of the tile
+            u64 A[8];
+            {
+                const u32 cc = (u32)lane >> (LGI - 3), gg = (u32)lane & (IT / 8 - 1);
+                chacha8(K.own, (((u64)(k0 + cc) * N8 + tile0) >> 3) + gg, op, 1, A);
+            }
+            __syncthreads();
+            u64 snd[8], rcv[8], mn[8];
+            u32 nl = 0;
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const u32 col = k0 + cg * 8 + s;
+                nl += (valid && col < w) ? 1u : 0u;
+                const int el = s * GT_LANES + lane;
+                const Sh nsub = pub(p, 0 - (base + col));
+                snd[s] = u.o + nsub.o + s_mat[p][el];      // columns beyond w, instances beyond NI: any value serves
+                mn[s] = u.n + nsub.n + s_mat[pn][el];
+            }
+            if (p == 0) s_bitw[par ^ 1][lane] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = snd[s];   // the opening, 64 bits per test
+            LW.nopen += 64u * nl;
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) rcv[s] = s_mat[pp][s * GT_LANES + lane];
+            Sh t[8];
+            if (p == 0) {
+#pragma unroll
+                for (int s = 0; s < 8; s++) {
+                    const int el = s * GT_LANES + lane;
+                    t[s].o = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
+                    t[s].n = s_mat[4][el];
+                }
+            } else if (p == 2) {
+#pragma unroll
+                for (int s = 0; s < 8; s++) {
+                    const int el = s * GT_LANES + lane;
+                    t[s].n = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
+                    t[s].o = s_mat[5][el];
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 8; s++) {
+                    const int el = s * GT_LANES + lane;
+                    t[s].o = s_mat[4][el];
+                    t[s].n = s_mat[5][el];
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) s_mat[p][8 * lane + s] = A[s];           // block (cc, gg): words of 8 instances
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const u32 idx = (cg * 8 + s) * IT + inst;
+                A[s] = s_mat[p][idx] ^ s_mat[pn][idx];
+            }
+            u32 To8, Tn8;
+            eq_rounds8_packed(LW, t, A, nl, To8, Tn8);
+            u32 f;
+            {
+                const u32 bw = s_bitw[par][lane];
+                const u32 fo = To8 ^ ((bw >> (8 * p)) & 0xffu), fn = Tn8 ^ ((bw >> (8 * pn)) & 0xffu);
+                f = fo ^ fn ^ (u32)LW.open1((u64)fo, nl);
+            }
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const u32 col = k0 + cg * 8 + s;
+                const int el = s * GT_LANES + lane;
+                const Sh bA = { s_mat[6 + p][el], s_mat[6 + pn][el] };
+                Sh E;
+                E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
+                E.n = ((f >> s) & 1) ? one.n - bA.n : bA.n;
+                if (col < w) {
+                    if (ROWS) {
+                        Sh x = { 0, 0 };
+                        if (valid) x = ld(I, p, i * d + col);
+                        acc += prod3(E, x);
+                    } else {
+                        acc += prod3(E, ld(W1, p, w1off + col));
+                        if (NDOT == 2) acc2 += prod3(E, ld(W2, p, w2off + col));
+                    }
+                }
+            }
+            par ^= 1;
+            __syncthreads();                           // the material in LDS is overwritten next
+        }
+        acc = sum_over_column_groups<LGI>(acc);
+        if (NDOT == 2) acc2 = sum_over_column_groups<LGI>(acc2);
+        const u32 bits = (valid && cg == 0) ? 64u : 0u;   // the lanes of one instance hold the same result: one of them counts
+        if (NDOT == 2) {
+            const u32 st[2] = { 2, 3 }; u64 wo[2], wn[2];
+            prf_tile_it<2, LGI>(K, op, st, tile0, wo, wn);
+            u64 s2[2] = { acc + (wo[0] - wn[0]), acc2 + (wo[1] - wn[1]) }, r2[2];
+            LW.reshare<2>(s2, r2, 2 * bits);
+            z.o = s2[0]; z.n = r2[0]; z2.o = s2[1]; z2.n = r2[1];
+        } else {
+            const u32 st[1] = { 2 }; u64 wo[1], wn[1];
+            prf_tile_it<1, LGI>(K, op, st, tile0, wo, wn);
+            z.o = acc + (wo[0] - wn[0]);
+            z.n = LW.reshare1(z.o, bits);
+        }
+        __syncthreads();                               // message slots and scratch are free again
+    }
+
+    // bit = [x > theta] as an arithmetic sharing (threshold mode)
+    __device__ __forceinline__ Sh greater(u32 op, Sh th, Sh x)
+    {
+        const bool act = valid && cg == 0;
+        const Dealer D = dealer_of(K, p, op, i);
+        const u32 st[2] = { 1, 2 }; u64 wo[2], wn[2];
+        prf_tile_it<2, LGI>(K, op, st, tile0, wo, wn);
+        const Sh b = b2a(LW, p, not_bit(p, ge_bit_masks(LW, p, th - x, D, wo[0] ^ wn[0], wo[1] ^ wn[1], act)), D, act);
+        __syncthreads();
+        return b;
+    }
+};
+
+// OCC: wavefronts per SIMD the register budget is cut for (3: four workgroups per compute
+// unit, for batches that fill the device; 2: no register spills, for small batches whose
+// few workgroups gain nothing from a higher occupancy)
+template <int LGI, int OCC>
+__global__ __launch_bounds__(192, OCC) void k_infer(InferArgs a)
+{
+    __shared__ u64 s_mat[9][GT_TILE_EL];
+    __shared__ u32 s_bitw[2][GT_LANES];
+    __shared__ u64 s_cnt[6];
+    InferWg<LGI> X;
+    constexpr u32 IT = InferWg<LGI>::IT;
+    X.s_mat = s_mat; X.s_bitw = s_bitw;
+    X.p = party_of_wave(); X.lane = threadIdx.x; X.tid = X.p * GT_LANES + X.lane;
+    X.pn = X.p == 2 ? 0 : X.p + 1; X.pp = X.p == 0 ? 2 : X.p - 1;
+    X.LW.init(&s_mat[3][0], s_cnt);
+    X.K = load_party_keys(a.c.keys, X.p, &s_mat[6 + X.p][0]);
+    X.inst = (u32)X.lane & (IT - 1); X.cg = (u32)X.lane >> LGI; X.par = 0; X.N8 = a.N8;
+    if (X.tid < 2 * GT_LANES) (&s_bitw[0][0])[X.tid] = 0;
+    __syncthreads();
+    const u32 S = a.has_thr ? 3 : 2;
+    const u64 ntile = (a.NI + IT - 1) / IT;
+    for (u64 tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        X.tile0 = tile * IT; X.i = X.tile0 + X.inst; X.valid = X.i < a.NI;
+        Sh tidx = { 0, 0 }, zz = { 0, 0 };
+        for (u32 n = 0; n < a.H; n++) {
+            const u64 wn = (u64)1 << n, base = wn - 1;
+            const u32 op = a.c.op + n * S;
+            Sh f, th = { 0, 0 }, x;
+            if (a.has_thr) X.template access<false, 2>(op, tidx, base, (u32)wn, a.feat, base, a.thr, base, a.I, a.d, f, th);
+            else X.template access<false, 1>(op, tidx, base, (u32)wn, a.feat, base, a.feat, base, a.I, a.d, f, zz);
+            X.template access<true, 1>(op + 1, f, 0, a.d, a.feat, 0, a.feat, 0, a.I, a.d, x, zz);
+            if (a.has_thr) x = X.greater(op + 2, th, x);
+            tidx = scale(tidx, 2) + x + pub(X.p, 1);
+        }
+        const u64 nleaf = (u64)1 << a.H;
+        Sh R;
+        X.template access<false, 1>(a.c.op + a.H * S, tidx, nleaf - 1, (u32)nleaf, a.leaf, 0, a.leaf, 0, a.I, a.d, R, zz);
+        if (X.valid && X.cg == 0) st(a.out, X.p, X.i, R);
+        X.LW.drain();
+    }
+    X.LW.flush(a.c.wire);
+}

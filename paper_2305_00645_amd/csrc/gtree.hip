@@ -2,6 +2,7 @@
 // state, the operation schedule of each protocol, message accounting, launches.
 #include "gtree.h"
 #include "gt_kernels.hpp"
+#include "gt_infer.hpp"
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
@@ -41,6 +42,8 @@ struct gt_ctx {
     unsigned resident;        // workgroups of 192 lanes that fit on the device at once
     gt_stats acc;
     bool profile;
+    bool levelwise_infer;     // GT_FLAG_LEVELWISE_INFER
+    int infer_lgi;            // forced log2 of the instances per workgroup of k_infer (0: chosen from the batch size)
     std::vector<hipEvent_t> ev_pool;   // GT_FLAG_PROFILE: a pair of events per launch, resolved when the times are read
     size_t ev_used;
     std::vector<int> ev_cls;
@@ -222,6 +225,9 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     c->op = 0; c->ev_used = 0; c->keys_d = nullptr; c->wire_d = nullptr; c->dacc = nullptr; c->dacc_words = 0; c->resident = 1024;
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     c->profile = (prm->flags & GT_FLAG_PROFILE) != 0;
+    c->levelwise_infer = (prm->flags & GT_FLAG_LEVELWISE_INFER) != 0;
+    c->infer_lgi = 0;
+    if (prm->flags & GT_FLAG_INFER_TILE_MASK) c->infer_lgi = 3 + (int)((prm->flags & GT_FLAG_INFER_TILE_MASK) >> 8);
     c->tau = prm->tau; c->K = prm->K; c->stream = (hipStream_t)prm->hip_stream;
     u32 keys[5][8];
     for (int k = 0; k < 5; k++)
@@ -885,6 +891,35 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
     Timed T(c);
     const size_t N8 = pad8(NI);
     const u32 H = tr->H;
+    if (!c->levelwise_infer) {
+        // one launch: a workgroup carries a tile of instances through all levels.  Smaller tiles
+        // (more lanes per instance, more columns per step) for batches that would otherwise leave
+        // compute units without a workgroup.
+        InferArgs a{}; a.c = kc(c, c->op); a.feat = tr->feat.v; a.thr = tr->has_thr ? tr->thr.v : tr->feat.v; a.leaf = tr->leaf.v;
+        a.I = to_p6(I); a.out = to_p6(R); a.NI = NI; a.N8 = N8; a.d = d; a.H = H; a.has_thr = tr->has_thr ? 1 : 0;
+        const u32 S = tr->has_thr ? 3 : 2;
+        c->op += H * S + 1;
+        int lgi = c->infer_lgi;
+        if (!lgi) lgi = (NI + 63) / 64 >= 2ull * c->resident ? 6 : ((NI + 31) / 32 >= c->resident / 4 ? 5 : 4);
+        const u64 ntile = (NI + ((u64)1 << lgi) - 1) >> lgi;
+        const dim3 g((unsigned)std::min<u64>(ntile, 1u << 20));
+        const bool small = ntile <= 2ull * (c->resident / 4);      // at most two workgroups per compute unit
+        int rc;
+        if (small) rc = lgi == 6 ? launch(c, GT_KC_INFER, k_infer<6, 2>, g, GT_BLOCK, a)
+                      : lgi == 5 ? launch(c, GT_KC_INFER, k_infer<5, 2>, g, GT_BLOCK, a)
+                                 : launch(c, GT_KC_INFER, k_infer<4, 2>, g, GT_BLOCK, a);
+        else rc = lgi == 6 ? launch(c, GT_KC_INFER, k_infer<6, 3>, g, GT_BLOCK, a)
+                : lgi == 5 ? launch(c, GT_KC_INFER, k_infer<5, 3>, g, GT_BLOCK, a)
+                           : launch(c, GT_KC_INFER, k_infer<4, 3>, g, GT_BLOCK, a);
+        for (u32 n = 0; n < H; n++) {
+            const u64 nel = ((u64)1 << n) * NI;
+            acct_eq(c, nel); acct_b2a(c, nel); acct_reshare(c, NI, tr->has_thr ? 2 : 1);
+            acct_eq(c, (u64)d * NI); acct_b2a(c, (u64)d * NI); acct_reshare(c, NI, 1);
+            if (tr->has_thr) { acct_ge(c, NI); acct_b2a(c, NI); }
+        }
+        acct_eq(c, ((u64)1 << H) * NI); acct_b2a(c, ((u64)1 << H) * NI); acct_reshare(c, NI, 1);
+        return T.finish(rc);
+    }
     // workspace: transposed instances, node index, fetched id / threshold / value
     const size_t need[5] = { (size_t)d * N8, NI, NI, tr->has_thr ? NI : 0, tr->has_thr ? NI : 0 };
     int rc = GT_OK;

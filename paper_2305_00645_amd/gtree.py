@@ -38,11 +38,13 @@ class _Stats(C.Structure):
 
 
 GT_FLAG_PROFILE = 1
-KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local", "eqgrid_rows", "eqgrid_store")
+GT_FLAG_LEVELWISE_INFER = 2
+GT_FLAG_INFER_TILE = {16: 0x100, 32: 0x200, 64: 0x300}
+KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local", "eqgrid_rows", "eqgrid_store", "infer")
 
 
 class _Prof(C.Structure):
-    _fields_ = [("ms", C.c_double * 8), ("launches", C.c_uint64 * 8)]
+    _fields_ = [("ms", C.c_double * 9), ("launches", C.c_uint64 * 9)]
 
 
 class _Params(C.Structure):
@@ -157,14 +159,14 @@ def _ref(s):
 class GTree:
     """One protocol context (keys, operation counter, message buffers, stream)."""
 
-    def __init__(self, seed, tau=16, K=2, device="cuda:0", stream=None, profile=False):
+    def __init__(self, seed, tau=16, K=2, device="cuda:0", stream=None, profile=False, flags=0):
         import torch
         self.L = load()
         self.torch = torch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         prm = _Params()
-        prm.tau, prm.K, prm.flags = int(tau), int(K), GT_FLAG_PROFILE if profile else 0
+        prm.tau, prm.K, prm.flags = int(tau), int(K), (GT_FLAG_PROFILE if profile else 0) | int(flags)
         sd = np.asarray(seed, dtype=np.uint64).reshape(5, 4)
         for a in range(5):
             for b in range(4):

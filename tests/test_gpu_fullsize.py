@@ -109,6 +109,27 @@ def test_c5_inference_full_size(seed):
     torch.cuda.empty_cache()
 
 
+def test_c5_inference_levelwise_equals_one_launch(seed):
+    """At full size (10^6 instances, depth 10) the level-by-level path and the one-launch path
+    give the same six planes of R; together with the sampled-row test above this ties both to
+    the oracle."""
+    import torch
+    from paper_2305_00645_amd import gtree, workloads as wl
+    w = wl.c5_infer()
+    NI, d, H = w["NI"], w["d"], w["H"]
+    res = []
+    for flags in (0, gtree.GT_FLAG_LEVELWISE_INFER):
+        g = gtree.GTree(seed, K=4, flags=flags)
+        tree = g.tree_import(g.share_a(w["feat"]), None, g.share_a(w["leaf"]), H)
+        R = g.infer_batch(tree, g.share_a(w["I"].reshape(-1)), NI, d)
+        res.append((R.planes(), g.stats()[0], g.stats()[1], g.wire_bits_dev(), g.op_counter()))
+        tree.close(); g.close()
+        torch.cuda.empty_cache()
+    assert np.array_equal(res[0][0], res[1][0])
+    assert res[0][1] == res[1][1] and np.array_equal(res[0][2], res[1][2]) and np.array_equal(res[0][3], res[1][3])
+    assert res[0][4] == res[1][4]
+
+
 def test_c3_full_training(seed):
     """Census-shaped workload at full size: 48,842 samples x 294 candidate columns, depth 7,
     every exported share of the last level and of the finished tree against the oracle."""

@@ -375,6 +375,36 @@ def test_infer(mods, seed, binary, NI, H):
     same_stats(o, g)
 
 
+@pytest.mark.parametrize("how", ["levelwise", 16, 32, 64])
+@pytest.mark.parametrize("binary,NI,H,d", [(False, 333, 5, 16), (True, 1000, 7, 16), (True, 70, 9, 3), (False, 129, 3, 37), (True, 17, 0, 5)])
+def test_infer_paths_agree(mods, seed, how, binary, NI, H, d):
+    """The level-by-level path and the one-launch path with each of its three tile shapes
+    (16, 32, 64 instances per workgroup; 32, 16, 8 columns per step, so column counts that
+    are not a multiple of the step and instance counts that leave a ragged tile) all give the
+    oracle's shares, rounds, bytes and bits."""
+    import plain_cart
+    Oracle, gtree = mods
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c4_infer(NI=NI, H=H, d=d, binary=binary, seed=4000 + H)
+    flags = gtree.GT_FLAG_LEVELWISE_INFER if how == "levelwise" else gtree.GT_FLAG_INFER_TILE[how]
+    o, g = Oracle(seed), gtree.GTree(seed, flags=flags)
+    fo, lo = o.share(w["feat"]), o.share(w["leaf"])
+    fg, lg = g.share_a(w["feat"]), g.share_a(w["leaf"])
+    to = tg = None
+    if not binary:
+        to, tg = o.share(w["thr"]), g.share_a(w["thr"])
+    Io, Ig = o.share(w["I"].reshape(-1)), g.share_a(w["I"].reshape(-1))
+    tree = g.tree_import(fg, tg, lg, H)
+    Ro = o.infer(fo, to, lo, H, Io, NI, d)
+    Rg = g.infer_batch(tree, Ig, NI, d)
+    same(Rg, Ro, "inference (%s)" % how)
+    T = np.concatenate([w["feat"], w["leaf"]]).astype(np.int64)
+    thr = None if binary else np.concatenate([w["thr"], np.zeros(1 << H, dtype=np.uint64)])
+    assert np.array_equal(g.rec(Rg).astype(np.int64), plain_cart.predict(T, H, w["I"], thr))
+    same_stats(o, g)
+    tree.close(); g.close()
+
+
 def test_infer_depth0(mods, seed):
     o, g = pair(mods, seed)
     lo, lg = o.share(u64([3])), g.share_a(u64([3]))
