@@ -195,6 +195,18 @@ int gt_tree_destroy(gt_tree *tree);
 int gt_infer_batch(gt_ctx *ctx, const gt_tree *tree, const gt_shares *I, size_t N_I,
                    uint32_t d, const gt_shares *R_out);
 
+/* ---- forests (Sec. VI, inference results: for deep trees a random forest of shallow
+ * trees may serve better).  ntrees trees of the same depth and mode are evaluated on the
+ * same batch in ONE launch: R[t*N_I + i] = label of instance i by tree t.  Shares, operation
+ * ids, rounds and bytes are those of gt_infer_batch called for tree 0, 1, ... in this
+ * order.  gt_forest_create copies the trees' shares (the trees may be destroyed afterwards);
+ * how the per-tree labels are combined (vote) is left to the caller. */
+typedef struct gt_forest gt_forest;
+int gt_forest_create(gt_ctx *ctx, const gt_tree *const *trees, size_t ntrees, gt_forest **out);
+int gt_forest_destroy(gt_forest *forest);
+int gt_infer_forest(gt_ctx *ctx, const gt_forest *forest, const gt_shares *I, size_t N_I,
+                    uint32_t d, const gt_shares *R_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -194,6 +194,7 @@ __device__ __forceinline__ int party_of_wave() { return __builtin_amdgcn_readfir
 // message suffices (a slot is rewritten only after the barrier of the message that
 // followed it); a message of more than four words takes the whole region and is
 // followed by a second barrier, after which the region may be written again.
+#define GT_WIRE_SLOTS 64
 #define GT_LWIRE_SLOT (3 * 4 * GT_LANES)
 #define GT_LWIRE_WORDS (2 * GT_LWIRE_SLOT)
 // Every send states how many payload bits the lane's message carries (0 for a lane whose
@@ -243,8 +244,10 @@ struct LWire {
         if (nresh) atomicAdd((unsigned long long *)&cnt[2 * p + 1], (unsigned long long)nresh);
         nopen = 0; nresh = 0;
     }
-    // end of the kernel: add the party's sums to g[2p] (bits sent to the successor) and
-    // g[2p+1] (to the predecessor); every lane calls it once
+    // end of the kernel: add the party's sums to the context's counters, g[6*slot + 2p] (bits
+    // sent to the successor) and g[6*slot + 2p+1] (to the predecessor); the workgroups of a
+    // launch spread over GT_WIRE_SLOTS slots so that their atomic adds do not queue up on one
+    // address (the host adds the slots up).  Every lane calls it once.
     __device__ __forceinline__ void flush(u64 *g)
     {
         drain();
@@ -252,7 +255,8 @@ struct LWire {
         __builtin_amdgcn_wave_barrier();
         if (lane < 2) {
             const u64 v = cnt[2 * p + lane];
-            if (v) atomicAdd((unsigned long long *)&g[2 * p + lane], (unsigned long long)v);
+            const u32 slot = (blockIdx.x + blockIdx.y) & (GT_WIRE_SLOTS - 1);
+            if (v) atomicAdd((unsigned long long *)&g[6 * slot + 2 * p + lane], (unsigned long long)v);
         }
     }
 };

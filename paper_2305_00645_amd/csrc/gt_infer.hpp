@@ -11,11 +11,11 @@
 
 struct InferArgs {
     KCommon c;                 // c.op: first operation id of the batch
-    P6 feat, thr, leaf;        // 2^H-1 ids, 2^H-1 thresholds (has_thr), 2^H labels
-    P6 I, out;                 // NI x d row-major instances, NI results
+    P6 feat, thr, leaf;        // per tree 2^H-1 ids, 2^H-1 thresholds (has_thr), 2^H labels, tree after tree
+    P6 I, out;                 // NI x d row-major instances; results out[t*NI + i]
     u64 NI, N8;
-    u32 d, H;
-    int has_thr;
+    u32 d, H, ntrees;          // ntrees > 1: a forest; tree t takes the operation ids that the t-th of
+    int has_thr;               // ntrees single-tree batches in a row would take
 };
 
 // Words of NS streams under the own and the next key for the tile's IT consecutive
@@ -243,24 +243,25 @@ __global__ __launch_bounds__(192, OCC) void k_infer(InferArgs a)
     if (X.tid < 2 * GT_LANES) (&s_bitw[0][0])[X.tid] = 0;
     __syncthreads();
     const u32 S = a.has_thr ? 3 : 2;
-    const u64 ntile = (a.NI + IT - 1) / IT;
-    for (u64 tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+    const u64 ntile = (a.NI + IT - 1) / IT, nleaf = (u64)1 << a.H, nint = nleaf - 1;
+    for (u64 item = blockIdx.x; item < ntile * a.ntrees; item += gridDim.x) {
+        const u64 tree = item / ntile, tile = item % ntile;
+        const u32 op0 = a.c.op + (u32)tree * (a.H * S + 1);
         X.tile0 = tile * IT; X.i = X.tile0 + X.inst; X.valid = X.i < a.NI;
         Sh tidx = { 0, 0 }, zz = { 0, 0 };
         for (u32 n = 0; n < a.H; n++) {
-            const u64 wn = (u64)1 << n, base = wn - 1;
-            const u32 op = a.c.op + n * S;
+            const u64 wn = (u64)1 << n, base = wn - 1, off = tree * nint + base;
+            const u32 op = op0 + n * S;
             Sh f, th = { 0, 0 }, x;
-            if (a.has_thr) X.template access<false, 2>(op, tidx, base, (u32)wn, a.feat, base, a.thr, base, a.I, a.d, f, th);
-            else X.template access<false, 1>(op, tidx, base, (u32)wn, a.feat, base, a.feat, base, a.I, a.d, f, zz);
+            if (a.has_thr) X.template access<false, 2>(op, tidx, base, (u32)wn, a.feat, off, a.thr, off, a.I, a.d, f, th);
+            else X.template access<false, 1>(op, tidx, base, (u32)wn, a.feat, off, a.feat, off, a.I, a.d, f, zz);
             X.template access<true, 1>(op + 1, f, 0, a.d, a.feat, 0, a.feat, 0, a.I, a.d, x, zz);
             if (a.has_thr) x = X.greater(op + 2, th, x);
             tidx = scale(tidx, 2) + x + pub(X.p, 1);
         }
-        const u64 nleaf = (u64)1 << a.H;
         Sh R;
-        X.template access<false, 1>(a.c.op + a.H * S, tidx, nleaf - 1, (u32)nleaf, a.leaf, 0, a.leaf, 0, a.I, a.d, R, zz);
-        if (X.valid && X.cg == 0) st(a.out, X.p, X.i, R);
+        X.template access<false, 1>(op0 + a.H * S, tidx, nint, (u32)nleaf, a.leaf, tree * nleaf, a.leaf, 0, a.I, a.d, R, zz);
+        if (X.valid && X.cg == 0) st(a.out, X.p, tree * a.NI + X.i, R);
         X.LW.drain();
     }
     X.LW.flush(a.c.wire);

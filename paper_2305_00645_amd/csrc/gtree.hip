@@ -38,7 +38,7 @@ struct gt_ctx {
     u32 op;
     hipStream_t stream;
     u32 *keys_d;
-    u64 *wire_d;              // six counters filled by the kernels: payload bits party p sent to p+1 [2p], to p-1 [2p+1]
+    u64 *wire_d;              // GT_WIRE_SLOTS x six counters filled by the kernels: payload bits party p sent to p+1 [2p], to p-1 [2p+1]
     unsigned resident;        // workgroups of 192 lanes that fit on the device at once
     gt_stats acc;
     bool profile;
@@ -66,6 +66,12 @@ struct gt_tree {
     bool has_thr;
     DSh feat, thr, leaf;
     TreeSlot *slot;           // non-null: feat and leaf are the slot's buffers
+};
+
+struct gt_forest {             // trees of one depth and mode, their shares tree after tree
+    u32 H, ntrees;
+    bool has_thr;
+    DSh feat, thr, leaf;
 };
 
 struct gt_train {
@@ -243,9 +249,9 @@ extern "C" int gt_ctx_create(gt_ctx **out, const gt_params *prm)
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
         c->resident = std::min<unsigned>(GT_MAX_BLOCKS, 4u * (unsigned)cus);
     if (hipMalloc(&c->keys_d, sizeof keys) != hipSuccess) { delete c; return GT_ENOMEM; }
-    if (hipMalloc(&c->wire_d, 8 * sizeof(u64)) != hipSuccess) { (void)hipFree(c->keys_d); delete c; return GT_ENOMEM; }
+    if (hipMalloc(&c->wire_d, 6 * GT_WIRE_SLOTS * sizeof(u64)) != hipSuccess) { (void)hipFree(c->keys_d); delete c; return GT_ENOMEM; }
     if (hipMemcpy(c->keys_d, keys, sizeof keys, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemset(c->wire_d, 0, 8 * sizeof(u64)) != hipSuccess) {
+        hipMemset(c->wire_d, 0, 6 * GT_WIRE_SLOTS * sizeof(u64)) != hipSuccess) {
         (void)hipFree(c->keys_d); (void)hipFree(c->wire_d); delete c; return GT_EHIP;
     }
     *out = c;
@@ -271,10 +277,14 @@ extern "C" int gt_stats_get(gt_ctx *c, gt_stats *out)
     if (!c || !out) return GT_EINVAL;
     HIPCHK(hipStreamSynchronize(c->stream));
     GTCHK(resolve_events(c));
-    u64 bits[6];
+    u64 bits[6 * GT_WIRE_SLOTS];
     HIPCHK(hipMemcpy(bits, c->wire_d, sizeof bits, hipMemcpyDeviceToHost));
     memset(c->acc.wire_bits_dev, 0, sizeof c->acc.wire_bits_dev);
-    for (int p = 0; p < 3; p++) { c->acc.wire_bits_dev[p][(p + 1) % 3] = bits[2 * p]; c->acc.wire_bits_dev[p][(p + 2) % 3] = bits[2 * p + 1]; }
+    for (int sl = 0; sl < GT_WIRE_SLOTS; sl++)
+        for (int p = 0; p < 3; p++) {
+            c->acc.wire_bits_dev[p][(p + 1) % 3] += bits[6 * sl + 2 * p];
+            c->acc.wire_bits_dev[p][(p + 2) % 3] += bits[6 * sl + 2 * p + 1];
+        }
     *out = c->acc;
     return GT_OK;
 }
@@ -282,7 +292,7 @@ extern "C" int gt_stats_reset(gt_ctx *c)
 {
     if (!c) return GT_EINVAL;
     GTCHK(resolve_events(c));
-    HIPCHK(hipMemsetAsync(c->wire_d, 0, 8 * sizeof(u64), c->stream));
+    HIPCHK(hipMemsetAsync(c->wire_d, 0, 6 * GT_WIRE_SLOTS * sizeof(u64), c->stream));
     memset(&c->acc, 0, sizeof c->acc); memset(&c->prof, 0, sizeof c->prof);
     return GT_OK;
 }
@@ -884,6 +894,43 @@ extern "C" int gt_tree_destroy(gt_tree *tr)
     return GT_OK;
 }
 
+// One launch for the whole batch (and for every tree of a forest): a workgroup carries a
+// tile of instances through all levels of one tree.  Smaller tiles (more lanes per instance,
+// more columns per step) for batches that would otherwise leave compute units without a
+// workgroup.
+static int infer_one_launch(gt_ctx *c, P6 feat, P6 thr, P6 leaf, bool has_thr, u32 H, u32 ntrees,
+                            const gt_shares *I, size_t NI, uint32_t d, const gt_shares *R)
+{
+    const size_t N8 = pad8(NI);
+    InferArgs a{}; a.c = kc(c, c->op); a.feat = feat; a.thr = thr; a.leaf = leaf;
+    a.I = to_p6(I); a.out = to_p6(R); a.NI = NI; a.N8 = N8; a.d = d; a.H = H; a.ntrees = ntrees; a.has_thr = has_thr ? 1 : 0;
+    const u32 S = has_thr ? 3 : 2;
+    c->op += ntrees * (H * S + 1);
+    int lgi = c->infer_lgi;
+    const u64 per64 = (NI + 63) / 64 * ntrees, per32 = (NI + 31) / 32 * ntrees;
+    if (!lgi) lgi = per64 >= 2ull * c->resident ? 6 : (per32 >= c->resident / 4 ? 5 : 4);
+    const u64 nitem = ((NI + ((u64)1 << lgi) - 1) >> lgi) * ntrees;
+    const dim3 g((unsigned)std::min<u64>(nitem, 1u << 20));
+    const bool small = nitem <= 2ull * (c->resident / 4);      // at most two workgroups per compute unit
+    int rc;
+    if (small) rc = lgi == 6 ? launch(c, GT_KC_INFER, k_infer<6, 2>, g, GT_BLOCK, a)
+                  : lgi == 5 ? launch(c, GT_KC_INFER, k_infer<5, 2>, g, GT_BLOCK, a)
+                             : launch(c, GT_KC_INFER, k_infer<4, 2>, g, GT_BLOCK, a);
+    else rc = lgi == 6 ? launch(c, GT_KC_INFER, k_infer<6, 3>, g, GT_BLOCK, a)
+            : lgi == 5 ? launch(c, GT_KC_INFER, k_infer<5, 3>, g, GT_BLOCK, a)
+                       : launch(c, GT_KC_INFER, k_infer<4, 3>, g, GT_BLOCK, a);
+    for (u32 t = 0; t < ntrees; t++) {
+        for (u32 n = 0; n < H; n++) {
+            const u64 nel = ((u64)1 << n) * NI;
+            acct_eq(c, nel); acct_b2a(c, nel); acct_reshare(c, NI, has_thr ? 2 : 1);
+            acct_eq(c, (u64)d * NI); acct_b2a(c, (u64)d * NI); acct_reshare(c, NI, 1);
+            if (has_thr) { acct_ge(c, NI); acct_b2a(c, NI); }
+        }
+        acct_eq(c, ((u64)1 << H) * NI); acct_b2a(c, ((u64)1 << H) * NI); acct_reshare(c, NI, 1);
+    }
+    return rc;
+}
+
 extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, size_t NI, uint32_t d, const gt_shares *R)
 {
     if (!c || !tr || NI == 0 || d == 0 || d > 65536) return GT_EINVAL;
@@ -891,35 +938,8 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
     Timed T(c);
     const size_t N8 = pad8(NI);
     const u32 H = tr->H;
-    if (!c->levelwise_infer) {
-        // one launch: a workgroup carries a tile of instances through all levels.  Smaller tiles
-        // (more lanes per instance, more columns per step) for batches that would otherwise leave
-        // compute units without a workgroup.
-        InferArgs a{}; a.c = kc(c, c->op); a.feat = tr->feat.v; a.thr = tr->has_thr ? tr->thr.v : tr->feat.v; a.leaf = tr->leaf.v;
-        a.I = to_p6(I); a.out = to_p6(R); a.NI = NI; a.N8 = N8; a.d = d; a.H = H; a.has_thr = tr->has_thr ? 1 : 0;
-        const u32 S = tr->has_thr ? 3 : 2;
-        c->op += H * S + 1;
-        int lgi = c->infer_lgi;
-        if (!lgi) lgi = (NI + 63) / 64 >= 2ull * c->resident ? 6 : ((NI + 31) / 32 >= c->resident / 4 ? 5 : 4);
-        const u64 ntile = (NI + ((u64)1 << lgi) - 1) >> lgi;
-        const dim3 g((unsigned)std::min<u64>(ntile, 1u << 20));
-        const bool small = ntile <= 2ull * (c->resident / 4);      // at most two workgroups per compute unit
-        int rc;
-        if (small) rc = lgi == 6 ? launch(c, GT_KC_INFER, k_infer<6, 2>, g, GT_BLOCK, a)
-                      : lgi == 5 ? launch(c, GT_KC_INFER, k_infer<5, 2>, g, GT_BLOCK, a)
-                                 : launch(c, GT_KC_INFER, k_infer<4, 2>, g, GT_BLOCK, a);
-        else rc = lgi == 6 ? launch(c, GT_KC_INFER, k_infer<6, 3>, g, GT_BLOCK, a)
-                : lgi == 5 ? launch(c, GT_KC_INFER, k_infer<5, 3>, g, GT_BLOCK, a)
-                           : launch(c, GT_KC_INFER, k_infer<4, 3>, g, GT_BLOCK, a);
-        for (u32 n = 0; n < H; n++) {
-            const u64 nel = ((u64)1 << n) * NI;
-            acct_eq(c, nel); acct_b2a(c, nel); acct_reshare(c, NI, tr->has_thr ? 2 : 1);
-            acct_eq(c, (u64)d * NI); acct_b2a(c, (u64)d * NI); acct_reshare(c, NI, 1);
-            if (tr->has_thr) { acct_ge(c, NI); acct_b2a(c, NI); }
-        }
-        acct_eq(c, ((u64)1 << H) * NI); acct_b2a(c, ((u64)1 << H) * NI); acct_reshare(c, NI, 1);
-        return T.finish(rc);
-    }
+    if (!c->levelwise_infer)
+        return T.finish(infer_one_launch(c, tr->feat.v, tr->has_thr ? tr->thr.v : tr->feat.v, tr->leaf.v, tr->has_thr, H, 1, I, NI, d, R));
     // workspace: transposed instances, node index, fetched id / threshold / value
     const size_t need[5] = { (size_t)d * N8, NI, NI, tr->has_thr ? NI : 0, tr->has_thr ? NI : 0 };
     int rc = GT_OK;
@@ -952,4 +972,46 @@ extern "C" int gt_infer_batch(gt_ctx *c, const gt_tree *tr, const gt_shares *I, 
         rc = do_grid(c, GM_COMMON, false, 1, a);
     }
     return T.finish(rc);
+}
+
+// ---- forests: many trees of one depth on the same batch, one launch -----------------------
+extern "C" int gt_forest_create(gt_ctx *c, const gt_tree *const *trees, size_t ntrees, gt_forest **out)
+{
+    if (!c || !trees || !out || ntrees == 0 || ntrees > 65536) return GT_EINVAL;
+    for (size_t t = 0; t < ntrees; t++)
+        if (!trees[t] || trees[t]->H != trees[0]->H || trees[t]->has_thr != trees[0]->has_thr) return GT_EINVAL;
+    Timed T(c);
+    gt_forest *f = new (std::nothrow) gt_forest();
+    if (!f) return GT_ENOMEM;
+    f->H = trees[0]->H; f->ntrees = (u32)ntrees; f->has_thr = trees[0]->has_thr;
+    const size_t nint = ((size_t)1 << f->H) - 1, nleaf = (size_t)1 << f->H;
+    int rc = dsh_alloc(f->feat, ntrees * nint, c->stream);
+    if (rc == GT_OK) rc = dsh_alloc(f->leaf, ntrees * nleaf, c->stream);
+    if (rc == GT_OK && f->has_thr) rc = dsh_alloc(f->thr, ntrees * nint, c->stream);
+    for (size_t t = 0; t < ntrees && rc == GT_OK; t++) {
+        rc = copy6(c, f->feat.v, t * nint, trees[t]->feat.v, 0, 1, nint);
+        if (rc == GT_OK) rc = copy6(c, f->leaf.v, t * nleaf, trees[t]->leaf.v, 0, 1, nleaf);
+        if (rc == GT_OK && f->has_thr) rc = copy6(c, f->thr.v, t * nint, trees[t]->thr.v, 0, 1, nint);
+    }
+    rc = T.finish(rc);
+    if (rc != GT_OK) { (void)hipStreamSynchronize(c->stream); dsh_free(f->feat); dsh_free(f->leaf); dsh_free(f->thr); delete f; return rc; }
+    *out = f;
+    return GT_OK;
+}
+
+extern "C" int gt_forest_destroy(gt_forest *f)
+{
+    if (!f) return GT_EINVAL;
+    (void)hipDeviceSynchronize();
+    dsh_free(f->feat); dsh_free(f->thr); dsh_free(f->leaf);
+    delete f;
+    return GT_OK;
+}
+
+extern "C" int gt_infer_forest(gt_ctx *c, const gt_forest *f, const gt_shares *I, size_t NI, uint32_t d, const gt_shares *R)
+{
+    if (!c || !f || NI == 0 || d == 0 || d > 65536) return GT_EINVAL;
+    if (!shares_ok(I, NI * d) || !shares_ok(R, NI * f->ntrees)) return GT_EINVAL;
+    Timed T(c);
+    return T.finish(infer_one_launch(c, f->feat.v, f->has_thr ? f->thr.v : f->feat.v, f->leaf.v, f->has_thr, f->H, f->ntrees, I, NI, d, R));
 }

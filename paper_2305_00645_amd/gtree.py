@@ -100,6 +100,9 @@ def load():
         "gt_tree_export": (i, [vp, vp, S, S]),
         "gt_tree_destroy": (i, [vp]),
         "gt_infer_batch": (i, [vp, vp, S, sz, u32, S]),
+        "gt_forest_create": (i, [vp, C.POINTER(vp), sz, C.POINTER(vp)]),
+        "gt_forest_destroy": (i, [vp]),
+        "gt_infer_forest": (i, [vp, vp, S, sz, u32, S]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -317,6 +320,35 @@ class GTree:
         R = self.new(NI)
         _chk(self.L.gt_infer_batch(self.ctx, tree.h, _ref(I), NI, d, _ref(R)), "gt_infer_batch")
         return R
+
+
+    def forest_create(self, trees):
+        arr = (C.c_void_p * len(trees))(*[t.h for t in trees])
+        h = C.c_void_p()
+        _chk(self.L.gt_forest_create(self.ctx, arr, len(trees), C.byref(h)), "gt_forest_create")
+        return Forest(self, h, len(trees))
+
+    def infer_forest(self, forest, I, NI, d):
+        """Shares of the labels, tree after tree: R[t*NI + i]."""
+        R = self.new(NI * forest.ntrees)
+        _chk(self.L.gt_infer_forest(self.ctx, forest.h, _ref(I), NI, d, _ref(R)), "gt_infer_forest")
+        return R
+
+
+class Forest:
+    def __init__(self, g, h, ntrees):
+        self.g, self.h, self.ntrees = g, h, ntrees
+
+    def close(self):
+        if self.h:
+            self.g.L.gt_forest_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Tree:

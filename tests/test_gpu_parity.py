@@ -405,6 +405,40 @@ def test_infer_paths_agree(mods, seed, how, binary, NI, H, d):
     tree.close(); g.close()
 
 
+@pytest.mark.parametrize("binary,ntrees,NI,H,d", [(True, 7, 150, 3, 9), (False, 3, 77, 4, 16), (True, 40, 1000, 2, 5)])
+def test_forest_in_one_launch(mods, seed, binary, ntrees, NI, H, d):
+    """Many shallow trees on one batch in one launch: shares, operation ids, rounds, bytes
+    and bits are those of the oracle's single-tree inference called tree after tree."""
+    import plain_cart
+    Oracle, gtree = mods
+    from paper_2305_00645_amd import workloads as wl
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(500 + ntrees)
+    I = rng.integers(0, 1 << 16, size=(NI, d)).astype(np.uint64)
+    if binary:
+        I &= np.uint64(1)
+    Io, Ig = o.share(I.reshape(-1)), g.share_a(I.reshape(-1))
+    plain = [wl.random_tree(H, d, rng, thresholds=not binary) for _ in range(ntrees)]
+    so = [(o.share(f), None if t is None else o.share(t), o.share(l)) for f, t, l in plain]
+    trees = []
+    for f, t, l in plain:
+        trees.append(g.tree_import(g.share_a(f), None if t is None else g.share_a(t), g.share_a(l), H))
+    assert o.op_counter() == g.op_counter()
+    forest = g.forest_create(trees)
+    for tr in trees:
+        tr.close()                               # the forest holds copies
+    Rg = g.infer_forest(forest, Ig, NI, d).components()
+    for t, (f, th, l) in enumerate(plain):
+        Ro = o.infer(so[t][0], so[t][1], so[t][2], H, Io, NI, d)
+        assert np.array_equal(Rg[:, t * NI:(t + 1) * NI], Ro), t
+        T = np.concatenate([f, l]).astype(np.int64)
+        thr = None if binary else np.concatenate([th, np.zeros(1 << H, dtype=np.uint64)])
+        got = (Rg[0, t * NI:(t + 1) * NI] + Rg[1, t * NI:(t + 1) * NI] + Rg[2, t * NI:(t + 1) * NI]).astype(np.int64)
+        assert np.array_equal(got, plain_cart.predict(T, H, I, thr))
+    same_stats(o, g)
+    forest.close(); g.close()
+
+
 def test_infer_depth0(mods, seed):
     o, g = pair(mods, seed)
     lo, lg = o.share(u64([3])), g.share_a(u64([3]))
