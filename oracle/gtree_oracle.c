@@ -30,6 +30,7 @@ struct orc_ctx {
     u64 rounds;
     u64 wire[3][3];  /* bytes sent from party a to party b */
     u64 bits[3][3];  /* the same messages in payload bits, n*bits per message with no rounding */
+    u64 scorer[2];   /* heuristic by reconstruction: bytes the three parties send to the scorer, and get back */
 };
 
 /* ------------------------------------------------------------------------- */
@@ -338,7 +339,12 @@ void orc_stats_bits(const orc_ctx *c, uint64_t wire_bits[9])
 {
     for (int a = 0; a < 3; a++) for (int b = 0; b < 3; b++) wire_bits[3 * a + b] = c->bits[a][b];
 }
-void orc_stats_reset(orc_ctx *c) { c->rounds = 0; memset(c->wire, 0, sizeof c->wire); memset(c->bits, 0, sizeof c->bits); }
+void orc_stats_scorer(const orc_ctx *c, uint64_t bytes[2]) { bytes[0] = c->scorer[0]; bytes[1] = c->scorer[1]; }
+void orc_stats_reset(orc_ctx *c)
+{
+    c->rounds = 0; memset(c->wire, 0, sizeof c->wire); memset(c->bits, 0, sizeof c->bits);
+    memset(c->scorer, 0, sizeof c->scorer);
+}
 uint32_t orc_op_counter(const orc_ctx *c) { return c->op; }
 void orc_set_threads(int n)
 {
@@ -641,6 +647,7 @@ struct orc_train {
     sh Clast, Glast, Slast;/* copies kept for export */
     u32 last;              /* level the copies belong to */
     int fresh_import;      /* state was imported and no level has run since: the copies are not valid */
+    int hc_open;           /* heuristic computation by reconstruction instead of the MPC protocol */
 };
 
 static size_t nodes_upto(u32 H) { return ((size_t)2 << H) - 1; }
@@ -852,7 +859,7 @@ static void heuristic(orc_ctx *c, orc_train *t, u32 h)
  * becomes internal and its children start as leaves with empty statistics; in
  * every other case the children are dummies that inherit the statistics; gamma is
  * always inherited; T at this level takes the split decisions. */
-static void update(orc_ctx *c, orc_train *t, u32 h)
+static void update_flags(orc_ctx *c, orc_train *t, u32 h)
 {
     size_t nh = (size_t)1 << h, base = nh - 1, d = t->d, K = t->K, dK = d * K, CW = t->CW;
     u32 op = c->op++;
@@ -907,6 +914,14 @@ static void update(orc_ctx *c, orc_train *t, u32 h)
         sh_set(&t->F, 2 * (base + r) + 2, z);
     }
     wire_reshare(c, nh, 1); wire_eq(c, nh); wire_and1(c, nh); wire_b2a(c, nh); wire_reshare(c, nh, 1);
+}
+
+/* Node split (Sec. V-B): T takes the split decisions; the children of a node that was split
+ * start with empty statistics, all others inherit them; gamma is always inherited. */
+static void node_split(orc_ctx *c, orc_train *t, u32 h)
+{
+    size_t nh = (size_t)1 << h, base = nh - 1, d = t->d, CW = t->CW;
+    u32 op;
     /* keep this level's statistics and flags for export, then build level h+1 */
     for (int j = 0; j < 3; j++) {
         memcpy(t->Clast.c[j], t->C.c[j], nh * CW * 8);
@@ -941,14 +956,90 @@ static void update(orc_ctx *c, orc_train *t, u32 h)
     sh_free(&Cn);
 }
 
+/* Heuristic computation by reconstruction: the host analogue of the TEE-based protocol of
+ * Sec. V-B.  The parties hand the shares of the level's C, gamma and F to a scorer (the
+ * enclave of the paper; here a fourth role with the dealer's key), which reconstructs them,
+ * computes in the clear what the MPC protocol computes - the fixed-point scores
+ * sum_j floor(S_j 2^tau / Q_j) with an empty branch counting 0, masked by gamma, the first
+ * maximum, the updated gamma, the purity test n^2 = sum_c tot_c^2 and the node types - and
+ * hands back fresh sharings of SD, gamma, F (node and children), the split flags and the
+ * masked scores, one operation id each in this order: x1, x2 = words e of streams 0 and 1
+ * under the dealer's key, x3 = x - x1 - x2.  Two rounds; the bytes to and from the scorer
+ * are counted apart from the messages between the parties. */
+static void share_from_scorer(orc_ctx *c, const u64 *plain, size_t n, sh *out, size_t off)
+{
+    u32 op = c->op++;
+    for (size_t e = 0; e < n; e++) {
+        u64 x1 = prf(c, KEY_DEALER, op, 0, e), x2 = prf(c, KEY_DEALER, op, 1, e);
+        out->c[0][off + e] = x1; out->c[1][off + e] = x2; out->c[2][off + e] = plain[e] - x1 - x2;
+    }
+    c->scorer[1] += 3 * 2 * 8 * (u64)n;            /* every party receives its two components */
+}
+
+static void heuristic_open(orc_ctx *c, orc_train *t, u32 h)
+{
+    size_t nh = (size_t)1 << h, base = nh - 1, d = t->d, K = t->K, dK = d * K, CW = t->CW;
+    u64 *SDp = (u64 *)calloc(nh, 8), *Gp = (u64 *)calloc(nh * d, 8), *Fn = (u64 *)calloc(nh, 8),
+        *Fc = (u64 *)calloc(nh, 8), *Sp = (u64 *)calloc(nh, 8), *SCp = (u64 *)calloc(nh * d, 8);
+    c->scorer[0] += 3 * 8 * (u64)(nh * (CW + d + 1)); /* every party sends its first component of C, gamma, F */
+    c->rounds += 1;
+    for (size_t r = 0; r < nh; r++) {
+        u64 tot[64], n = 0, sq = 0, best = 0, bi = 0;
+        for (size_t cl = 0; cl < K; cl++) {
+            tot[cl] = t->C.c[0][r * CW + dK + cl] + t->C.c[1][r * CW + dK + cl] + t->C.c[2][r * CW + dK + cl];
+            n += tot[cl]; sq += tot[cl] * tot[cl];
+        }
+        for (size_t k = 0; k < d; k++) {
+            u64 score = 0;
+            for (int br = 0; br < 2; br++) {
+                u64 nj = 0, S = 0;
+                for (size_t cl = 0; cl < K; cl++) {
+                    size_t e = r * CW + k * K + cl;
+                    u64 n1 = t->C.c[0][e] + t->C.c[1][e] + t->C.c[2][e];
+                    u64 njc = br ? n1 : tot[cl] - n1;
+                    nj += njc; S += njc * njc;
+                }
+                u64 Q = nj * n;
+                if (Q == 0) Q = 1;                 /* empty branch: the term is 0 */
+                score += (S << c->tau) / Q;        /* S <= Q < 2^40, tau <= 20: no overflow */
+            }
+            u64 g = t->gamma.c[0][r * d + k] + t->gamma.c[1][r * d + k] + t->gamma.c[2][r * d + k];
+            score *= g;
+            SCp[r * d + k] = score; Gp[r * d + k] = g;
+            if (score > best) { best = score; bi = k; }     /* first maximum: the lowest index wins ties */
+        }
+        SDp[r] = bi;
+        Gp[r * d + bi] = 0;
+        u64 F = t->F.c[0][base + r] + t->F.c[1][base + r] + t->F.c[2][base + r];
+        u64 split = (F == 1 && n * n - sq != 0) ? 1 : 0;
+        Sp[r] = split; Fn[r] = F * (1 - split); Fc[r] = 2 - split;
+    }
+    share_from_scorer(c, SDp, nh, &t->SD, 0);
+    share_from_scorer(c, Gp, nh * d, &t->gamma, 0);
+    share_from_scorer(c, Fn, nh, &t->F, base);
+    {   /* both children of node r get the same sharing */
+        sh tmp = sh_alloc(nh);
+        share_from_scorer(c, Fc, nh, &tmp, 0);
+        for (size_t r = 0; r < nh; r++) { u64 x[3]; sh_get(&tmp, r, x); sh_set(&t->F, 2 * (base + r) + 1, x); sh_set(&t->F, 2 * (base + r) + 2, x); }
+        sh_free(&tmp);
+    }
+    share_from_scorer(c, Sp, nh, &t->split, 0);
+    share_from_scorer(c, SCp, nh * d, &t->Slast, 0);
+    c->rounds += 1;
+    free(SDp); free(Gp); free(Fn); free(Fc); free(Sp); free(SCp);
+}
+
+void orc_train_set_heuristic(orc_train *t, int by_reconstruction) { t->hc_open = by_reconstruction ? 1 : 0; }
+
 int orc_train_level(orc_ctx *c, orc_train *t, uint32_t h)
 {
     if (h != t->level || h >= t->H) return -1;
     if (h > 0) partition(c, t, h);
     leaf_onehot(c, t, h);
     count(c, t, h, 0);
-    heuristic(c, t, h);
-    update(c, t, h);
+    if (t->hc_open) heuristic_open(c, t, h);
+    else { heuristic(c, t, h); update_flags(c, t, h); }
+    node_split(c, t, h);
     t->level = h + 1;
     t->fresh_import = 0;
     return 0;

@@ -57,6 +57,8 @@ void orc_ctx_destroy(orc_ctx *);
 void orc_stats(const orc_ctx *, uint64_t *rounds, uint64_t wire_bytes[9]);
 /* payload bits of the same messages, n*bits per message without rounding up to bytes */
 void orc_stats_bits(const orc_ctx *c, uint64_t wire_bits[9]);
+/* heuristic by reconstruction: bytes the parties sent to the scorer [0] and got back [1] */
+void orc_stats_scorer(const orc_ctx *c, uint64_t bytes[2]);
 void orc_stats_reset(orc_ctx *);
 uint32_t orc_op_counter(const orc_ctx *);
 void orc_set_threads(int n); /* OpenMP threads for the element loops; 0 = default */
@@ -97,6 +99,10 @@ orc_train *orc_train_create(orc_ctx *, const uint64_t *X /*N x d comps*/,
                             const uint64_t *Y /*N x K comps*/, size_t N, uint32_t d,
                             uint32_t H);
 void orc_train_destroy(orc_train *);
+/* Heuristic computation of the following levels by reconstruction (host analogue of the
+ * TEE-based protocol of Sec. V-B: a scorer reconstructs C, gamma, F, scores in the clear with
+ * the same fixed-point rule and hands back fresh sharings) instead of the MPC protocol. */
+void orc_train_set_heuristic(orc_train *t, int by_reconstruction);
 int orc_train_level(orc_ctx *, orc_train *, uint32_t h);
 /* level H: partition, class totals, labels. feat: 2^H-1 comps, leaf: 2^H comps */
 int orc_train_finish(orc_ctx *, orc_train *, uint64_t *feat, uint64_t *leaf);

@@ -49,6 +49,8 @@ def _load():
         "orc_ctx_destroy": (None, [vp]),
         "orc_stats": (None, [vp, _u64p, _u64p]),
         "orc_stats_bits": (None, [vp, _u64p]),
+        "orc_stats_scorer": (None, [vp, _u64p]),
+        "orc_train_set_heuristic": (None, [vp, i]),
         "orc_stats_reset": (None, [vp]),
         "orc_op_counter": (u32, [vp]),
         "orc_set_threads": (None, [i]),
@@ -145,6 +147,11 @@ class Oracle:
         w = np.zeros(9, dtype=np.uint64)
         self.L.orc_stats_bits(self.ctx, _p(w))
         return w.reshape(3, 3).copy()
+
+    def scorer_bytes(self):
+        w = np.zeros(2, dtype=np.uint64)
+        self.L.orc_stats_scorer(self.ctx, _p(w))
+        return int(w[0]), int(w[1])
 
     def stats_reset(self):
         self.L.orc_stats_reset(self.ctx)
@@ -244,6 +251,9 @@ class Oracle:
             self.L.orc_train_destroy(self._train)
         self._train = self.L.orc_train_create(self.ctx, _p(X.reshape(-1)), _p(Y.reshape(-1)), N, d, H)
         self._tshape = (N, d, H)
+
+    def train_set_heuristic(self, by_reconstruction):
+        self.L.orc_train_set_heuristic(self._train, int(bool(by_reconstruction)))
 
     def train_level(self, h):
         rc = self.L.orc_train_level(self.ctx, self._train, h)

@@ -11,12 +11,13 @@ from paper_2305_00645_amd import workloads as wl
 M64 = (1 << 64) - 1
 
 
-def run_oracle_train(seed, w, tau=16, H=None, check_levels=True):
+def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstruction=False):
     H = w["H"] if H is None else H
     N, d, K = w["N"], w["d"], w["K"]
     o = Oracle(seed, tau=tau, K=K)
     sx, sy = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
     o.train_create(sx, sy, N, d, H)
+    o.train_set_heuristic(by_reconstruction)
     ref = plain_cart.train(w["X"], w["y"], K, H, tau)
     CW = d * K + K
     for h in range(H):
@@ -129,6 +130,36 @@ def test_degenerate_inputs(seed):
     y1 = np.array([0, 1, 1, 0])
     Y1 = np.zeros((4, 2), dtype=np.uint64); Y1[np.arange(4), y1] = 1
     run_oracle_train(seed, dict(X=X1, Y=Y1, y=y1, N=4, d=1, K=2, H=2))
+
+
+def test_heuristic_by_reconstruction_matches_plaintext_cart(seed):
+    """The reconstruct-and-score heuristic (host analogue of the TEE-based protocol, Sec. V-B)
+    gives, level by level, the same M, statistics, masked scores, split decisions, gamma, node
+    types and tree as the plaintext CART - hence the same as the MPC heuristic, which the
+    tests above pin to the same reference - on two-class, multi-class, ragged and degenerate
+    inputs; its sharings are fresh (components differ from the MPC run) and it needs far fewer
+    rounds."""
+    w = wl.c1_train()
+    o, ref, _ = run_oracle_train(seed, w, by_reconstruction=True)
+    o2, _, _ = run_oracle_train(seed, w)
+    assert o.stats()[0] < o2.stats()[0] / 5
+    assert not np.array_equal(o.train_export(X_T), o2.train_export(X_T))
+    assert np.array_equal(Oracle.rec(o.train_export(X_T)), Oracle.rec(o2.train_export(X_T)))
+    sin, sout = o.scorer_bytes()
+    CW = w["d"] * w["K"] + w["K"]
+    nn = sum(1 << h for h in range(w["H"]))
+    assert sin == 3 * 8 * nn * (CW + w["d"] + 1) and sout == 3 * 16 * nn * (2 * w["d"] + 4)
+    run_oracle_train(seed, wl.c2_train(), H=5, by_reconstruction=True)
+    rng = np.random.default_rng(77)
+    N, d, K = 150, 9, 4
+    X = (rng.random((N, d)) < 0.4).astype(np.uint64)
+    y = (X[:, 0].astype(np.int64) * 2 + X[:, 3].astype(np.int64) + (rng.random(N) < 0.1)) % K
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), tau=10, by_reconstruction=True)
+    X = np.array([[0, 1], [1, 1], [1, 0], [0, 0], [1, 1]], dtype=np.uint64)
+    y = np.ones(5, dtype=np.int64)
+    Y = np.zeros((5, 2), dtype=np.uint64); Y[:, 1] = 1
+    run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=2), by_reconstruction=True)
 
 
 def test_counter_array_paper_layout(seed):
