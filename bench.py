@@ -79,6 +79,20 @@ def paper_shapes(np, torch, gtree, wl):
     ncand = sum((1 << h) * d for h in range(H))
     res["c3_train_depth7"] = {"samples": N, "columns": d, "seconds": tm, "candidates_per_s": ncand / tm,
                               "candidates_per_s_per_level": [(1 << h) * d / per_level[h] for h in range(H)]}
+    # the same training with the heuristic by reconstruction (host analogue of the TEE-based protocol):
+    # what is left when Gini division, arg-max and updates cost two rounds - the bound for steps a4-a7
+    g.train_set_heuristic(True)
+    times = []
+    for it in range(6):
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        g.train_reset(X, Y)
+        for h in range(H):
+            g.train_level(h)
+        g.train_finish().close()
+        torch.cuda.synchronize()
+        if it:
+            times.append(time.perf_counter() - t0)
+    res["c3_train_depth7"]["seconds_with_heuristic_by_reconstruction"] = sorted(times)[len(times) // 2]
     g.close(); del g, X, Y
     wi = wl.c4_infer()
     g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=2)

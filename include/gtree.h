@@ -65,7 +65,11 @@ typedef struct { gt_plane2 party[3]; size_t n; } gt_shares;
  * where they store them (per element that exists, so padding lanes count nothing);
  * kernel_ms: GPU time of the launches, from HIP events on the context's stream
  * (only with GT_FLAG_PROFILE, otherwise 0). */
-typedef struct { uint64_t rounds; uint64_t wire_bytes[3][3]; uint64_t wire_bits_dev[3][3]; double kernel_ms; } gt_stats;
+typedef struct {
+    uint64_t rounds; uint64_t wire_bytes[3][3]; uint64_t wire_bits_dev[3][3];
+    uint64_t scorer_bytes[2]; /* heuristic by reconstruction: bytes the parties sent to the scorer, and got back */
+    double kernel_ms;
+} gt_stats;
 
 /* tau: fractional bits of the fixed-point Gini quotients (Sec. V-B); K: classes;
  * seed[0..2]: pairwise keys k1..k3 (party p uses seed[p], seed[p+1 mod 3], Sec. III),
@@ -159,6 +163,15 @@ int gt_train_level(gt_ctx *ctx, gt_train *tr, uint32_t h);
 /* level H: partition, class totals, majority label per node.  The tree's shares
  * are copied into a new gt_tree (binary mode). */
 int gt_train_finish(gt_ctx *ctx, gt_train *tr, gt_tree **out);
+/* Heuristic computation of the following levels by reconstruction instead of the MPC
+ * protocol: the host analogue of the TEE-based protocol (Sec. V-B, Alg. "Oblivious
+ * Heuristic Computation via TEE"), as a debugging aid and an upper bound for the MPC
+ * heuristic.  A scorer (a fourth role, played by a kernel that reads all three components)
+ * reconstructs the level's C, gamma and F, computes scores, first maximum, gamma and node
+ * types in the clear with the same fixed-point rule, and hands back fresh sharings under
+ * the dealer's key.  Same reconstructed SD, gamma, F, T as the MPC heuristic; two rounds.
+ * There is no enclave here: the scorer sees the statistics in the clear. */
+int gt_train_set_heuristic(gt_train *tr, int by_reconstruction);
 int gt_train_destroy(gt_train *tr);
 
 enum {

@@ -27,9 +27,11 @@ __device__ __forceinline__ P6 p6_off(P6 a, size_t off)
 // ---------------------------------------------------------------------------------
 // Share^A (Sec. II-B): x1, x2 from the owner's key (streams 0 and 1), x3 = x - x1 - x2.
 // One lane produces 8 consecutive elements (one PRF block per stream).
-__global__ __launch_bounds__(256) void k_share(const u32 *keys, u32 op, const u64 *plain, u64 n, P6 out)
+// key: whose randomness shares the values (the data owner / query user, or the scorer of the
+// heuristic by reconstruction, who uses the dealer's key); off: first element of `out`.
+__global__ __launch_bounds__(256) void k_share(const u32 *keys, int key, u32 op, const u64 *plain, u64 n, P6 out, u64 off)
 {
-    const Key ko = load_key(keys, GT_KEY_OWNER);
+    const Key ko = load_key(keys, key);
     const u64 ngrp = (n + 7) / 8;
     for (u64 g = (u64)blockIdx.x * blockDim.x + threadIdx.x; g < ngrp; g += (u64)gridDim.x * blockDim.x) {
         u64 a[8], b[8];
@@ -40,9 +42,9 @@ __global__ __launch_bounds__(256) void k_share(const u32 *keys, u32 op, const u6
             const u64 e = g * 8 + s;
             if (e < n) {
                 const u64 x3 = plain[e] - a[s] - b[s];
-                out.o[0][e] = a[s]; out.n[0][e] = b[s];
-                out.o[1][e] = b[s]; out.n[1][e] = x3;
-                out.o[2][e] = x3;   out.n[2][e] = a[s];
+                out.o[0][off + e] = a[s]; out.n[0][off + e] = b[s];
+                out.o[1][off + e] = b[s]; out.n[1][off + e] = x3;
+                out.o[2][off + e] = x3;   out.n[2][off + e] = a[s];
             }
         }
     }
@@ -1016,6 +1018,80 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
         }
     }
     W.flush(a.c.wire);
+}
+
+// ---------------------------------------------------------------------------------
+// Heuristic computation by reconstruction, the host analogue of the TEE-based protocol of
+// Sec. V-B: the scorer (a fourth role, not one of the parties) reconstructs the level's C,
+// gamma and F from the three components and computes in the clear what the MPC protocol
+// computes: fixed-point scores sum_j floor(S_j 2^tau / Q_j) (empty branch: 0) masked by
+// gamma, the first maximum, the updated gamma, purity n^2 = sum_c tot_c^2, node types.
+// One workgroup per node; plain results for the sharing kernel.
+struct HcOpenArgs { P6 C, gamma, F; u64 base; u32 nh, d, K, CW, tau; u64 *SD, *G, *Fn, *Fc, *Sp, *SC; };
+__device__ __forceinline__ u64 rec3(const P6 &a, u64 e) { return a.o[0][e] + a.n[0][e] + a.o[2][e]; }
+
+__global__ __launch_bounds__(256) void k_hc_open(HcOpenArgs a)
+{
+    __shared__ u64 s_tot[16], s_best[256];
+    __shared__ u32 s_idx[256];
+    const u32 tid = threadIdx.x;
+    const u64 dK = (u64)a.d * a.K;
+    for (u32 r = blockIdx.x; r < a.nh; r += gridDim.x) {
+        if (tid < a.K) s_tot[tid] = rec3(a.C, (u64)r * a.CW + dK + tid);
+        __syncthreads();
+        u64 n = 0;
+        for (u32 cl = 0; cl < a.K; cl++) n += s_tot[cl];
+        u64 best = 0; u32 bi = 0xffffffffu;
+        for (u32 k = tid; k < a.d; k += blockDim.x) {
+            u64 score = 0;
+            for (int br = 0; br < 2; br++) {
+                u64 nj = 0, S = 0;
+                for (u32 cl = 0; cl < a.K; cl++) {
+                    const u64 n1 = rec3(a.C, (u64)r * a.CW + (u64)k * a.K + cl);
+                    const u64 njc = br ? n1 : s_tot[cl] - n1;
+                    nj += njc; S += njc * njc;
+                }
+                u64 Q = nj * n;
+                if (Q == 0) Q = 1;
+                score += (S << a.tau) / Q;
+            }
+            const u64 g = rec3(a.gamma, (u64)r * a.d + k);
+            score *= g;
+            a.SC[(u64)r * a.d + k] = score; a.G[(u64)r * a.d + k] = g;
+            if (bi == 0xffffffffu || score > best) { best = score; bi = k; }   // ascending k: the first maximum of this thread
+        }
+        s_best[tid] = best; s_idx[tid] = bi;
+        __syncthreads();
+        for (u32 st = 128; st > 0; st >>= 1) {         // larger score wins, then the lower index
+            if (tid < st) {
+                const u64 ob = s_best[tid + st]; const u32 oi = s_idx[tid + st];
+                if (oi != 0xffffffffu && (s_idx[tid] == 0xffffffffu || ob > s_best[tid] || (ob == s_best[tid] && oi < s_idx[tid]))) {
+                    s_best[tid] = ob; s_idx[tid] = oi;
+                }
+            }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            const u32 sd = s_idx[0];
+            u64 sq = 0;
+            for (u32 cl = 0; cl < a.K; cl++) sq += s_tot[cl] * s_tot[cl];
+            const u64 F = rec3(a.F, a.base + r);
+            const u64 split = (F == 1 && n * n - sq != 0) ? 1 : 0;
+            a.SD[r] = sd; a.G[(u64)r * a.d + sd] = 0;
+            a.Sp[r] = split; a.Fn[r] = F * (1 - split); a.Fc[r] = 2 - split;
+        }
+        __syncthreads();
+    }
+}
+
+// F of both children of node r := the sharing of node r in src
+__global__ __launch_bounds__(256) void k_children(P6 F, P6 src, u64 base, u64 nh)
+{
+    for (u64 r = (u64)blockIdx.x * blockDim.x + threadIdx.x; r < nh; r += (u64)gridDim.x * blockDim.x)
+        for (int j = 0; j < 3; j++) {
+            F.o[j][2 * (base + r) + 1] = F.o[j][2 * (base + r) + 2] = src.o[j][r];
+            F.n[j][2 * (base + r) + 1] = F.n[j][2 * (base + r) + 2] = src.n[j][r];
+        }
 }
 
 // ---------------------------------------------------------------------------------

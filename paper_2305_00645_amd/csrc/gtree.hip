@@ -78,6 +78,8 @@ struct gt_train {
     size_t N, N8;
     u32 d, K, H, CW, level, last, P2;
     bool finished;
+    bool hc_open;                    // heuristic computation by reconstruction instead of the MPC protocol
+    u64 *hcp;                        // the scorer's plain results: SD, gamma, F node, F children, split, scores
     bool fresh_import;               // state was imported and no level has run since: nothing to export for "last"
     TreeSlot *slot;
     DSh XT, YT;                      // [k][i], [c][i]: sample-contiguous copies of the inputs
@@ -313,7 +315,7 @@ extern "C" int gt_share_a(gt_ctx *c, const uint64_t *plain, size_t n, const gt_s
     Timed T(c);
     u32 op = c->op++;
     int rc = GT_OK;
-    if (n) rc = launch(c, GT_KC_SHARE, k_share, g1((n + 7) / 8), B256, (const u32 *)c->keys_d, op, plain, (u64)n, to_p6(out));
+    if (n) rc = launch(c, GT_KC_SHARE, k_share, g1((n + 7) / 8), B256, (const u32 *)c->keys_d, (int)GT_KEY_OWNER, op, plain, (u64)n, to_p6(out), (u64)0);
     return T.finish(rc);
 }
 
@@ -493,6 +495,7 @@ static void train_free(gt_train *t)
                    &t->tval, &t->best, &t->lab, &t->Clast, &t->Glast, &t->Slast };
     for (DSh *s : all) dsh_free(*s);
     if (t->Zacc) (void)hipFree(t->Zacc);
+    if (t->hcp) (void)hipFree(t->hcp);
     if (t->slot) {
         if (t->slot->in_use) t->slot->orphan = true;     // the tree made from it frees it
         else { dsh_free(t->slot->feat); dsh_free(t->slot->leaf); delete t->slot; }
@@ -552,6 +555,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     size_t P2 = 1; while (P2 < d) P2 *= 2;
     t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
     t->finished = false; t->fresh_import = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr; t->slot = nullptr;
+    t->hc_open = false; t->hcp = nullptr;
     hipStream_t s = c->stream;
     int rc = GT_OK;
     struct { DSh *v; size_t n; } plan[] = {
@@ -570,6 +574,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
         if (rc == GT_OK) rc = dsh_alloc(t->slot->leaf, nmax, s);
     }
     if (rc == GT_OK && hipMalloc(&t->Zacc, 3 * nmax * CW * 8) != hipSuccess) rc = GT_ENOMEM;
+    if (rc == GT_OK && hipMalloc(&t->hcp, nmax * (2 * (size_t)d + 4) * 8) != hipSuccess) rc = GT_ENOMEM;
     // zero once: k_count_fin leaves every word it has read at zero again
     if (rc == GT_OK && hipMemsetAsync(t->Zacc, 0, 3 * nmax * CW * 8, s) != hipSuccess) rc = GT_EHIP;
     t->nblk = (N + 31) / 32;
@@ -584,6 +589,13 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     rc = T.finish(rc);
     if (rc != GT_OK) { train_free(t); return rc; }
     *out = t;
+    return GT_OK;
+}
+
+extern "C" int gt_train_set_heuristic(gt_train *t, int by_reconstruction)
+{
+    if (!t) return GT_EINVAL;
+    t->hc_open = by_reconstruction != 0;
     return GT_OK;
 }
 
@@ -689,9 +701,9 @@ static int heuristic(gt_ctx *c, gt_train *t, u32 h)
     return copy6(c, t->SD.v, 0, t->idx[cur].v, 0, 1, nh);
 }
 
-static int update(gt_ctx *c, gt_train *t, u32 h)
+static int update_flags(gt_ctx *c, gt_train *t, u32 h)
 {
-    const u64 nh = (u64)1 << h, base = nh - 1, d = t->d, CW = t->CW;
+    const u64 nh = (u64)1 << h, base = nh - 1, d = t->d;
     GammaArgs ga{}; ga.c = kc(c, c->op++); ga.SD = t->SD.v; ga.gamma = t->gamma.v; ga.n = nh * d; ga.d = t->d;
     GTCHK(launch(c, GT_KC_SMALL, k_gamma, dim3(tiles(ga.n)), GT_BLOCK, ga));
     acct_eq(c, nh * d); acct_b2a(c, nh * d); acct_reshare(c, nh * d, 1);
@@ -699,6 +711,38 @@ static int update(gt_ctx *c, gt_train *t, u32 h)
     sa.n = nh; sa.base = base; sa.K = t->K; sa.CW = t->CW; sa.dK = (u64)t->d * t->K;
     GTCHK(launch(c, GT_KC_SMALL, k_split, dim3(tiles(nh)), GT_BLOCK, sa));
     acct_reshare(c, nh, 1); acct_eq(c, nh); acct_and1(c, nh); acct_b2a(c, nh); acct_reshare(c, nh, 1);
+    return GT_OK;
+}
+
+// Heuristic by reconstruction: the scorer's kernel, then six sharings under the dealer's key
+// (SD, gamma, F of the nodes, F of the children, split flags, masked scores), one operation
+// id each.  Two rounds; bytes to and from the scorer are counted apart.
+static int heuristic_open(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 nh = (u64)1 << h, base = nh - 1, d = t->d, nmax = (u64)1 << t->H;
+    u64 *SDp = t->hcp, *Gp = SDp + nmax, *Fn = Gp + nmax * d, *Fc = Fn + nmax, *Sp = Fc + nmax, *SCp = Sp + nmax;
+    HcOpenArgs a{}; a.C = t->C.v; a.gamma = t->gamma.v; a.F = t->F.v; a.base = base; a.nh = (u32)nh; a.d = t->d; a.K = t->K; a.CW = t->CW;
+    a.tau = c->tau; a.SD = SDp; a.G = Gp; a.Fn = Fn; a.Fc = Fc; a.Sp = Sp; a.SC = SCp;
+    GTCHK(launch(c, GT_KC_SMALL, k_hc_open, dim3((unsigned)std::min<u64>(nh, 4096)), B256, a));
+    c->acc.scorer_bytes[0] += 3 * 8 * nh * (t->CW + d + 1);
+    c->acc.rounds += 1;
+    struct { const u64 *plain; u64 n; P6 out; u64 off; } sh[6] = {
+        { SDp, nh, t->SD.v, 0 }, { Gp, nh * d, t->gamma.v, 0 }, { Fn, nh, t->F.v, base }, { Fc, nh, t->best.v, 0 },
+        { Sp, nh, t->split.v, 0 }, { SCp, nh * d, t->Slast.v, 0 } };
+    for (int i = 0; i < 6; i++) {
+        GTCHK(launch(c, GT_KC_SHARE, k_share, g1((sh[i].n + 7) / 8), B256, (const u32 *)c->keys_d, (int)GT_KEY_DEALER, c->op++,
+                     sh[i].plain, sh[i].n, sh[i].out, sh[i].off));
+        c->acc.scorer_bytes[1] += 3 * 2 * 8 * sh[i].n;
+        if (i == 3) GTCHK(launch(c, GT_KC_LOCAL, k_children, g1(nh), B256, t->F.v, t->best.v, base, nh));
+    }
+    c->acc.rounds += 1;
+    return GT_OK;
+}
+
+// Node split: T takes the split decisions, children inherit or clear the statistics.
+static int node_split(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 nh = (u64)1 << h, base = nh - 1, d = t->d, CW = t->CW;
     // keep this level's statistics and flags for export; T takes the split decisions
     GTCHK(copy6(c, t->Clast.v, 0, t->C.v, 0, 1, nh * CW));
     GTCHK(copy6(c, t->Glast.v, 0, t->gamma.v, 0, 1, nh * d));
@@ -725,8 +769,10 @@ extern "C" int gt_train_level(gt_ctx *c, gt_train *t, uint32_t h)
     if (h > 0) rc = partition(c, t, h);
     if (rc == GT_OK) rc = leaf_onehot(c, t, h);
     if (rc == GT_OK) rc = count(c, t, h, false);
-    if (rc == GT_OK) rc = heuristic(c, t, h);
-    if (rc == GT_OK) rc = update(c, t, h);
+    if (rc == GT_OK && t->hc_open) rc = heuristic_open(c, t, h);
+    if (rc == GT_OK && !t->hc_open) rc = heuristic(c, t, h);
+    if (rc == GT_OK && !t->hc_open) rc = update_flags(c, t, h);
+    if (rc == GT_OK) rc = node_split(c, t, h);
     if (rc == GT_OK) { t->level = h + 1; t->fresh_import = false; }
     return T.finish(rc);
 }

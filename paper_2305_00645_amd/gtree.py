@@ -34,7 +34,7 @@ class _Shares(C.Structure):
 
 class _Stats(C.Structure):
     _fields_ = [("rounds", C.c_uint64), ("wire_bytes", (C.c_uint64 * 3) * 3), ("wire_bits_dev", (C.c_uint64 * 3) * 3),
-                ("kernel_ms", C.c_double)]
+                ("scorer_bytes", C.c_uint64 * 2), ("kernel_ms", C.c_double)]
 
 
 GT_FLAG_PROFILE = 1
@@ -91,6 +91,7 @@ def load():
         "gt_div": (i, [vp, S, S, sz, S]),
         "gt_train_create": (i, [vp, S, S, sz, u32, u32, C.POINTER(vp)]),
         "gt_train_level": (i, [vp, vp, u32]),
+        "gt_train_set_heuristic": (i, [vp, i]),
         "gt_train_finish": (i, [vp, vp, C.POINTER(vp)]),
         "gt_train_destroy": (i, [vp]),
         "gt_train_export_size": (sz, [vp, i]),
@@ -291,6 +292,14 @@ class GTree:
 
     def train_reset(self, X, Y):
         _chk(self.L.gt_train_reset(self.ctx, self._train, _ref(X), _ref(Y)), "gt_train_reset")
+
+    def train_set_heuristic(self, by_reconstruction):
+        _chk(self.L.gt_train_set_heuristic(self._train, int(bool(by_reconstruction))), "gt_train_set_heuristic")
+
+    def scorer_bytes(self):
+        st = _Stats()
+        _chk(self.L.gt_stats_get(self.ctx, C.byref(st)), "gt_stats_get")
+        return int(st.scorer_bytes[0]), int(st.scorer_bytes[1])
 
     def train_level(self, h):
         _chk(self.L.gt_train_level(self.ctx, self._train, h), "gt_train_level")

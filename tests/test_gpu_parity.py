@@ -335,6 +335,52 @@ def test_export_after_import_needs_a_level(mods, seed):
     assert g.train_export(X_C).n == 4 * 12
 
 
+@pytest.mark.parametrize("case", ["c1", "c2", "multi", "degenerate"])
+def test_heuristic_by_reconstruction(mods, seed, case):
+    """Reconstruct-and-score heuristic (host analogue of the TEE-based protocol): share by
+    share against the oracle in the same mode, and the reconstructed tree against the
+    plaintext CART (hence equal to the MPC heuristic's)."""
+    import plain_cart
+    from oracle import X_T, X_F, X_M, X_C, X_GAMMA, X_SD, X_SCORE
+    from paper_2305_00645_amd import workloads as wl
+    tau = 16
+    if case == "c1":
+        w = wl.c1_train()
+    elif case == "c2":
+        w = wl.c2_train(H=5)
+    elif case == "multi":
+        rng = np.random.default_rng(77)
+        N, d, K = 203, 9, 4
+        X = (rng.random((N, d)) < 0.4).astype(np.uint64)
+        y = (X[:, 0].astype(np.int64) * 2 + X[:, 3].astype(np.int64) + (rng.random(N) < 0.1)) % K
+        Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+        w, tau = dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), 10
+    else:
+        X = np.array([[0, 1], [1, 1], [1, 0], [0, 0], [1, 1]], dtype=np.uint64)
+        y = np.ones(5, dtype=np.int64)
+        Y = np.zeros((5, 2), dtype=np.uint64); Y[:, 1] = 1
+        w = dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=2)
+    N, d, K, H = w["N"], w["d"], w["K"], w["H"]
+    o, g = pair(mods, seed, tau=tau, K=K)
+    o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, H)
+    g.train_create(g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1)), N, d, H)
+    o.train_set_heuristic(True); g.train_set_heuristic(True)
+    for h in range(H):
+        o.train_level(h); g.train_level(h)
+        for nm, what in (("M", X_M), ("C", X_C), ("SCORE", X_SCORE), ("SD", X_SD), ("GAMMA", X_GAMMA), ("F", X_F), ("T", X_T)):
+            same(g.train_export(what), o.train_export(what), "level %d %s" % (h, nm))
+    fo, lo = o.train_finish()
+    tree = g.train_finish()
+    fg, lg = tree.export()
+    same(fg, fo, "features"); same(lg, lo, "labels")
+    ref = plain_cart.train(w["X"], w["y"], K, H, tau)
+    assert np.array_equal(g.rec(g.train_export(X_T)).astype(np.int64), ref["T"])
+    assert np.array_equal(g.rec(g.train_export(X_F)).astype(np.int64), ref["F"])
+    same_stats(o, g)
+    assert o.scorer_bytes() == g.scorer_bytes()
+    tree.close(); g.close()
+
+
 def test_train_errors(mods, seed):
     Oracle, gtree = mods
     from paper_2305_00645_amd import workloads as wl
