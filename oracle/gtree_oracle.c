@@ -558,6 +558,56 @@ void orc_oaa(orc_ctx *c, const uint64_t *Wf, size_t w, const uint64_t *uf, size_
 }
 
 /* ------------------------------------------------------------------------- */
+/* The protocols as the paper prints them (Sec. V-A, Alg. "Oblivious Array Access";
+ * Sec. V-B, Alg. "Oblivious Learning"), without the fusion into inner products used
+ * above: every array element goes through its own SelectShare - the comparison bit is
+ * converted with a daBit of the element's own, the opened value travelling as a ring
+ * element of l bits as the paper's cost formula counts it, then multiplied with the array
+ * element with a zero-sharing word and a reshare of the element's own - and the selected
+ * elements are added up locally.  Per element: equality test 2l-1 bits, conversion l,
+ * product l = 4l-1 bits, in log l + 3 rounds.  Reconstructed results equal those of the
+ * fused protocols.  Streams: 0 dealer, 1 masks, 2 product; all indexed by the element. */
+static void wire_b2a_wide(orc_ctx *c, u64 n) { wire(c, +1, n, 64); c->rounds += 1; }
+
+/* z[i] = sum_k Select(E[k][i], W) with E[k][i] = [u[i] - base == k]; W is common to all
+ * rows (Wcommon, offset woff) or the row's own (Wrows[k*n8 + i]) */
+static void oaa_literal(orc_ctx *c, const sh *u, u64 base, size_t w, size_t n, const sh *Wcommon,
+                        size_t woff, const sh *Wrows, sh *z)
+{
+    u32 op = c->op++;
+    size_t n8 = pad8(n);
+    sh_zero(z);
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; i++) {
+        u64 acc[3] = { 0, 0, 0 };
+        for (size_t k = 0; k < w; k++) {
+            size_t e = k * n8 + i;
+            u64 v[3], A[3], t[3], a[3], b[3], al[3], p[3]; dealer_t D;
+            sh_get(u, i, v);
+            v[0] -= base + k;
+            dealer(c, op, e, &D);
+            eq_el(c, op, e, v, &D, A, t);
+            b2a_el(t, &D, a);
+            if (Wcommon) sh_get(Wcommon, woff + k, b); else sh_get(Wrows, e, b);
+            zero_a(c, op, 2, e, al);
+            mult_el(a, b, al, p);
+            for (int j = 0; j < 3; j++) acc[j] += p[j];
+        }
+        sh_set(z, i, acc);
+    }
+    wire_eq(c, (u64)w * n); wire_b2a_wide(c, (u64)w * n); wire_reshare(c, (u64)w * n, 1);
+}
+
+void orc_oaa_literal(orc_ctx *c, const uint64_t *Wf, size_t w, const uint64_t *uf, size_t n, uint64_t *zf)
+{
+    sh W = sh_alloc(w), u = sh_alloc(n), z = sh_alloc(n);
+    sh_from_flat(&W, Wf); sh_from_flat(&u, uf);
+    oaa_literal(c, &u, 0, w, n, &W, 0, NULL, &z);
+    sh_to_flat(&z, zf);
+    sh_free(&W); sh_free(&u); sh_free(&z);
+}
+
+/* ------------------------------------------------------------------------- */
 /* One step of restoring division on n elements (one op): b = [r >= Q],
  * r <- r - b*Q, quo <- 2*quo + b.  Streams: 0 dealer, 1/2 comparison, 3 product. */
 static void div_step(orc_ctx *c, sh *r, const sh *Q, sh *quo, size_t n)
@@ -648,6 +698,8 @@ struct orc_train {
     u32 last;              /* level the copies belong to */
     int fresh_import;      /* state was imported and no level has run since: the copies are not valid */
     int hc_open;           /* heuristic computation by reconstruction instead of the MPC protocol */
+    int literal;           /* learning protocol as printed: whole-T scans, per-element SelectShare */
+    sh LB;                 /* literal mode: per-sample leaf flags as Boolean bits, n_h x N8 */
 };
 
 static size_t nodes_upto(u32 H) { return ((size_t)2 << H) - 1; }
@@ -666,6 +718,7 @@ orc_train *orc_train_create(orc_ctx *c, const uint64_t *Xf, const uint64_t *Yf, 
     t->isLeaf = sh_alloc(nmax); t->LT = sh_alloc(nmax * N8);
     t->SD = sh_alloc(nmax); t->split = sh_alloc(nmax);
     t->Clast = sh_alloc(nmax * t->CW); t->Glast = sh_alloc(nmax * d); t->Slast = sh_alloc(nmax * d);
+    t->LB = sh_alloc(0);
     for (int j = 0; j < 3; j++) {
         for (size_t i = 0; i < N; i++) {
             for (u32 k = 0; k < d; k++) t->XT.c[j][k * N8 + i] = Xf[(size_t)j * N * d + i * d + k];
@@ -696,7 +749,7 @@ void orc_train_destroy(orc_train *t)
 {
     if (!t) return;
     sh *all[] = { &t->XT, &t->YT, &t->XYT, &t->M, &t->T, &t->F, &t->C, &t->gamma, &t->isLeaf,
-                  &t->LT, &t->SD, &t->split, &t->Clast, &t->Glast, &t->Slast };
+                  &t->LT, &t->SD, &t->split, &t->Clast, &t->Glast, &t->Slast, &t->LB };
     for (size_t i = 0; i < sizeof all / sizeof all[0]; i++) sh_free(all[i]);
     free(t);
 }
@@ -765,6 +818,111 @@ static void count(orc_ctx *c, orc_train *t, u32 h, int totals_only)
         }
     wire_reshare(c, (u64)nh * ncol, 1);
 }
+
+/* The learning protocol as printed (Alg. "Oblivious Learning").  Data partition: array
+ * access over the WHOLE tree array (all 2^(H+1)-1 entries, index M itself), then over the
+ * sample's features. */
+static void partition_literal(orc_ctx *c, orc_train *t, u32 h)
+{
+    (void)h;
+    size_t N = t->N;
+    sh Tval = sh_alloc(N), Dval = sh_alloc(N);
+    oaa_literal(c, &t->M, 0, nodes_upto(t->H), N, &t->T, 0, NULL, &Tval);
+    oaa_literal(c, &Tval, 0, t->d, N, NULL, 0, &t->XT, &Dval);
+    for (int j = 0; j < 3; j++)
+        for (size_t i = 0; i < N; i++)
+            t->M.c[j][i] = 2 * t->M.c[j][i] + Dval.c[j][i] + (j == 0 ? 1 : 0);
+    sh_free(&Tval); sh_free(&Dval);
+}
+
+/* Leaf flags as Boolean bits: LCF[r][i] = [M[i] - (2^h - 1) == r] and isLeaf[r], no
+ * conversion (the per-element SelectShare of the counting step converts). */
+static void leaf_bits_literal(orc_ctx *c, orc_train *t, u32 h)
+{
+    size_t nh = (size_t)1 << h, base = nh - 1, N = t->N, N8 = t->N8;
+    u32 op = c->op++;
+    for (size_t r = 0; r < nh; r++) {
+        u64 v[3], A[3], b[3]; dealer_t D;
+        sh_get(&t->F, base + r, v);
+        v[0] -= 1;
+        dealer(c, op, r, &D);
+        eq_el(c, op, r, v, &D, A, b);
+        sh_set(&t->isLeaf, r, b);
+    }
+    wire_eq(c, nh);
+    op = c->op++;
+    sh_free(&t->LB);
+    t->LB = sh_alloc(nh * N8);
+#pragma omp parallel for schedule(static) collapse(2)
+    for (size_t r = 0; r < nh; r++)
+        for (size_t i = 0; i < N; i++) {
+            size_t e = r * N8 + i;
+            u64 v[3], A[3], b[3], g[3], al[3]; dealer_t D;
+            sh_get(&t->M, i, v);
+            v[0] -= base + r;
+            dealer(c, op, e, &D);
+            eq_el(c, op, e, v, &D, A, b);
+            sh_get(&t->isLeaf, r, g);
+            for (int j = 0; j < 3; j++) al[j] = (A[j] >> 63) & 1;
+            and_el(b, g, al, 1, b);
+            sh_set(&t->LB, e, b);
+        }
+    wire_eq(c, (u64)nh * N); wire_and1(c, (u64)nh * N);
+}
+
+/* Statistics counting as printed: the per-sample counter array C'[i] of (1+K) x 2d
+ * entries (row 0: [X_k = v]; row c+1: [X_k = v and class c]; column 2k+v) is selected by
+ * LCF[r][i] element by element and accumulated into the counter array of leaf r.  With
+ * totals_only (label level) only the entries of candidate 0 are needed.  The compact
+ * statistics (count of X_k = 1 and class c; class totals) are read off the counter array
+ * by local linear operations and added to the inherited ones.  Element index of the
+ * conversion and the product: (r*PW + q)*N8 + i, q the position in the counter array. */
+static void count_literal(orc_ctx *c, orc_train *t, u32 h, int totals_only)
+{
+    size_t nh = (size_t)1 << h, N = t->N, N8 = t->N8, d = t->d, K = t->K, dK = d * K, CW = t->CW;
+    size_t dd = totals_only ? 1 : d, PW = (1 + K) * 2 * dd;
+    u32 op = c->op++;
+    sh Cp = sh_alloc(nh * PW);
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (size_t r = 0; r < nh; r++)
+        for (size_t q = 0; q < PW; q++) {
+            size_t row = q / (2 * dd), k = (q % (2 * dd)) / 2, v = q & 1;
+            u64 acc[3] = { 0, 0, 0 };
+            for (size_t i = 0; i < N; i++) {
+                size_t e = (r * PW + q) * N8 + i;
+                u64 s[3], a[3], cv[3], al[3], p[3]; dealer_t D;
+                /* C'[i][row][2k+v] by local linear operations on X, Y and the one-time products */
+                for (int j = 0; j < 3; j++) {
+                    u64 x = t->XT.c[j][k * N8 + i];
+                    if (row == 0) cv[j] = v ? x : (u64)(j == 0) - x;
+                    else {
+                        u64 xy = t->XYT.c[j][(k * K + (row - 1)) * N8 + i], y = t->YT.c[j][(row - 1) * N8 + i];
+                        cv[j] = v ? xy : y - xy;
+                    }
+                }
+                sh_get(&t->LB, r * N8 + i, s);
+                dealer(c, op, e, &D);
+                b2a_el(s, &D, a);
+                zero_a(c, op, 2, e, al);
+                mult_el(a, cv, al, p);
+                for (int j = 0; j < 3; j++) acc[j] += p[j];
+            }
+            sh_set(&Cp, r * PW + q, acc);
+        }
+    wire_b2a_wide(c, (u64)nh * PW * N); wire_reshare(c, (u64)nh * PW * N, 1);
+    for (int j = 0; j < 3; j++)
+        for (size_t r = 0; r < nh; r++) {
+            const u64 *o = Cp.c[j] + r * PW;
+            for (size_t cl = 0; cl < K; cl++) {
+                t->C.c[j][r * CW + dK + cl] += o[(cl + 1) * 2 * dd] + o[(cl + 1) * 2 * dd + 1];
+                if (!totals_only)
+                    for (size_t k = 0; k < d; k++) t->C.c[j][r * CW + k * K + cl] += o[(cl + 1) * 2 * dd + 2 * k + 1];
+            }
+        }
+    sh_free(&Cp);
+}
+
+void orc_train_set_literal(orc_train *t, int literal) { t->literal = literal ? 1 : 0; }
 
 /* Heuristic computation (Sec. V-B, MPC-based): for every node r, candidate k and
  * branch j the class counts n_jc, S = sum_c n_jc^2 and Q = n_j * n; the score
@@ -1034,9 +1192,15 @@ void orc_train_set_heuristic(orc_train *t, int by_reconstruction) { t->hc_open =
 int orc_train_level(orc_ctx *c, orc_train *t, uint32_t h)
 {
     if (h != t->level || h >= t->H) return -1;
-    if (h > 0) partition(c, t, h);
-    leaf_onehot(c, t, h);
-    count(c, t, h, 0);
+    if (t->literal) {
+        if (h > 0) partition_literal(c, t, h);
+        leaf_bits_literal(c, t, h);
+        count_literal(c, t, h, 0);
+    } else {
+        if (h > 0) partition(c, t, h);
+        leaf_onehot(c, t, h);
+        count(c, t, h, 0);
+    }
     if (t->hc_open) heuristic_open(c, t, h);
     else { heuristic(c, t, h); update_flags(c, t, h); }
     node_split(c, t, h);
@@ -1053,9 +1217,15 @@ int orc_train_finish(orc_ctx *c, orc_train *t, uint64_t *feat, uint64_t *leaf)
     u32 H = t->H, K = t->K;
     if (t->level != H) return -1;
     size_t nh = (size_t)1 << H, base = nh - 1, dK = (size_t)t->d * K, CW = t->CW;
-    if (H > 0) partition(c, t, H);
-    leaf_onehot(c, t, H);
-    count(c, t, H, 1);
+    if (t->literal) {
+        if (H > 0) partition_literal(c, t, H);
+        leaf_bits_literal(c, t, H);
+        count_literal(c, t, H, 1);
+    } else {
+        if (H > 0) partition(c, t, H);
+        leaf_onehot(c, t, H);
+        count(c, t, H, 1);
+    }
     sh best = sh_alloc(nh), lab = sh_alloc(nh), cand = sh_alloc(nh), ci = sh_alloc(nh);
     for (size_t r = 0; r < nh; r++) { u64 x[3]; sh_get(&t->C, r * CW + dK, x); sh_set(&best, r, x); }
     for (u32 cl = 1; cl < K; cl++) {
@@ -1113,7 +1283,7 @@ int orc_train_export(const orc_train *t, int what, uint64_t *comp)
     case ORC_X_GAMMA: src = &t->Glast; break;
     case ORC_X_SCORE: src = &t->Slast; break;
     case ORC_X_SD: src = &t->SD; break;
-    case ORC_X_L: src = &t->LT; break;
+    case ORC_X_L: if (t->literal) return -1; src = &t->LT; break;
     case ORC_X_C_PAPER: {
         /* counter array of Sec. V-B: per node, rows 1..K hold the (value, class)
          * counts, column 2k+v for value v of candidate k; row 0 is their sum */

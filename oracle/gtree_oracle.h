@@ -99,6 +99,15 @@ orc_train *orc_train_create(orc_ctx *, const uint64_t *X /*N x d comps*/,
                             const uint64_t *Y /*N x K comps*/, size_t N, uint32_t d,
                             uint32_t H);
 void orc_train_destroy(orc_train *);
+/* The array access as the paper prints it (Sec. V-A): a SelectShare of its own for every
+ * array element (conversion with the opened value sent as a ring element, product with a
+ * reshare), local sum.  N(4l-1) bits for N = w*n, log l + 3 rounds.  Same reconstructed z. */
+void orc_oaa_literal(orc_ctx *c, const uint64_t *W, size_t w, const uint64_t *u, size_t n, uint64_t *z);
+/* Learning protocol of the following levels as printed (Sec. V-B, Alg. "Oblivious
+ * Learning"): array access over the whole tree array, per-element SelectShare of the
+ * per-sample counter arrays and local accumulation.  Same reconstructed state; X_L is not
+ * exported in this mode.  For small inputs only. */
+void orc_train_set_literal(orc_train *t, int literal);
 /* Heuristic computation of the following levels by reconstruction (host analogue of the
  * TEE-based protocol of Sec. V-B: a scorer reconstructs C, gamma, F, scores in the clear with
  * the same fixed-point rule and hands back fresh sharings) instead of the MPC protocol. */

@@ -51,6 +51,8 @@ def _load():
         "orc_stats_bits": (None, [vp, _u64p]),
         "orc_stats_scorer": (None, [vp, _u64p]),
         "orc_train_set_heuristic": (None, [vp, i]),
+        "orc_train_set_literal": (None, [vp, i]),
+        "orc_oaa_literal": (None, [vp, _u64p, sz, _u64p, sz, _u64p]),
         "orc_stats_reset": (None, [vp]),
         "orc_op_counter": (u32, [vp]),
         "orc_set_threads": (None, [i]),
@@ -236,6 +238,13 @@ class Oracle:
                        _p(z.reshape(-1)))
         return z
 
+    def oaa_literal(self, W, u):
+        W, u = self._c(W), self._c(u)
+        z = np.zeros_like(u)
+        self.L.orc_oaa_literal(self.ctx, _p(W.reshape(-1)), W.shape[1], _p(u.reshape(-1)), u.shape[1],
+                               _p(z.reshape(-1)))
+        return z
+
     def div(self, S, Q):
         S, Q = self._c(S), self._c(Q)
         z = np.zeros_like(S)
@@ -251,6 +260,9 @@ class Oracle:
             self.L.orc_train_destroy(self._train)
         self._train = self.L.orc_train_create(self.ctx, _p(X.reshape(-1)), _p(Y.reshape(-1)), N, d, H)
         self._tshape = (N, d, H)
+
+    def train_set_literal(self, literal):
+        self.L.orc_train_set_literal(self._train, int(bool(literal)))
 
     def train_set_heuristic(self, by_reconstruction):
         self.L.orc_train_set_heuristic(self._train, int(bool(by_reconstruction)))

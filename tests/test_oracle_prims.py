@@ -210,3 +210,28 @@ def test_payload_bits_follow_the_cost_formulas(seed):
     o.eq_b(o.share(np.arange(3, dtype=np.uint64)), None)
     assert int(o.stats()[1][0].sum()) == 24 + 12 + 6 + 3 + 2 + 1 + 1      # 3 elements: 64,32,16,8,4,2,1 bits each
     assert int(o.wire_bits()[0].sum()) == 3 * 127
+
+
+@pytest.mark.parametrize("w,n", [(1, 3), (5, 40), (16, 9)])
+def test_array_access_as_printed_costs_4l_minus_1_bits(seed, w, n):
+    """The array access run element by element as the paper prints it (Sec. V-A) returns
+    W[u] and costs exactly N(4l-1) bits per party in log l + 3 rounds for N = |W|*|U|; the
+    fused access used elsewhere returns the same values for fewer bits."""
+    o = Oracle(seed)
+    rng = np.random.default_rng(w * 100 + n)
+    Wp = rng.integers(0, M64, size=w, dtype=np.uint64)
+    u = rng.integers(0, w + 1, size=n).astype(np.uint64)
+    sW, su = o.share(Wp), o.share(u)
+    o.stats_reset()
+    z = o.oaa_literal(sW, su)
+    want = np.array([Wp[int(i)] if int(i) < w else 0 for i in u], dtype=np.uint64)
+    assert np.array_equal(Oracle.rec(z), want)
+    rounds, _ = o.stats()
+    assert rounds == 6 + 3
+    bits = o.wire_bits()
+    for p in range(3):
+        assert int(bits[p].sum()) == w * n * (4 * 64 - 1)
+    o.stats_reset()
+    z2 = o.oaa(sW, su)
+    assert np.array_equal(Oracle.rec(z2), want)
+    assert int(o.wire_bits()[0].sum()) == w * n * 128 + n * 64 < w * n * 255 + 1

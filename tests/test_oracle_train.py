@@ -11,13 +11,14 @@ from paper_2305_00645_amd import workloads as wl
 M64 = (1 << 64) - 1
 
 
-def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstruction=False):
+def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstruction=False, literal=False):
     H = w["H"] if H is None else H
     N, d, K = w["N"], w["d"], w["K"]
     o = Oracle(seed, tau=tau, K=K)
     sx, sy = o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1))
     o.train_create(sx, sy, N, d, H)
     o.train_set_heuristic(by_reconstruction)
+    o.train_set_literal(literal)
     ref = plain_cart.train(w["X"], w["y"], K, H, tau)
     CW = d * K + K
     for h in range(H):
@@ -36,6 +37,8 @@ def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstructi
         assert np.array_equal(Oracle.rec(o.train_export(X_SD)).astype(np.int64), np.array(L["SD"]))
         G = Oracle.rec(o.train_export(X_GAMMA)).astype(np.int64).reshape(nh, d)
         assert np.array_equal(G, np.array(L["gamma"]))
+        if literal:
+            continue                           # no arithmetic one-hot exists in this mode
         # per-sample leaf one-hot: 1 exactly at the sample's node when that node is a real leaf
         LT = Oracle.rec(o.train_export(X_L)).astype(np.int64).reshape(nh, -1)[:, :N]
         Fbefore = np.array([1 if (L["split"][r] or _was_leaf(ref, h, r)) else 0 for r in range(nh)])
@@ -160,6 +163,39 @@ def test_heuristic_by_reconstruction_matches_plaintext_cart(seed):
     y = np.ones(5, dtype=np.int64)
     Y = np.zeros((5, 2), dtype=np.uint64); Y[:, 1] = 1
     run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=2), by_reconstruction=True)
+
+
+def test_learning_protocol_as_printed_matches_plaintext_and_cost_formula(seed):
+    """The learning protocol run as the paper prints it (array access over the whole tree
+    array, a SelectShare per element of the per-sample counter arrays, local accumulation)
+    gives the plaintext CART level by level - hence the same reconstructed state as the fused
+    protocol - and costs what the formulas of Sec. V-A say: per level h >= 1 and party,
+    (N*|T| + N*d)(4l-1) bits for the two array accesses, n_h(2l-1) for the leaf flags,
+    N*n_h*2l for the per-sample flags (test and AND), N*n_h*(1+K)*2d*2l for the selects."""
+    w = wl.c1_train(N=60, d=5, depth=3)
+    N, d, K, H, l = w["N"], w["d"], w["K"], w["H"], 64
+    o, ref, _ = run_oracle_train(seed, w, literal=True)
+    o2, _, _ = run_oracle_train(seed, w)
+    for what in (X_T, X_F, X_M, X_C):
+        assert np.array_equal(Oracle.rec(o.train_export(what)), Oracle.rec(o2.train_export(what)))
+    # learning part of the cost, separated from heuristic and node split by differencing two modes:
+    # both runs share the heuristic, so the difference of their bits is (literal - fused) learning
+    nT = (2 << H) - 1
+    lit = 0
+    for h in range(H + 1):
+        nh = 1 << h
+        cols = (1 + K) * 2 * (1 if h == H else d)
+        lit += (N * nT + N * d) * (4 * l - 1) if h > 0 else 0
+        lit += nh * (2 * l - 1) + N * nh * 2 * l + N * nh * cols * 2 * l
+    fused = 0
+    CW = d * K + K
+    for h in range(H + 1):
+        nh = 1 << h
+        if h > 0:
+            fused += N * (nh // 2) * 128 + N * l + N * d * 128 + N * l
+        fused += nh * (2 * l - 1) + N * nh * (2 * l + 1) + nh * (K if h == H else CW) * l
+    assert int(o.wire_bits()[0].sum()) - int(o2.wire_bits()[0].sum()) == lit - fused
+    run_oracle_train(seed, wl.c2_train(N=80, d=7, H=3), literal=True)
 
 
 def test_counter_array_paper_layout(seed):
