@@ -94,6 +94,25 @@ def paper_shapes(np, torch, gtree, wl):
             times.append(time.perf_counter() - t0)
     res["c3_train_depth7"]["seconds_with_heuristic_by_reconstruction"] = sorted(times)[len(times) // 2]
     g.close(); del g, X, Y
+    # the learning protocol run as the paper prints it (whole-tree scans, per-element SelectShare) beside
+    # the fused one, on the small heart-data-shaped workload (267 x 22, depth 4): counted bytes and time
+    w2 = wl.c2_train(H=4)
+    lit = {}
+    for mode in ("fused", "as_printed"):
+        g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=w2["K"])
+        g.train_create(g.share_a(w2["X"].reshape(-1)), g.share_a(w2["Y"].reshape(-1)), w2["N"], w2["d"], w2["H"])
+        g.train_set_literal(mode == "as_printed")
+        g.stats_reset()
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        for h in range(w2["H"]):
+            g.train_level(h)
+        g.train_finish().close()
+        torch.cuda.synchronize()
+        rounds, wire, _ = g.stats()
+        lit[mode] = {"seconds": time.perf_counter() - t0, "rounds": rounds, "bytes_sent_per_party": int(wire[0].sum()),
+                     "payload_bits_counted_by_the_kernels_per_party": int(g.wire_bits_dev()[0].sum())}
+        g.close()
+    res["c2_train_depth4_learning_as_printed_vs_fused"] = lit
     wi = wl.c4_infer()
     g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=2)
     tree = g.tree_import(g.share_a(wi["feat"]), g.share_a(wi["thr"]), g.share_a(wi["leaf"]), wi["H"])

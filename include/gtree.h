@@ -143,6 +143,12 @@ int gt_oaa(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t
  * of any kind is made.  n > GT_STATIC_MAX_N returns GT_EINVAL.  All contexts on one GPU
  * share the array: calls that overlap on one GPU race. */
 int gt_oaa_static(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z);
+/* gt_oaa run as the paper prints it (Sec. V-A, Alg. "Oblivious Array Access"): every one of
+ * the N = w*n array elements goes through a SelectShare of its own (conversion with the
+ * opened value counted as a ring element, product with a reshare), the selected elements are
+ * added up locally: N(4l-1) bits per party, log l + 3 rounds, same reconstructed z.  For
+ * setting the counted bytes beside the paper's formula; one element per lane, small inputs. */
+int gt_oaa_literal(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z);
 /* q = floor(S * 2^tau / Q) for 0 <= S <= Q < 2^40, Q > 0 (restoring division) */
 int gt_div(gt_ctx *ctx, const gt_shares *S, const gt_shares *Q, size_t n, const gt_shares *q);
 
@@ -172,6 +178,12 @@ int gt_train_finish(gt_ctx *ctx, gt_train *tr, gt_tree **out);
  * the dealer's key.  Same reconstructed SD, gamma, F, T as the MPC heuristic; two rounds.
  * There is no enclave here: the scorer sees the statistics in the clear. */
 int gt_train_set_heuristic(gt_train *tr, int by_reconstruction);
+/* Learning protocol of the following levels as printed (Sec. V-B, Alg. "Oblivious
+ * Learning"): array access over the whole tree array, a SelectShare per element of the
+ * per-sample (1+K) x 2d counter arrays, local accumulation - instead of the level slice and
+ * the fused inner products.  Same reconstructed state, the paper's message volume; meant
+ * for small inputs (first call allocates 2^H * N8 shares; GT_X_L is not exported). */
+int gt_train_set_literal(gt_ctx *ctx, gt_train *tr, int literal);
 int gt_train_destroy(gt_train *tr);
 
 enum {

@@ -385,10 +385,12 @@ __device__ __forceinline__ Sh ge_bit(Wire &W, const PartyKeys &K, int p, u32 op,
 }
 
 // bit -> arithmetic: open f = s xor beta; s = beta if f = 0 else 1 - beta
-__device__ __forceinline__ Sh b2a(Wire &W, int p, Sh s, const Dealer &D, bool act)
+// (bits: what the opened value is counted as - one bit, or a ring element of 64 bits where
+// the protocol is run as the paper's cost formula prices it)
+__device__ __forceinline__ Sh b2a(Wire &W, int p, Sh s, const Dealer &D, bool act, u32 bits = 1)
 {
     const u64 fo = (s.o ^ D.bBo) & 1, fn = (s.n ^ D.bBn) & 1;
-    const u64 f = (fo ^ fn ^ W.open1(fo, act ? 1u : 0u)) & 1;
+    const u64 f = (fo ^ fn ^ W.open1(fo, act ? bits : 0u)) & 1;
     Sh one = pub(p, 1), out;
     out.o = f ? one.o - D.bA.o : D.bA.o;
     out.n = f ? one.n - D.bA.n : D.bA.n;

@@ -1021,6 +1021,136 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 }
 
 // ---------------------------------------------------------------------------------
+// The protocols as the paper prints them (Sec. V-A, Alg. "Oblivious Array Access"; Sec. V-B,
+// Alg. "Oblivious Learning"), for small inputs: every array element goes through a
+// SelectShare of its own - conversion of the comparison bit with the element's own daBit,
+// the opened value counted as a ring element, then a product with a zero-sharing word and
+// a reshare of its own - and the selected elements are added up locally (atomic adds of
+// both components: exact and order-free in the ring).  One element per lane; streams 0
+// dealer, 1 masks, 2 product, all indexed by the element.
+struct LitOaaArgs { KCommon c; P6 u; u64 base; u32 w; u64 N, N8; P6 W1; u64 w1off; P6 XT; u64 *acc; };
+template <bool ROWS>
+__global__ __launch_bounds__(192) void k_oaa_literal(LitOaaArgs a)
+{
+    const int p = party_of_wave();
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
+    GT_FOR_TILES((u64)a.w * a.N8) {
+        const u64 e = GT_ELEM(), k = e / a.N8, i = e % a.N8;
+        const bool act = k < a.w && i < a.N;
+        Sh v = { 0, 0 }, wv = { 0, 0 };
+        if (act) {
+            v = ld(a.u, p, i) - pub(p, a.base + k);
+            wv = ROWS ? ld(a.XT, p, k * a.N8 + i) : ld(a.W1, p, a.w1off + k);
+        }
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        u64 A;
+        const Sh E = b2a(W, p, eq_bit(W, K, p, a.c.op, e, v, D, A, act), D, act, 64);
+        const Sh z = mult_sh(W, E, wv, zero_a(K, a.c.op, 2, e), act);
+        if (act) {
+            atomicAdd((unsigned long long *)&a.acc[(u64)(2 * p) * a.N8 + i], (unsigned long long)z.o);
+            atomicAdd((unsigned long long *)&a.acc[(u64)(2 * p + 1) * a.N8 + i], (unsigned long long)z.n);
+        }
+    }
+    W.flush(a.c.wire);
+}
+
+// out[i] = the sums (own, next) [epi 1: 2*prev[i] + sum + 1]; the sums are left at zero
+__global__ __launch_bounds__(256) void k_lit_fin(u64 *acc, u64 N, u64 N8, P6 out, P6 prev, int epi)
+{
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += (u64)gridDim.x * blockDim.x)
+        for (int p = 0; p < 3; p++) {
+            u64 *ao = &acc[(u64)(2 * p) * N8 + i], *an = &acc[(u64)(2 * p + 1) * N8 + i];
+            Sh z = { *ao, *an };
+            *ao = 0; *an = 0;
+            if (epi == 1) z = scale(ld(prev, p, i), 2) + z + pub(p, 1);
+            st(out, p, i, z);
+        }
+}
+
+// per-sample leaf flags as Boolean bits: LB[r*N8 + i] = [M[i] - base == r] and isLeaf[r]
+struct LcfArgs { KCommon c; P6 M, isLeaf, LB; u64 base; u32 nh; u64 N, N8; };
+__global__ __launch_bounds__(192) void k_lcf_bits(LcfArgs a)
+{
+    const int p = party_of_wave();
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
+    GT_FOR_TILES((u64)a.nh * a.N8) {
+        const u64 e = GT_ELEM(), r = e / a.N8, i = e % a.N8;
+        const bool act = r < a.nh && i < a.N;
+        Sh v = { 0, 0 }, g = { 0, 0 };
+        if (act) { v = ld(a.M, p, i) - pub(p, a.base + r); g = ld(a.isLeaf, p, r); }
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        u64 A;
+        Sh b = eq_bit(W, K, p, a.c.op, e, v, D, A, act);
+        b = and_bit(W, b, g, A >> 63, act);
+        if (act) st(a.LB, p, e, b);
+    }
+    W.flush(a.c.wire);
+}
+
+// Statistics counting element by element: e = (r*PW + q)*N8 + i, q = row*2dd + 2k + v the
+// position in the (1+K) x 2dd counter array (dd = d, or 1 at the label level).
+struct LitCountArgs { KCommon c; P6 LB, XT, YT; LimbSet B; u64 N, N8; u32 nh, d, dd, K; u64 *acc; };
+__global__ __launch_bounds__(192) void k_count_literal(LitCountArgs a)
+{
+    const int p = party_of_wave();
+    __shared__ u64 s_wire[GT_LWIRE_WORDS];
+    __shared__ u64 s_cnt[6];
+    Wire W; W.init(s_wire, s_cnt);
+    __shared__ u64 s_prf[3][GT_PRF_SCRATCH_WORDS];
+    const PartyKeys K = load_party_keys(a.c.keys, p, s_prf[p]);
+    const u64 PW = (u64)(1 + a.K) * 2 * a.dd, total = (u64)a.nh * PW * a.N8;
+    GT_FOR_TILES(total) {
+        const u64 e = GT_ELEM(), i = e % a.N8, rq = e / a.N8, r = rq / PW, q = rq % PW;
+        const bool act = e < total && i < a.N;
+        Sh s = { 0, 0 }, cv = { 0, 0 };
+        if (act) {
+            const u64 row = q / (2 * a.dd), k = (q % (2 * a.dd)) / 2, v = q & 1;
+            const Sh x = ld(a.XT, p, k * a.N8 + i);
+            if (row == 0) cv = v ? x : pub(p, 1) - x;
+            else {
+                const u64 col = k * a.K + (row - 1);
+                const Sh xy = { load_limbs1(a.B.m[p][0], col, i), load_limbs1(a.B.m[p][1], col, i) };
+                cv = v ? xy : ld(a.YT, p, (row - 1) * a.N8 + i) - xy;
+            }
+            s = ld(a.LB, p, r * a.N8 + i);
+        }
+        const Dealer D = dealer_of(K, p, a.c.op, e);
+        const Sh E = b2a(W, p, s, D, act, 64);
+        const Sh z = mult_sh(W, E, cv, zero_a(K, a.c.op, 2, e), act);
+        if (act) {
+            atomicAdd((unsigned long long *)&a.acc[(u64)(2 * p) * a.nh * PW + rq], (unsigned long long)z.o);
+            atomicAdd((unsigned long long *)&a.acc[(u64)(2 * p + 1) * a.nh * PW + rq], (unsigned long long)z.n);
+        }
+    }
+    W.flush(a.c.wire);
+}
+
+// compact statistics from the accumulated counter arrays (local linear operations), added
+// to the inherited ones
+__global__ __launch_bounds__(256) void k_from_paper(u64 *acc, P6 C, u32 nh, u32 d, u32 dd, u32 K, u32 CW)
+{
+    const u64 PW = (u64)(1 + K) * 2 * dd, n = (u64)nh * K;
+    for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (u64)gridDim.x * blockDim.x) {
+        const u64 r = t / K, cl = t % K;
+        for (int p = 0; p < 3; p++)
+            for (int pl = 0; pl < 2; pl++) {
+                u64 *o = acc + (u64)(2 * p + pl) * nh * PW + r * PW + (cl + 1) * 2 * dd;
+                u64 *dst = pl ? C.n[p] : C.o[p];
+                dst[r * CW + (u64)d * K + cl] += o[0] + o[1];
+                if (dd == d) for (u32 k = 0; k < d; k++) dst[r * CW + (u64)k * K + cl] += o[2 * k + 1];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // Heuristic computation by reconstruction, the host analogue of the TEE-based protocol of
 // Sec. V-B: the scorer (a fourth role, not one of the parties) reconstructs the level's C,
 // gamma and F from the three components and computes in the clear what the MPC protocol

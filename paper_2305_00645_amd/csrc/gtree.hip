@@ -78,6 +78,9 @@ struct gt_train {
     size_t N, N8;
     u32 d, K, H, CW, level, last, P2;
     bool finished;
+    bool literal;                    // learning protocol as printed (whole-tree scans, per-element SelectShare)
+    DSh LB;                          // literal mode: per-sample leaf flags as Boolean bits, n_h x N8
+    u64 *lit_acc;                    // literal mode: local sums, max(6*N8, 6*nmax*(1+K)*2d) words
     bool hc_open;                    // heuristic computation by reconstruction instead of the MPC protocol
     u64 *hcp;                        // the scorer's plain results: SD, gamma, F node, F children, split, scores
     bool fresh_import;               // state was imported and no level has run since: nothing to export for "last"
@@ -153,6 +156,7 @@ static void acct_ge(gt_ctx *c, u64 n)
     c->acc.rounds += 7;
 }
 static void acct_b2a(gt_ctx *c, u64 n) { wire_add(c, +1, n, 1); c->acc.rounds += 1; }
+static void acct_b2a_wide(gt_ctx *c, u64 n) { wire_add(c, +1, n, 64); c->acc.rounds += 1; }   // opened value sent as a ring element
 static void acct_and1(gt_ctx *c, u64 n) { wire_add(c, -1, n, 1); c->acc.rounds += 1; }
 static void acct_reshare(gt_ctx *c, u64 n, u64 words) { wire_add(c, -1, n, 64 * words); c->acc.rounds += 1; }
 
@@ -496,6 +500,8 @@ static void train_free(gt_train *t)
     for (DSh *s : all) dsh_free(*s);
     if (t->Zacc) (void)hipFree(t->Zacc);
     if (t->hcp) (void)hipFree(t->hcp);
+    if (t->lit_acc) (void)hipFree(t->lit_acc);
+    dsh_free(t->LB);
     if (t->slot) {
         if (t->slot->in_use) t->slot->orphan = true;     // the tree made from it frees it
         else { dsh_free(t->slot->feat); dsh_free(t->slot->leaf); delete t->slot; }
@@ -555,7 +561,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     size_t P2 = 1; while (P2 < d) P2 *= 2;
     t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
     t->finished = false; t->fresh_import = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr; t->slot = nullptr;
-    t->hc_open = false; t->hcp = nullptr;
+    t->hc_open = false; t->hcp = nullptr; t->literal = false; t->lit_acc = nullptr;
     hipStream_t s = c->stream;
     int rc = GT_OK;
     struct { DSh *v; size_t n; } plan[] = {
@@ -760,15 +766,97 @@ static int node_split(gt_ctx *c, gt_train *t, u32 h)
     return GT_OK;
 }
 
+// ---- the learning protocol as printed (small inputs) --------------------------------------
+static int oaa_literal(gt_ctx *c, bool rows, P6 u, u64 base, u64 w, u64 N, u64 N8, P6 W1, u64 w1off, P6 XT,
+                       u64 *acc, P6 out, P6 prev, int epi)
+{
+    LitOaaArgs a{}; a.c = kc(c, c->op++); a.u = u; a.base = base; a.w = (u32)w; a.N = N; a.N8 = N8; a.W1 = W1; a.w1off = w1off;
+    a.XT = XT; a.acc = acc;
+    const dim3 g(tiles(w * N8));
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_words, g1(6 * N8), B256, acc, (u64)(6 * N8), (u64)0));   // the counting step shares this buffer
+    GTCHK(rows ? launch(c, GT_KC_SMALL, k_oaa_literal<true>, g, GT_BLOCK, a) : launch(c, GT_KC_SMALL, k_oaa_literal<false>, g, GT_BLOCK, a));
+    GTCHK(launch(c, GT_KC_LOCAL, k_lit_fin, g1(N), B256, acc, N, N8, out, prev, epi));
+    acct_eq(c, w * N); acct_b2a_wide(c, w * N); acct_reshare(c, w * N, 1);
+    return GT_OK;
+}
+
+static int partition_literal(gt_ctx *c, gt_train *t)
+{
+    const u64 nodes = ((u64)2 << t->H) - 1;
+    GTCHK(oaa_literal(c, false, t->M.v, 0, nodes, t->N, t->N8, t->T.v, 0, t->XT.v, t->lit_acc, t->tval.v, t->M.v, 0));
+    return oaa_literal(c, true, t->tval.v, 0, t->d, t->N, t->N8, t->T.v, 0, t->XT.v, t->lit_acc, t->M.v, t->M.v, 1);
+}
+
+static int leaf_bits_literal(gt_ctx *c, gt_train *t, u32 h)
+{
+    const u64 nh = (u64)1 << h, base = nh - 1;
+    GTCHK(do_eq(c, true, t->F.v, base, nullptr, 1, t->isLeaf.v, nh));
+    LcfArgs a{}; a.c = kc(c, c->op++); a.M = t->M.v; a.isLeaf = t->isLeaf.v; a.LB = t->LB.v; a.base = base; a.nh = (u32)nh; a.N = t->N; a.N8 = t->N8;
+    GTCHK(launch(c, GT_KC_SMALL, k_lcf_bits, dim3(tiles(nh * t->N8)), GT_BLOCK, a));
+    acct_eq(c, nh * t->N); acct_and1(c, nh * t->N);
+    return GT_OK;
+}
+
+static int count_literal(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
+{
+    const u64 nh = (u64)1 << h;
+    const u32 dd = totals_only ? 1 : t->d;
+    const u64 PW = (u64)(1 + t->K) * 2 * dd;
+    GTCHK(launch(c, GT_KC_LOCAL, k_fill_words, g1(6 * nh * PW), B256, t->lit_acc, 6 * nh * PW, (u64)0));
+    LitCountArgs a{}; a.c = kc(c, c->op++); a.LB = t->LB.v; a.XT = t->XT.v; a.YT = t->YT.v; a.B = limbs_B(t); a.N = t->N; a.N8 = t->N8;
+    a.nh = (u32)nh; a.d = t->d; a.dd = dd; a.K = t->K; a.acc = t->lit_acc;
+    GTCHK(launch(c, GT_KC_SMALL, k_count_literal, dim3(tiles(nh * PW * t->N8)), GT_BLOCK, a));
+    GTCHK(launch(c, GT_KC_LOCAL, k_from_paper, g1(nh * t->K), B256, t->lit_acc, t->C.v, (u32)nh, t->d, dd, t->K, t->CW));
+    acct_b2a_wide(c, nh * PW * t->N); acct_reshare(c, nh * PW * t->N, 1);
+    return GT_OK;
+}
+
+extern "C" int gt_train_set_literal(gt_ctx *c, gt_train *t, int literal)
+{
+    if (!c || !t) return GT_EINVAL;
+    if (literal && !t->lit_acc) {
+        const size_t nmax = (size_t)1 << t->H;
+        const size_t words = std::max<size_t>(6 * t->N8, 6 * nmax * (size_t)(1 + t->K) * 2 * t->d);
+        if (nmax * t->N8 > ((size_t)1 << 31)) return GT_EINVAL;          // this mode is for small inputs
+        if (hipMalloc(&t->lit_acc, words * 8) != hipSuccess) { t->lit_acc = nullptr; return GT_ENOMEM; }
+        HIPCHK(hipMemsetAsync(t->lit_acc, 0, words * 8, c->stream));
+        GTCHK(dsh_alloc(t->LB, nmax * t->N8, c->stream));
+    }
+    t->literal = literal != 0;
+    return GT_OK;
+}
+
+extern "C" int gt_oaa_literal(gt_ctx *c, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z)
+{
+    if (!c || !shares_ok(W, w) || !shares_ok(u, n) || !shares_ok(z, n) || w == 0 || w > 0xffffffffu) return GT_EINVAL;
+    Timed T(c);
+    const size_t N8 = pad8(n), need = 6 * N8;
+    if (c->dacc_words < need) {
+        (void)hipStreamSynchronize(c->stream);
+        if (c->dacc) (void)hipFree(c->dacc);
+        c->dacc = nullptr; c->dacc_words = 0;
+        if (hipMalloc(&c->dacc, need * 8) != hipSuccess) return T.finish(GT_ENOMEM);
+        c->dacc_words = need;
+        HIPCHK(hipMemsetAsync(c->dacc, 0, need * 8, c->stream));     // both users leave it at zero
+    }
+    return T.finish(oaa_literal(c, false, to_p6(u), 0, w, n, N8, to_p6(W), 0, to_p6(W), c->dacc, to_p6(z), to_p6(z), 0));
+}
+
 extern "C" int gt_train_level(gt_ctx *c, gt_train *t, uint32_t h)
 {
     if (!c || !t) return GT_EINVAL;
     if (t->finished || h != t->level || h >= t->H) return GT_ESTATE;
     Timed T(c);
     int rc = GT_OK;
-    if (h > 0) rc = partition(c, t, h);
-    if (rc == GT_OK) rc = leaf_onehot(c, t, h);
-    if (rc == GT_OK) rc = count(c, t, h, false);
+    if (t->literal) {
+        if (h > 0) rc = partition_literal(c, t);
+        if (rc == GT_OK) rc = leaf_bits_literal(c, t, h);
+        if (rc == GT_OK) rc = count_literal(c, t, h, false);
+    } else {
+        if (h > 0) rc = partition(c, t, h);
+        if (rc == GT_OK) rc = leaf_onehot(c, t, h);
+        if (rc == GT_OK) rc = count(c, t, h, false);
+    }
     if (rc == GT_OK && t->hc_open) rc = heuristic_open(c, t, h);
     if (rc == GT_OK && !t->hc_open) rc = heuristic(c, t, h);
     if (rc == GT_OK && !t->hc_open) rc = update_flags(c, t, h);
@@ -799,9 +887,15 @@ extern "C" int gt_train_finish(gt_ctx *c, gt_train *t, gt_tree **out)
     const u32 H = t->H;
     const u64 nh = (u64)1 << H, base = nh - 1, dK = (u64)t->d * t->K;
     int rc = GT_OK;
-    if (H > 0) rc = partition(c, t, H);
-    if (rc == GT_OK) rc = leaf_onehot(c, t, H);
-    if (rc == GT_OK) rc = count(c, t, H, true);
+    if (t->literal) {
+        if (H > 0) rc = partition_literal(c, t);
+        if (rc == GT_OK) rc = leaf_bits_literal(c, t, H);
+        if (rc == GT_OK) rc = count_literal(c, t, H, true);
+    } else {
+        if (H > 0) rc = partition(c, t, H);
+        if (rc == GT_OK) rc = leaf_onehot(c, t, H);
+        if (rc == GT_OK) rc = count(c, t, H, true);
+    }
     // label = first maximum of the class totals
     if (rc == GT_OK) rc = copy6(c, t->best.v, 0, t->C.v, dK, t->CW, nh);
     if (rc == GT_OK) rc = launch(c, GT_KC_LOCAL, k_fill_const, g1(nh), B256, t->lab.v, (u64)0, nh, (u64)0);
@@ -853,6 +947,7 @@ extern "C" int gt_train_export(gt_ctx *c, const gt_train *t, int what, const gt_
     if (!c || !t) return GT_EINVAL;
     if (what < GT_X_T || what > GT_X_C_PAPER) return GT_EINVAL;
     if (t->fresh_import && of_last_level(what)) return GT_ESTATE;
+    if (t->literal && what == GT_X_L) return GT_ESTATE;               // no arithmetic one-hot exists in that mode
     const size_t n = gt_train_export_size(t, what);
     if (!shares_ok(out, n)) return GT_EINVAL;
     Timed T(c);

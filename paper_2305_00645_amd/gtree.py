@@ -92,6 +92,8 @@ def load():
         "gt_train_create": (i, [vp, S, S, sz, u32, u32, C.POINTER(vp)]),
         "gt_train_level": (i, [vp, vp, u32]),
         "gt_train_set_heuristic": (i, [vp, i]),
+        "gt_train_set_literal": (i, [vp, vp, i]),
+        "gt_oaa_literal": (i, [vp, S, sz, S, sz, S]),
         "gt_train_finish": (i, [vp, vp, C.POINTER(vp)]),
         "gt_train_destroy": (i, [vp]),
         "gt_train_export_size": (sz, [vp, i]),
@@ -292,6 +294,14 @@ class GTree:
 
     def train_reset(self, X, Y):
         _chk(self.L.gt_train_reset(self.ctx, self._train, _ref(X), _ref(Y)), "gt_train_reset")
+
+    def train_set_literal(self, literal):
+        _chk(self.L.gt_train_set_literal(self.ctx, self._train, int(bool(literal))), "gt_train_set_literal")
+
+    def oaa_literal(self, W, u):
+        z = self.new(u.n)
+        _chk(self.L.gt_oaa_literal(self.ctx, _ref(W), W.n, _ref(u), u.n, _ref(z)), "gt_oaa_literal")
+        return z
 
     def train_set_heuristic(self, by_reconstruction):
         _chk(self.L.gt_train_set_heuristic(self._train, int(bool(by_reconstruction))), "gt_train_set_heuristic")

@@ -381,6 +381,58 @@ def test_heuristic_by_reconstruction(mods, seed, case):
     tree.close(); g.close()
 
 
+@pytest.mark.parametrize("w,n", [(1, 5), (16, 513), (37, 100)])
+def test_oaa_as_printed(mods, seed, w, n):
+    """Array access element by element as the paper prints it: oracle's shares, W[u], and
+    exactly N(4l-1) bits per party counted by the kernels."""
+    o, g = pair(mods, seed)
+    rng = np.random.default_rng(w * 1000 + n)
+    Wp = rng.integers(0, M64, size=w, dtype=np.uint64)
+    u = rng.integers(0, w + 2, size=n).astype(np.uint64)
+    so, sg = (o.share(Wp), o.share(u)), (g.share_a(Wp), g.share_a(u))
+    o.stats_reset(); g.stats_reset()
+    zo, zg = o.oaa_literal(*so), g.oaa_literal(*sg)
+    same(zg, zo, "oaa as printed")
+    assert np.array_equal(g.rec(zg), np.array([Wp[int(i)] if int(i) < w else 0 for i in u], dtype=np.uint64))
+    same_stats(o, g)
+    assert int(g.wire_bits_dev()[0].sum()) == w * n * (4 * 64 - 1) and g.stats()[0] == 9
+    same(g.oaa(*sg), o.oaa(*so), "fused access after the literal one (shared scratch left clean)")
+
+
+@pytest.mark.parametrize("case", ["c1", "c2"])
+def test_learning_as_printed(mods, seed, case):
+    """Training with the learning protocol as printed (whole-tree scans, per-element
+    SelectShare, local accumulation): share by share against the oracle in the same mode, the
+    tree against the plaintext CART, the message volume against the fused mode."""
+    import plain_cart
+    from oracle import X_T, X_F, X_M, X_C, X_GAMMA, X_SD, X_SCORE
+    from paper_2305_00645_amd import workloads as wl
+    w = wl.c1_train(N=200, d=8, depth=3) if case == "c1" else wl.c2_train(H=4)
+    N, d, K, H = w["N"], w["d"], w["K"], w["H"]
+    o, g = pair(mods, seed, K=K)
+    o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, H)
+    g.train_create(g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1)), N, d, H)
+    o.train_set_literal(True); g.train_set_literal(True)
+    for h in range(H):
+        o.train_level(h); g.train_level(h)
+        for nm, what in (("M", X_M), ("C", X_C), ("SCORE", X_SCORE), ("SD", X_SD), ("GAMMA", X_GAMMA), ("F", X_F)):
+            same(g.train_export(what), o.train_export(what), "level %d %s" % (h, nm))
+    fo, lo = o.train_finish()
+    tree = g.train_finish()
+    fg, lg = tree.export()
+    same(fg, fo, "features"); same(lg, lo, "labels")
+    ref = plain_cart.train(w["X"], w["y"], K, H, 16)
+    assert np.array_equal(g.rec(g.train_export(X_T)).astype(np.int64), ref["T"])
+    same_stats(o, g)
+    g2 = mods[1].GTree(seed, K=K)
+    g2.train_create(g2.share_a(w["X"].reshape(-1)), g2.share_a(w["Y"].reshape(-1)), N, d, H)
+    for h in range(H):
+        g2.train_level(h)
+    g2.train_finish().close()
+    assert int(g.stats()[1][0].sum()) > 5 * int(g2.stats()[1][0].sum())      # what the fusion into inner products saves
+    tree.close(); g.close(); g2.close()
+
+
 def test_train_errors(mods, seed):
     Oracle, gtree = mods
     from paper_2305_00645_amd import workloads as wl
