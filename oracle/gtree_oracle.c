@@ -699,6 +699,8 @@ struct orc_train {
     int fresh_import;      /* state was imported and no level has run since: the copies are not valid */
     int hc_open;           /* heuristic computation by reconstruction instead of the MPC protocol */
     int literal;           /* learning protocol as printed: whole-T scans, per-element SelectShare */
+    int part_matmul;       /* data partition by products with the previous level's leaf one-hot */
+    u32 lt_level;          /* level whose per-sample one-hot LT holds, or (u32)-1 */
     sh LB;                 /* literal mode: per-sample leaf flags as Boolean bits, n_h x N8 */
 };
 
@@ -719,6 +721,7 @@ orc_train *orc_train_create(orc_ctx *c, const uint64_t *Xf, const uint64_t *Yf, 
     t->SD = sh_alloc(nmax); t->split = sh_alloc(nmax);
     t->Clast = sh_alloc(nmax * t->CW); t->Glast = sh_alloc(nmax * d); t->Slast = sh_alloc(nmax * d);
     t->LB = sh_alloc(0);
+    t->lt_level = (u32)-1;
     for (int j = 0; j < 3; j++) {
         for (size_t i = 0; i < N; i++) {
             for (u32 k = 0; k < d; k++) t->XT.c[j][k * N8 + i] = Xf[(size_t)j * N * d + i * d + k];
@@ -774,6 +777,72 @@ static void partition(orc_ctx *c, orc_train *t, u32 h)
     sh_free(&EA); sh_free(&Tval); sh_free(&Dval);
 }
 
+/* Data partition without per-sample equality tests (a variant beyond the paper's listing,
+ * which fetches T[M] and then D[i][T[M]] by two array accesses per sample).  The previous
+ * level has left the per-sample leaf one-hot L (of the statistics counting) and the split
+ * decisions T_{h-1}[r]; then
+ *   OH[r][k]  = [T_{h-1}[r] = k]                 n_{h-1} * d equality tests, sample-independent
+ *   sel[k][i] = sum_r L[r][i] * OH[r][k]          one reshare per (k, i)
+ *   Dval[i]   = sum_k sel[k][i] * X[k][i]          one reshare per sample
+ * and M <- 2M + Dval + 1 as before.  A sample whose node at level h-1 is not a real leaf has
+ * an all-zero one-hot, so its Dval is 0: it goes to the left child of a node that has no
+ * real leaves below it any more, which no later step can tell from the right one; for every
+ * sample in a real leaf Dval = X[i][T[M]] as in the paper.  Streams: op 1: 0 dealer, 1 masks;
+ * op 2 and 3: zero sharing of stream 0, word k*N8+i resp. i. */
+static int partition_matmul(orc_ctx *c, orc_train *t, u32 h)
+{
+    size_t N = t->N, N8 = t->N8, d = t->d, np = (size_t)1 << (h - 1), base = np - 1;
+    if (t->lt_level != h - 1) return -1;               /* needs the one-hot of the level just processed */
+    sh OH = sh_alloc(np * d), sel = sh_alloc(d * N8);
+    u32 op = c->op++;
+#pragma omp parallel for schedule(static)
+    for (size_t e = 0; e < np * d; e++) {
+        size_t r = e / d, k = e % d;
+        u64 v[3], A[3], b[3], a[3]; dealer_t D;
+        sh_get(&t->T, base + r, v);
+        v[0] -= k;
+        dealer(c, op, e, &D);
+        eq_el(c, op, e, v, &D, A, b);
+        b2a_el(b, &D, a);
+        sh_set(&OH, e, a);
+    }
+    wire_eq(c, np * d); wire_b2a(c, np * d);
+    op = c->op++;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (size_t k = 0; k < d; k++)
+        for (size_t i = 0; i < N; i++) {
+            u64 acc[3] = { 0, 0, 0 }, al[3];
+            for (size_t r = 0; r < np; r++) {
+                u64 a[3], b[3], p[3];
+                sh_get(&t->LT, r * N8 + i, a); sh_get(&OH, r * d + k, b);
+                prod3(a, b, p);
+                for (int j = 0; j < 3; j++) acc[j] += p[j];
+            }
+            zero_a(c, op, 0, k * N8 + i, al);
+            for (int j = 0; j < 3; j++) acc[j] += al[j];
+            sh_set(&sel, k * N8 + i, acc);
+        }
+    wire_reshare(c, (u64)N * d, 1);
+    op = c->op++;
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < N; i++) {
+        u64 acc[3] = { 0, 0, 0 }, al[3];
+        for (size_t k = 0; k < d; k++) {
+            u64 a[3], b[3], p[3];
+            sh_get(&sel, k * N8 + i, a); sh_get(&t->XT, k * N8 + i, b);
+            prod3(a, b, p);
+            for (int j = 0; j < 3; j++) acc[j] += p[j];
+        }
+        zero_a(c, op, 0, i, al);
+        for (int j = 0; j < 3; j++) t->M.c[j][i] = 2 * t->M.c[j][i] + acc[j] + al[j] + (j == 0 ? 1 : 0);
+    }
+    wire_reshare(c, N, 1);
+    sh_free(&OH); sh_free(&sel);
+    return 0;
+}
+
+void orc_train_set_partition(orc_train *t, int by_products) { t->part_matmul = by_products ? 1 : 0; }
+
 /* Leaf flags and per-sample one-hot of the statistics-counting step. */
 static void leaf_onehot(orc_ctx *c, orc_train *t, u32 h)
 {
@@ -790,6 +859,7 @@ static void leaf_onehot(orc_ctx *c, orc_train *t, u32 h)
     wire_eq(c, nh);
     op = c->op++;
     eq_grid(c, op, &t->M, base, nh, t->N, &t->isLeaf, &t->LT);
+    t->lt_level = h;
 }
 
 /* counts[r][col] += sum_i L[r][i] * B[col][i] for columns [col0, col1) of the
@@ -1197,7 +1267,8 @@ int orc_train_level(orc_ctx *c, orc_train *t, uint32_t h)
         leaf_bits_literal(c, t, h);
         count_literal(c, t, h, 0);
     } else {
-        if (h > 0) partition(c, t, h);
+        if (h > 0 && t->part_matmul) { if (partition_matmul(c, t, h)) return -1; }
+        else if (h > 0) partition(c, t, h);
         leaf_onehot(c, t, h);
         count(c, t, h, 0);
     }
@@ -1222,7 +1293,8 @@ int orc_train_finish(orc_ctx *c, orc_train *t, uint64_t *feat, uint64_t *leaf)
         leaf_bits_literal(c, t, H);
         count_literal(c, t, H, 1);
     } else {
-        if (H > 0) partition(c, t, H);
+        if (H > 0 && t->part_matmul) { if (partition_matmul(c, t, H)) return -1; }
+        else if (H > 0) partition(c, t, H);
         leaf_onehot(c, t, H);
         count(c, t, H, 1);
     }
@@ -1324,6 +1396,7 @@ int orc_train_import(orc_train *t, uint32_t h, const uint64_t *M, const uint64_t
     }
     t->level = h;
     t->fresh_import = 1;
+    t->lt_level = (u32)-1;
     return 0;
 }
 

@@ -108,6 +108,11 @@ void orc_oaa_literal(orc_ctx *c, const uint64_t *W, size_t w, const uint64_t *u,
  * per-sample counter arrays and local accumulation.  Same reconstructed state; X_L is not
  * exported in this mode.  For small inputs only. */
 void orc_train_set_literal(orc_train *t, int literal);
+/* Data partition of the following levels by products with the previous level's per-sample
+ * leaf one-hot instead of two array accesses per sample (see partition_matmul in the source):
+ * same M for every sample that sits in a real leaf, same tree, N*d*64 + N*64 bits per party
+ * instead of N*(n_{h-1} + d)*128.  Needs the previous level to have run in this object. */
+void orc_train_set_partition(orc_train *t, int by_products);
 /* Heuristic computation of the following levels by reconstruction (host analogue of the
  * TEE-based protocol of Sec. V-B: a scorer reconstructs C, gamma, F, scores in the clear with
  * the same fixed-point rule and hands back fresh sharings) instead of the MPC protocol. */

@@ -52,6 +52,7 @@ def _load():
         "orc_stats_scorer": (None, [vp, _u64p]),
         "orc_train_set_heuristic": (None, [vp, i]),
         "orc_train_set_literal": (None, [vp, i]),
+        "orc_train_set_partition": (None, [vp, i]),
         "orc_oaa_literal": (None, [vp, _u64p, sz, _u64p, sz, _u64p]),
         "orc_stats_reset": (None, [vp]),
         "orc_op_counter": (u32, [vp]),
@@ -260,6 +261,9 @@ class Oracle:
             self.L.orc_train_destroy(self._train)
         self._train = self.L.orc_train_create(self.ctx, _p(X.reshape(-1)), _p(Y.reshape(-1)), N, d, H)
         self._tshape = (N, d, H)
+
+    def train_set_partition(self, by_products):
+        self.L.orc_train_set_partition(self._train, int(bool(by_products)))
 
     def train_set_literal(self, literal):
         self.L.orc_train_set_literal(self._train, int(bool(literal)))

@@ -11,7 +11,23 @@ from paper_2305_00645_amd import workloads as wl
 M64 = (1 << 64) - 1
 
 
-def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstruction=False, literal=False):
+def expected_M_by_products(ref, w, H):
+    """M per level when the partition uses the previous level's leaf one-hot: a sample moves by
+    its feature value only while it sits in a real leaf; below a node that stopped being one it
+    keeps going left."""
+    X = np.asarray(w["X"]).astype(np.int64)
+    N = X.shape[0]
+    M = np.zeros(N, dtype=np.int64)
+    out = [M.copy()]
+    for h in range(1, H + 1):
+        prev = M - ((1 << (h - 1)) - 1)
+        real = np.array([_was_leaf(ref, h - 1, int(r)) for r in prev])
+        M = 2 * M + 1 + np.where(real, X[np.arange(N), ref["T"][M]], 0)
+        out.append(M.copy())
+    return out
+
+
+def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstruction=False, literal=False, by_products=False):
     H = w["H"] if H is None else H
     N, d, K = w["N"], w["d"], w["K"]
     o = Oracle(seed, tau=tau, K=K)
@@ -19,7 +35,9 @@ def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstructi
     o.train_create(sx, sy, N, d, H)
     o.train_set_heuristic(by_reconstruction)
     o.train_set_literal(literal)
+    o.train_set_partition(by_products)
     ref = plain_cart.train(w["X"], w["y"], K, H, tau)
+    Mexp = expected_M_by_products(ref, w, H) if by_products else [ref["levels"][h]["M"] for h in range(H + 1)]
     CW = d * K + K
     for h in range(H):
         o.train_level(h)
@@ -27,7 +45,7 @@ def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstructi
             continue
         nh = 1 << h
         L = ref["levels"][h]
-        assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), L["M"])
+        assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), Mexp[h])
         C = Oracle.rec(o.train_export(X_C)).astype(np.int64).reshape(nh, CW)
         for r in range(nh):
             assert np.array_equal(C[r, :d * K].reshape(d, K), L["n1"][r]), (h, r)
@@ -42,7 +60,7 @@ def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstructi
         # per-sample leaf one-hot: 1 exactly at the sample's node when that node is a real leaf
         LT = Oracle.rec(o.train_export(X_L)).astype(np.int64).reshape(nh, -1)[:, :N]
         Fbefore = np.array([1 if (L["split"][r] or _was_leaf(ref, h, r)) else 0 for r in range(nh)])
-        want = ((L["M"][None, :] - (nh - 1)) == np.arange(nh)[:, None]) & (Fbefore[:, None] == 1)
+        want = ((Mexp[h][None, :] - (nh - 1)) == np.arange(nh)[:, None]) & (Fbefore[:, None] == 1)
         assert np.array_equal(LT, want.astype(np.int64))
     feat, leaf = o.train_finish()
     T = Oracle.rec(o.train_export(X_T)).astype(np.int64)
@@ -51,7 +69,7 @@ def run_oracle_train(seed, w, tau=16, H=None, check_levels=True, by_reconstructi
     assert np.array_equal(F, ref["F"])
     assert np.array_equal(Oracle.rec(feat).astype(np.int64), ref["T"][:(1 << H) - 1])
     assert np.array_equal(Oracle.rec(leaf).astype(np.int64), ref["T"][(1 << H) - 1:])
-    assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), ref["levels"][H]["M"])
+    assert np.array_equal(Oracle.rec(o.train_export(X_M)).astype(np.int64), Mexp[H])
     return o, ref, (feat, leaf)
 
 
@@ -196,6 +214,44 @@ def test_learning_protocol_as_printed_matches_plaintext_and_cost_formula(seed):
         fused += nh * (2 * l - 1) + N * nh * (2 * l + 1) + nh * (K if h == H else CW) * l
     assert int(o.wire_bits()[0].sum()) - int(o2.wire_bits()[0].sum()) == lit - fused
     run_oracle_train(seed, wl.c2_train(N=80, d=7, H=3), literal=True)
+
+
+def test_partition_by_products_matches_plaintext_cart(seed):
+    """Data partition by products with the previous level's leaf one-hot: statistics, scores,
+    split decisions, node types, tree and labels equal the plaintext CART level by level; M
+    equals the paper's recurrence for every sample in a real leaf (and goes left below a node
+    that stopped being one); the partition costs N*d*l + N*l bits plus n_{h-1}*d equality tests
+    with conversion instead of N*(n_{h-1} + d)*2l + 2*N*l."""
+    w = wl.c1_train()
+    N, d, K, H, l = w["N"], w["d"], w["K"], w["H"], 64
+    o, ref, _ = run_oracle_train(seed, w, by_products=True)
+    o2, _, _ = run_oracle_train(seed, w)
+    assert np.array_equal(Oracle.rec(o.train_export(X_T)), Oracle.rec(o2.train_export(X_T)))
+    saved = 0
+    for h in range(1, H + 1):
+        npv = 1 << (h - 1)
+        saved += (N * (npv + d) * 2 * l + 2 * N * l) - (npv * d * 2 * l + N * d * l + N * l)
+    assert int(o2.wire_bits()[0].sum()) - int(o.wire_bits()[0].sum()) == saved
+    assert o.stats()[0] == o2.stats()[0] - H * (18 - 10)           # two array accesses of 9 rounds against 7 + 1 + 1 + 1
+    run_oracle_train(seed, wl.c2_train(), H=5, by_products=True)          # has nodes that stop early
+    rng = np.random.default_rng(77)
+    N, d, K = 150, 9, 4
+    X = (rng.random((N, d)) < 0.4).astype(np.uint64)
+    y = (X[:, 0].astype(np.int64) * 2 + X[:, 3].astype(np.int64) + (rng.random(N) < 0.1)) % K
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), tau=10, by_products=True)
+    X = np.array([[0, 1], [1, 1], [1, 0], [0, 0], [1, 1]], dtype=np.uint64)
+    y = np.ones(5, dtype=np.int64)
+    Y = np.zeros((5, 2), dtype=np.uint64); Y[:, 1] = 1
+    run_oracle_train(seed, dict(X=X, Y=Y, y=y, N=5, d=2, K=2, H=2), by_products=True)
+    # a state that was imported has no one-hot of the previous level: the level is refused
+    wi = wl.c5_level(N=50, d=4, K=2, h=2)
+    oi = Oracle(seed, K=2)
+    oi.train_create(oi.share(wi["X"].reshape(-1)), oi.share(wi["Y"].reshape(-1)), 50, 4, 3)
+    oi.train_set_partition(True)
+    oi.train_import(2, *[oi.share(a) for a in (wi["M"], wi["Tprev"], wi["F"], np.zeros(4 * 10, dtype=np.uint64), wi["gamma"].reshape(-1))])
+    with pytest.raises(RuntimeError):
+        oi.train_level(2)
 
 
 def test_counter_array_paper_layout(seed):
