@@ -178,6 +178,15 @@ int gt_train_finish(gt_ctx *ctx, gt_train *tr, gt_tree **out);
  * the dealer's key.  Same reconstructed SD, gamma, F, T as the MPC heuristic; two rounds.
  * There is no enclave here: the scorer sees the statistics in the clear. */
 int gt_train_set_heuristic(gt_train *tr, int by_reconstruction);
+/* Data partition of the following levels by products with the previous level's per-sample
+ * leaf one-hot (a variant beyond the paper's listing, which makes two array accesses per
+ * sample): OH[r][k] = [T_{h-1}[r] = k] (n_{h-1}*d equality tests, sample-independent),
+ * sel[k][i] = sum_r L[r][i] OH[r][k], Dval[i] = sum_k sel[k][i] X[i][k], M <- 2M + Dval + 1.
+ * Per party N*d*64 + N*64 bits instead of N*(n_{h-1} + d)*128 + 2*N*64, 10 rounds instead
+ * of 18.  Same tree and statistics; M equals the paper's for every sample in a real leaf (a
+ * sample below a node that stopped being one keeps going left).  The level before must have
+ * run in this object (GT_ESTATE after gt_train_import).  The first call allocates d*N8 shares. */
+int gt_train_set_partition(gt_ctx *ctx, gt_train *tr, int by_products);
 /* Learning protocol of the following levels as printed (Sec. V-B, Alg. "Oblivious
  * Learning"): array access over the whole tree array, a SelectShare per element of the
  * per-sample (1+K) x 2d counter arrays, local accumulation - instead of the level slice and

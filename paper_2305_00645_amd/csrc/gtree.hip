@@ -78,6 +78,9 @@ struct gt_train {
     size_t N, N8;
     u32 d, K, H, CW, level, last, P2;
     bool finished;
+    bool part_matmul;                // data partition by products with the previous level's leaf one-hot
+    u32 lt_level;                    // level whose leaf one-hot the limb tiles LQ hold, or ~0u
+    DSh OH, SEL;                     // partition by products: one-hot of the split decisions, selected columns d x N8
     bool literal;                    // learning protocol as printed (whole-tree scans, per-element SelectShare)
     DSh LB;                          // literal mode: per-sample leaf flags as Boolean bits, n_h x N8
     u64 *lit_acc;                    // literal mode: local sums, max(6*N8, 6*nmax*(1+K)*2d) words
@@ -501,7 +504,7 @@ static void train_free(gt_train *t)
     if (t->Zacc) (void)hipFree(t->Zacc);
     if (t->hcp) (void)hipFree(t->hcp);
     if (t->lit_acc) (void)hipFree(t->lit_acc);
-    dsh_free(t->LB);
+    dsh_free(t->LB); dsh_free(t->OH); dsh_free(t->SEL);
     if (t->slot) {
         if (t->slot->in_use) t->slot->orphan = true;     // the tree made from it frees it
         else { dsh_free(t->slot->feat); dsh_free(t->slot->leaf); delete t->slot; }
@@ -544,7 +547,7 @@ static int train_start(gt_ctx *c, gt_train *t, const gt_shares *X, const gt_shar
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(nmax * t->CW), B256, t->C.v, (u64)0, (u64)(nmax * t->CW), (u64)0));
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, dim3(1), B256, t->F.v, (u64)0, (u64)1, (u64)1));
     GTCHK(launch(c, GT_KC_LOCAL, k_fill_const, g1(d), B256, t->gamma.v, (u64)0, (u64)d, (u64)1));
-    t->level = 0; t->last = 0; t->finished = false; t->fresh_import = false;
+    t->level = 0; t->last = 0; t->finished = false; t->fresh_import = false; t->lt_level = ~0u;
     return GT_OK;
 }
 
@@ -561,7 +564,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     size_t P2 = 1; while (P2 < d) P2 *= 2;
     t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
     t->finished = false; t->fresh_import = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr; t->slot = nullptr;
-    t->hc_open = false; t->hcp = nullptr; t->literal = false; t->lit_acc = nullptr;
+    t->hc_open = false; t->hcp = nullptr; t->literal = false; t->lit_acc = nullptr; t->part_matmul = false; t->lt_level = ~0u;
     hipStream_t s = c->stream;
     int rc = GT_OK;
     struct { DSh *v; size_t n; } plan[] = {
@@ -630,7 +633,27 @@ static int leaf_onehot(gt_ctx *c, gt_train *t, u32 h)
     GTCHK(do_eq(c, true, t->F.v, base, nullptr, 1, t->isLeaf.v, nh));
     GridArgs a{}; a.u = t->M.v; a.base = base; a.w = (u32)nh; a.N = t->N; a.N8 = t->N8;
     a.g = t->isLeaf.v; a.L = limbs_L(t);
-    return do_grid(c, GM_STORE, true, 1, a);
+    GTCHK(do_grid(c, GM_STORE, true, 1, a));
+    t->lt_level = h;
+    return GT_OK;
+}
+
+// data partition by products: OH = onehot(T level h-1), sel = L^T OH, M <- 2M + <sel, X> + 1
+static int partition_matmul(gt_ctx *c, gt_train *t, u32 h)
+{
+    if (t->lt_level != h - 1) return GT_ESTATE;         // needs the one-hot of the level just processed
+    const u64 np = (u64)1 << (h - 1), base = np - 1, d = t->d, N = t->N;
+    OnehotArgs oa{}; oa.c = kc(c, c->op++); oa.T = t->T.v; oa.OH = t->OH.v; oa.base = base; oa.n = np * d; oa.d = t->d;
+    GTCHK(launch(c, GT_KC_SMALL, k_onehot, dim3(tiles(np * d)), GT_BLOCK, oa));
+    acct_eq(c, np * d); acct_b2a(c, np * d);
+    ColselArgs ca{}; ca.c = kc(c, c->op++); ca.L = limbs_L(t); ca.OH = t->OH.v; ca.sel = t->SEL.v; ca.N = N; ca.N8 = t->N8; ca.np = (u32)np; ca.d = t->d;
+    const u64 items = ((t->N8 / 8 + GT_LANES - 1) / GT_LANES) * ((d + GT_COLSEL_COLS - 1) / GT_COLSEL_COLS);
+    GTCHK(launch(c, GT_KC_MULT, k_colsel, dim3((unsigned)std::min<u64>(items, GT_MAX_BLOCKS)), GT_BLOCK, ca));
+    acct_reshare(c, N * d, 1);
+    RowdotArgs ra{}; ra.c = kc(c, c->op++); ra.sel = t->SEL.v; ra.XT = t->XT.v; ra.M = t->M.v; ra.N = N; ra.N8 = t->N8; ra.d = t->d;
+    GTCHK(launch(c, GT_KC_MULT, k_rowdot, dim3(tiles8(t->N8)), GT_BLOCK, ra));
+    acct_reshare(c, N, 1);
+    return GT_OK;
 }
 
 static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
@@ -811,6 +834,17 @@ static int count_literal(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     return GT_OK;
 }
 
+extern "C" int gt_train_set_partition(gt_ctx *c, gt_train *t, int by_products)
+{
+    if (!c || !t) return GT_EINVAL;
+    if (by_products && !t->SEL.base) {
+        GTCHK(dsh_alloc(t->OH, ((size_t)1 << t->H) * t->d, c->stream));
+        GTCHK(dsh_alloc(t->SEL, (size_t)t->d * t->N8, c->stream));
+    }
+    t->part_matmul = by_products != 0;
+    return GT_OK;
+}
+
 extern "C" int gt_train_set_literal(gt_ctx *c, gt_train *t, int literal)
 {
     if (!c || !t) return GT_EINVAL;
@@ -853,7 +887,7 @@ extern "C" int gt_train_level(gt_ctx *c, gt_train *t, uint32_t h)
         if (rc == GT_OK) rc = leaf_bits_literal(c, t, h);
         if (rc == GT_OK) rc = count_literal(c, t, h, false);
     } else {
-        if (h > 0) rc = partition(c, t, h);
+        if (h > 0) rc = t->part_matmul ? partition_matmul(c, t, h) : partition(c, t, h);
         if (rc == GT_OK) rc = leaf_onehot(c, t, h);
         if (rc == GT_OK) rc = count(c, t, h, false);
     }
@@ -892,7 +926,7 @@ extern "C" int gt_train_finish(gt_ctx *c, gt_train *t, gt_tree **out)
         if (rc == GT_OK) rc = leaf_bits_literal(c, t, H);
         if (rc == GT_OK) rc = count_literal(c, t, H, true);
     } else {
-        if (H > 0) rc = partition(c, t, H);
+        if (H > 0) rc = t->part_matmul ? partition_matmul(c, t, H) : partition(c, t, H);
         if (rc == GT_OK) rc = leaf_onehot(c, t, H);
         if (rc == GT_OK) rc = count(c, t, H, true);
     }
@@ -986,7 +1020,7 @@ extern "C" int gt_train_import(gt_ctx *c, gt_train *t, uint32_t h, const gt_shar
     if (rc == GT_OK) rc = copy6(c, t->F.v, base, to_p6(Fl), 0, 1, nh);
     if (rc == GT_OK) rc = copy6(c, t->C.v, 0, to_p6(Cc), 0, 1, nh * t->CW);
     if (rc == GT_OK) rc = copy6(c, t->gamma.v, 0, to_p6(gm), 0, 1, nh * t->d);
-    if (rc == GT_OK) { t->level = h; t->finished = false; t->fresh_import = true; }
+    if (rc == GT_OK) { t->level = h; t->finished = false; t->fresh_import = true; t->lt_level = ~0u; }
     return T.finish(rc);
 }
 

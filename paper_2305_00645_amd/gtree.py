@@ -93,6 +93,7 @@ def load():
         "gt_train_level": (i, [vp, vp, u32]),
         "gt_train_set_heuristic": (i, [vp, i]),
         "gt_train_set_literal": (i, [vp, vp, i]),
+        "gt_train_set_partition": (i, [vp, vp, i]),
         "gt_oaa_literal": (i, [vp, S, sz, S, sz, S]),
         "gt_train_finish": (i, [vp, vp, C.POINTER(vp)]),
         "gt_train_destroy": (i, [vp]),
@@ -294,6 +295,9 @@ class GTree:
 
     def train_reset(self, X, Y):
         _chk(self.L.gt_train_reset(self.ctx, self._train, _ref(X), _ref(Y)), "gt_train_reset")
+
+    def train_set_partition(self, by_products):
+        _chk(self.L.gt_train_set_partition(self.ctx, self._train, int(bool(by_products))), "gt_train_set_partition")
 
     def train_set_literal(self, literal):
         _chk(self.L.gt_train_set_literal(self.ctx, self._train, int(bool(literal))), "gt_train_set_literal")

@@ -433,6 +433,47 @@ def test_learning_as_printed(mods, seed, case):
     tree.close(); g.close(); g2.close()
 
 
+@pytest.mark.parametrize("case", ["c1", "c2", "multi", "c3small"])
+def test_partition_by_products(mods, seed, case):
+    """Data partition by products with the previous level's leaf one-hot: share by share
+    against the oracle in the same mode at every level, the tree against the plaintext CART."""
+    import plain_cart
+    from oracle import X_T, X_F, X_M, X_C, X_GAMMA, X_SD, X_SCORE, X_L
+    from paper_2305_00645_amd import workloads as wl
+    tau = 16
+    if case == "c1":
+        w = wl.c1_train()
+    elif case == "c2":
+        w = wl.c2_train(H=6)
+    elif case == "c3small":
+        w = wl.c3_train(N=3000, H=4, n_thr=8)
+    else:
+        rng = np.random.default_rng(77)
+        N, d, K = 203, 9, 4
+        X = (rng.random((N, d)) < 0.4).astype(np.uint64)
+        y = (X[:, 0].astype(np.int64) * 2 + X[:, 3].astype(np.int64) + (rng.random(N) < 0.1)) % K
+        Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+        w, tau = dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), 10
+    N, d, K, H = w["N"], w["d"], w["K"], w["H"]
+    o, g = pair(mods, seed, tau=tau, K=K)
+    o.train_create(o.share(w["X"].reshape(-1)), o.share(w["Y"].reshape(-1)), N, d, H)
+    g.train_create(g.share_a(w["X"].reshape(-1)), g.share_a(w["Y"].reshape(-1)), N, d, H)
+    o.train_set_partition(True); g.train_set_partition(True)
+    for h in range(H):
+        o.train_level(h); g.train_level(h)
+        for nm, what in (("M", X_M), ("L", X_L), ("C", X_C), ("SCORE", X_SCORE), ("SD", X_SD), ("GAMMA", X_GAMMA), ("F", X_F)):
+            same(g.train_export(what), o.train_export(what), "level %d %s" % (h, nm))
+    fo, lo = o.train_finish()
+    tree = g.train_finish()
+    fg, lg = tree.export()
+    same(fg, fo, "features"); same(lg, lo, "labels")
+    same(g.train_export(X_M), o.train_export(X_M), "M at the label level")
+    ref = plain_cart.train(w["X"], w["y"], K, H, tau)
+    assert np.array_equal(g.rec(g.train_export(X_T)).astype(np.int64), ref["T"])
+    same_stats(o, g)
+    tree.close(); g.close()
+
+
 def test_train_errors(mods, seed):
     Oracle, gtree = mods
     from paper_2305_00645_amd import workloads as wl
