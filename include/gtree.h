@@ -105,7 +105,8 @@ enum {
     GT_KC_EQGRID_ROWS = 6,  /* equality grid with inner product against the sample's own row */
     GT_KC_EQGRID_STORE = 7, /* equality grid that stores the per-sample leaf one-hot */
     GT_KC_INFER = 8,        /* one-launch inference */
-    GT_KC_N = 9
+    GT_KC_PARTMM = 9,       /* data partition by products on the matrix cores */
+    GT_KC_N = 10
 };
 typedef struct { double ms[GT_KC_N]; uint64_t launches[GT_KC_N]; } gt_prof;
 
@@ -185,7 +186,8 @@ int gt_train_set_heuristic(gt_train *tr, int by_reconstruction);
  * Per party N*d*64 + N*64 bits instead of N*(n_{h-1} + d)*128 + 2*N*64, 10 rounds instead
  * of 18.  Same tree and statistics; M equals the paper's for every sample in a real leaf (a
  * sample below a node that stopped being one keeps going left).  The level before must have
- * run in this object (GT_ESTATE after gt_train_import).  The first call allocates d*N8 shares. */
+ * run in this object (GT_ESTATE after gt_train_import).  Depth at most 13.  The first call
+ * allocates the operand buffers (48 * d * 2^(H-1) bytes). */
 int gt_train_set_partition(gt_ctx *ctx, gt_train *tr, int by_products);
 /* Learning protocol of the following levels as printed (Sec. V-B, Alg. "Oblivious
  * Learning"): array access over the whole tree array, a SelectShare per element of the

@@ -213,18 +213,6 @@ __device__ __forceinline__ void store_limbs8(const LimbMat &m, u64 row, u64 i0, 
     for (int sl = 0; sl < 8; sl++) *(u64 *)(m.base + limb_addr(m, ib, sl, row) + off) = y[sl];
 }
 
-// the values of 8 consecutive samples (first one i0, a multiple of 8) of a row
-__device__ __forceinline__ void load_limbs8(const LimbMat &m, u64 row, u64 i0, u64 (&x)[8])
-{
-    const u64 ib = i0 >> 5;
-    const u32 off = (u32)i0 & 31;
-#pragma unroll
-    for (int sl = 0; sl < 8; sl++) x[sl] = *(const u64 *)(m.base + limb_addr(m, ib, sl, row) + off);
-    transpose8x8(x);
-#pragma unroll
-    for (int j = 0; j < 8; j++) x[j] = (x[j] ^ GT_BIAS) - GT_BIAS;
-}
-
 // value of sample i of a row
 __device__ __forceinline__ u64 load_limbs1(const LimbMat &m, u64 row, u64 i)
 {
@@ -1040,9 +1028,10 @@ __global__ __launch_bounds__(192) void k_split(SplitArgs a)
 // ---------------------------------------------------------------------------------
 // Data partition by products with the previous level's per-sample leaf one-hot (a variant
 // beyond the paper's listing: no per-sample equality tests).
-//   k_onehot : OH[r*d + k] = [T[base + r] == k] as an arithmetic sharing
-//   k_colsel : sel[k][i] = sum_r L[r][i] * OH[r][k], zero sharing of stream 0, word k*N8+i
-//   k_rowdot : M[i] <- 2 M[i] + sum_k sel[k][i] * X[k][i] + 1, zero sharing of stream 0, word i
+//   k_onehot  : OH[r*d + k] = [T[base + r] == k] as an arithmetic sharing
+//   k_part_mm : sel[k][i] = sum_r L[r][i] * OH[r][k], zero sharing of stream 0, word k*N8+i, and
+//               M[i] <- 2 M[i] + sum_k sel[k][i] * X[k][i] + 1, zero sharing of stream 0, word i
+//               (gt_partmm.hpp, on the matrix cores)
 struct OnehotArgs { KCommon c; P6 T, OH; u64 base, n; u32 d; };
 __global__ __launch_bounds__(192) void k_onehot(OnehotArgs a)
 {
@@ -1061,96 +1050,6 @@ __global__ __launch_bounds__(192) void k_onehot(OnehotArgs a)
         u64 A;
         const Sh oh = b2a(W, p, eq_bit(W, K, p, a.c.op, e, v, D, A, act), D, act);
         if (act) st(a.OH, p, e, oh);
-    }
-    W.flush(a.c.wire);
-}
-
-// A lane owns 8 consecutive samples and COLS adjacent columns; the one-hot rows are read
-// from the limb tiles that the leaf grid of the previous level wrote (own+next, own).
-#define GT_COLSEL_COLS 4
-struct ColselArgs { KCommon c; LimbSet L; P6 OH, sel; u64 N, N8; u32 np, d; };
-__global__ __launch_bounds__(192) void k_colsel(ColselArgs a)
-{
-    const int p = party_of_wave(), lane = threadIdx.x;
-    __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    __shared__ u64 s_cnt[6];
-    Wire W; W.init(s_wire, s_cnt);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
-    const u64 ngrp = a.N8 / 8, nt = (ngrp + GT_LANES - 1) / GT_LANES, nq = (a.d + GT_COLSEL_COLS - 1) / GT_COLSEL_COLS;
-    for (u64 item = blockIdx.x; item < nt * nq; item += gridDim.x) {
-        const u64 tile = item / nq, k0 = (item % nq) * GT_COLSEL_COLS;
-        const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
-        const bool actg = grp < ngrp;
-        u64 acc[GT_COLSEL_COLS][8];
-#pragma unroll
-        for (int q = 0; q < GT_COLSEL_COLS; q++)
-#pragma unroll
-            for (int s = 0; s < 8; s++) acc[q][s] = 0;
-        if (actg)
-            for (u32 r = 0; r < a.np; r++) {
-                u64 Ls[8], Lo[8];
-                load_limbs8(a.L.m[p][0], r, i0, Ls);          // own + next component
-                load_limbs8(a.L.m[p][1], r, i0, Lo);          // own component
-#pragma unroll
-                for (int q = 0; q < GT_COLSEL_COLS; q++) {
-                    const u64 k = k0 + q < a.d ? k0 + q : a.d - 1;
-                    const Sh oh = ld(a.OH, p, (u64)r * a.d + k);
-#pragma unroll
-                    for (int s = 0; s < 8; s++) acc[q][s] += Ls[s] * oh.o + Lo[s] * oh.n;
-                }
-            }
-#pragma unroll
-        for (int q = 0; q < GT_COLSEL_COLS; q++) {
-            const u64 k = k0 + q;
-            const bool act = actg && k < a.d;
-            const u64 blk = ((act ? k : 0) * a.N8 + (actg ? i0 : 0)) >> 3;
-            u64 ao[8], an[8], snd[8], rcv[8];
-            chacha8(K.own, blk, a.c.op, 0, ao);
-            chacha8(K.nxt, blk, a.c.op, 0, an);
-#pragma unroll
-            for (int s = 0; s < 8; s++) snd[s] = acc[q][s] + (ao[s] - an[s]);
-            W.reshare<8>(snd, rcv, act ? 64u * live8(i0, a.N) : 0u);
-            if (act)
-#pragma unroll
-                for (int s = 0; s < 8; s++)
-                    if (i0 + s < a.N) { Sh z = { snd[s], rcv[s] }; st(a.sel, p, k * a.N8 + i0 + s, z); }
-        }
-    }
-    W.flush(a.c.wire);
-}
-
-struct RowdotArgs { KCommon c; P6 sel, XT, M; u64 N, N8; u32 d; };
-__global__ __launch_bounds__(192) void k_rowdot(RowdotArgs a)
-{
-    const int p = party_of_wave(), lane = threadIdx.x;
-    __shared__ u64 s_wire[GT_LWIRE_WORDS];
-    __shared__ u64 s_cnt[6];
-    Wire W; W.init(s_wire, s_cnt);
-    const PartyKeys K = load_party_keys(a.c.keys, p);
-    const u64 ngrp = a.N8 / 8;
-    const Sh one = pub(p, 1);
-    for (u64 tile = blockIdx.x, nt = (ngrp + GT_LANES - 1) / GT_LANES; tile < nt; tile += gridDim.x) {
-        const u64 grp = tile * GT_LANES + lane, i0 = grp * 8;
-        const u64 nv = grp < ngrp ? a.N : 0;
-        u64 acc[8];
-#pragma unroll
-        for (int s = 0; s < 8; s++) acc[s] = 0;
-        for (u32 k = 0; k < a.d; k++) {
-            u64 so[8], sn[8], xo[8], xn[8];
-            ld8(own_of(a.sel, p) + (u64)k * a.N8, i0, nv, so); ld8(nxt_of(a.sel, p) + (u64)k * a.N8, i0, nv, sn);
-            ld8(own_of(a.XT, p) + (u64)k * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + (u64)k * a.N8, i0, nv, xn);
-#pragma unroll
-            for (int s = 0; s < 8; s++) { const Sh e = { so[s], sn[s] }, x = { xo[s], xn[s] }; acc[s] += prod3(e, x); }
-        }
-        u64 ao[8], an[8], snd[8], rcv[8];
-        chacha8(K.own, grp, a.c.op, 0, ao);
-        chacha8(K.nxt, grp, a.c.op, 0, an);
-#pragma unroll
-        for (int s = 0; s < 8; s++) snd[s] = acc[s] + (ao[s] - an[s]);
-        W.reshare<8>(snd, rcv, 64u * live8(i0, nv));
-#pragma unroll
-        for (int s = 0; s < 8; s++)
-            if (i0 + s < nv) { Sh z = { snd[s], rcv[s] }; st(a.M, p, i0 + s, scale(ld(a.M, p, i0 + s), 2) + z + one); }
     }
     W.flush(a.c.wire);
 }

@@ -3,6 +3,7 @@
 #include "gtree.h"
 #include "gt_kernels.hpp"
 #include "gt_infer.hpp"
+#include "gt_partmm.hpp"
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
@@ -80,7 +81,8 @@ struct gt_train {
     bool finished;
     bool part_matmul;                // data partition by products with the previous level's leaf one-hot
     u32 lt_level;                    // level whose leaf one-hot the limb tiles LQ hold, or ~0u
-    DSh OH, SEL;                     // partition by products: one-hot of the split decisions, selected columns d x N8
+    DSh OH;                          // partition by products: one-hot of the split decisions
+    unsigned char *OHL;              // ... and its limb bytes, the matrix cores' operand
     bool literal;                    // learning protocol as printed (whole-tree scans, per-element SelectShare)
     DSh LB;                          // literal mode: per-sample leaf flags as Boolean bits, n_h x N8
     u64 *lit_acc;                    // literal mode: local sums, max(6*N8, 6*nmax*(1+K)*2d) words
@@ -504,7 +506,8 @@ static void train_free(gt_train *t)
     if (t->Zacc) (void)hipFree(t->Zacc);
     if (t->hcp) (void)hipFree(t->hcp);
     if (t->lit_acc) (void)hipFree(t->lit_acc);
-    dsh_free(t->LB); dsh_free(t->OH); dsh_free(t->SEL);
+    dsh_free(t->LB); dsh_free(t->OH);
+    if (t->OHL) (void)hipFree(t->OHL);
     if (t->slot) {
         if (t->slot->in_use) t->slot->orphan = true;     // the tree made from it frees it
         else { dsh_free(t->slot->feat); dsh_free(t->slot->leaf); delete t->slot; }
@@ -564,7 +567,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     size_t P2 = 1; while (P2 < d) P2 *= 2;
     t->N = N; t->N8 = N8; t->d = d; t->K = K; t->H = H; t->CW = (u32)CW; t->level = 0; t->last = 0; t->P2 = (u32)P2;
     t->finished = false; t->fresh_import = false; t->Zacc = nullptr; t->LQ = nullptr; t->BQ = nullptr; t->slot = nullptr;
-    t->hc_open = false; t->hcp = nullptr; t->literal = false; t->lit_acc = nullptr; t->part_matmul = false; t->lt_level = ~0u;
+    t->hc_open = false; t->hcp = nullptr; t->literal = false; t->lit_acc = nullptr; t->part_matmul = false; t->lt_level = ~0u; t->OHL = nullptr;
     hipStream_t s = c->stream;
     int rc = GT_OK;
     struct { DSh *v; size_t n; } plan[] = {
@@ -646,12 +649,13 @@ static int partition_matmul(gt_ctx *c, gt_train *t, u32 h)
     OnehotArgs oa{}; oa.c = kc(c, c->op++); oa.T = t->T.v; oa.OH = t->OH.v; oa.base = base; oa.n = np * d; oa.d = t->d;
     GTCHK(launch(c, GT_KC_SMALL, k_onehot, dim3(tiles(np * d)), GT_BLOCK, oa));
     acct_eq(c, np * d); acct_b2a(c, np * d);
-    ColselArgs ca{}; ca.c = kc(c, c->op++); ca.L = limbs_L(t); ca.OH = t->OH.v; ca.sel = t->SEL.v; ca.N = N; ca.N8 = t->N8; ca.np = (u32)np; ca.d = t->d;
-    const u64 items = ((t->N8 / 8 + GT_LANES - 1) / GT_LANES) * ((d + GT_COLSEL_COLS - 1) / GT_COLSEL_COLS);
-    GTCHK(launch(c, GT_KC_MULT, k_colsel, dim3((unsigned)std::min<u64>(items, GT_MAX_BLOCKS)), GT_BLOCK, ca));
+    const u32 rpad = (u32)((np + 31) / 32 * 32), dpad = (t->d + 63) / 64 * 64;
+    GTCHK(launch(c, GT_KC_LOCAL, k_oh_limbs, g1(6ull * dpad * rpad), B256, t->OH.v, t->OHL, (u32)np, t->d, rpad, dpad));
+    PartMmArgs pa{}; pa.c = kc(c, c->op); c->op += 2;
+    pa.L = limbs_L(t); pa.OHL = t->OHL; pa.XT = t->XT.v; pa.M = t->M.v; pa.N = N; pa.N8 = t->N8; pa.nblk = t->nblk;
+    pa.d = t->d; pa.dpad = dpad; pa.rpad = rpad;
+    GTCHK(launch(c, GT_KC_PARTMM, k_part_mm, dim3((unsigned)std::min<u64>(t->nblk, 16 * (u64)c->resident)), GT_BLOCK, pa));
     acct_reshare(c, N * d, 1);
-    RowdotArgs ra{}; ra.c = kc(c, c->op++); ra.sel = t->SEL.v; ra.XT = t->XT.v; ra.M = t->M.v; ra.N = N; ra.N8 = t->N8; ra.d = t->d;
-    GTCHK(launch(c, GT_KC_MULT, k_rowdot, dim3(tiles8(t->N8)), GT_BLOCK, ra));
     acct_reshare(c, N, 1);
     return GT_OK;
 }
@@ -837,9 +841,11 @@ static int count_literal(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
 extern "C" int gt_train_set_partition(gt_ctx *c, gt_train *t, int by_products)
 {
     if (!c || !t) return GT_EINVAL;
-    if (by_products && !t->SEL.base) {
-        GTCHK(dsh_alloc(t->OH, ((size_t)1 << t->H) * t->d, c->stream));
-        GTCHK(dsh_alloc(t->SEL, (size_t)t->d * t->N8, c->stream));
+    if (by_products && !t->OHL) {
+        if (t->H > 13) return GT_EINVAL;               // int32 accumulators of the limb products: at most 4096 nodes in the level before
+        const size_t nprev = std::max<size_t>(32, (size_t)1 << (t->H ? t->H - 1 : 0)), dpad = ((size_t)t->d + 63) / 64 * 64;
+        GTCHK(dsh_alloc(t->OH, nprev * t->d, c->stream));
+        if (hipMalloc(&t->OHL, 48 * dpad * nprev) != hipSuccess) { t->OHL = nullptr; return GT_ENOMEM; }
     }
     t->part_matmul = by_products != 0;
     return GT_OK;

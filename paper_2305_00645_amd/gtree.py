@@ -40,11 +40,11 @@ class _Stats(C.Structure):
 GT_FLAG_PROFILE = 1
 GT_FLAG_LEVELWISE_INFER = 2
 GT_FLAG_INFER_TILE = {16: 0x100, 32: 0x200, 64: 0x300}
-KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local", "eqgrid_rows", "eqgrid_store", "infer")
+KC_NAMES = ("share", "mult", "eqgrid", "count", "small", "local", "eqgrid_rows", "eqgrid_store", "infer", "partmm")
 
 
 class _Prof(C.Structure):
-    _fields_ = [("ms", C.c_double * 9), ("launches", C.c_uint64 * 9)]
+    _fields_ = [("ms", C.c_double * 10), ("launches", C.c_uint64 * 10)]
 
 
 class _Params(C.Structure):
