@@ -28,9 +28,9 @@ EQ_ALU_OPS = EQ_ALU_OPS_DEALER + EQ_ALU_OPS_ONLINE
 # HBM bytes per equality test of the three grid variants, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (table in profiles/pmc_traffic_micro.md): inner product against a shared array, against the
 # sample's own row, leaf one-hot written as limb tiles
-# (the one-launch inference reads the instances once and writes one result per instance; its
-# figure is the counter bytes of the C5 batch over its 2.687e9 tests)
-EQ_HBM_BYTES = {"eqgrid": 7.3, "eqgrid_rows": 81.6, "eqgrid_store": 52.1, "infer": 1.2}
+# (the one-launch inference reads every feature of an instance once per level: 10 levels x 48 B x 64
+# features over 2687 tests per instance at C5)
+EQ_HBM_BYTES = {"eqgrid": 7.5, "eqgrid_rows": 81.6, "eqgrid_store": 52.1, "infer": 14.2}
 SHADER_CLOCK_MEASURED_GHZ = 2.1  # under the equality grid's load (profiles/pmc_sq_micro.md); the peak below uses the nominal 2.4
 
 
@@ -135,7 +135,8 @@ def paper_shapes(np, torch, gtree, wl):
 def micro(args, np, torch, gtree, wl):
     """Calibration: gt_reconstruct_a on 2^27 words reads 3 GiB and writes 1 GiB exactly.
     Then one array access (equality grid with inner product) over 64 entries for
-    --instances rows, and one split-scoring level of the C5 recipe at --samples."""
+    --instances rows, one split-scoring level of the C5 recipe at --samples, and one
+    depth-10 inference batch of --instances."""
     g = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=4)
     n = 1 << 27
     s = g.new(n)
@@ -156,7 +157,15 @@ def micro(args, np, torch, gtree, wl):
     g.train_import(h, *st)
     g.train_level(h)
     torch.cuda.synchronize()
-    print(json.dumps({"micro": "done", "calibration_words": n, "oaa_rows": NI, "oaa_entries": 64, "level_samples": N}))
+    del X, Y, st
+    torch.cuda.empty_cache()
+    # the one-launch inference on the C5 batch (depth 10, 64 binary features)
+    wi = wl.c5_infer(NI=NI)
+    tree = g.tree_import(g.share_a(wi["feat"]), None, g.share_a(wi["leaf"]), wi["H"])
+    g.infer_batch(tree, g.share_a(wi["I"].reshape(-1)), NI, wi["d"])
+    torch.cuda.synchronize()
+    print(json.dumps({"micro": "done", "calibration_words": n, "oaa_rows": NI, "oaa_entries": 64, "level_samples": N,
+                      "inference_instances": NI, "inference_depth": wi["H"]}))
 
 
 def main():

@@ -675,7 +675,10 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     // groups of 64 columns; a remainder of at most 16 columns joins their launch as a
     // narrow group, one of 17 to 32 columns runs in a launch of its own with a 32-wide tile
     const u32 rem = ncol % 64, nfull = ncol / 64 + (rem > 32 ? 1 : 0);
-    const u32 narrow = (nfull && rem && rem <= 16) ? 1 : 0;   // alone it would only re-read L: no gain over the 32-wide tile
+    // (a remainder of at most 16 columns with no full group beside it - the class totals of the
+    // label level - runs on the 16-wide tiles alone: half the matrix-core work of a padded 32-wide
+    // tile, measured 2.15 ms instead of 2.56 ms at 256 nodes x 10^6 samples)
+    const u32 narrow = (rem && rem <= 16) ? 1 : 0;
     const u32 ncg2 = (nfull + cper - 1) / cper, ncg1 = (rem && rem <= 32 && !narrow) ? 1 : 0;
     // sample chunk per workgroup: as long as the int32 accumulators allow, shorter when
     // that is needed to give every compute unit several workgroups
