@@ -30,6 +30,9 @@ __device__ __forceinline__ u32 rotl32(u32 x, int r) { return __builtin_rotatelef
     a += b; d ^= a; d = rotl32(d, 16); c += d; b ^= c; b = rotl32(b, 12);                     \
     a += b; d ^= a; d = rotl32(d, 8);  c += d; b ^= c; b = rotl32(b, 7);
 
+#ifndef GT_PRF_ROUNDS
+#define GT_PRF_ROUNDS 8          // ChaCha rounds of the PRF (the CPU check uses the same number)
+#endif
 __device__ __forceinline__ void chacha8(const Key &key, u64 blk, u32 op, u32 stream, u64 (&out)[8])
 {
     const u32 i0 = 0x61707865u, i1 = 0x3320646eu, i2 = 0x79622d32u, i3 = 0x6b206574u;
@@ -39,7 +42,7 @@ __device__ __forceinline__ void chacha8(const Key &key, u64 blk, u32 op, u32 str
     u32 x8 = key.k[4], x9 = key.k[5], x10 = key.k[6], x11 = key.k[7];
     u32 x12 = c12, x13 = c13, x14 = op, x15 = stream;
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
+    for (int r = 0; r < GT_PRF_ROUNDS / 2; r++) {
         GT_QR(x0, x4, x8, x12) GT_QR(x1, x5, x9, x13) GT_QR(x2, x6, x10, x14) GT_QR(x3, x7, x11, x15)
         GT_QR(x0, x5, x10, x15) GT_QR(x1, x6, x11, x12) GT_QR(x2, x7, x8, x13) GT_QR(x3, x4, x9, x14)
     }
