@@ -147,6 +147,33 @@ static void dealer(const orc_ctx *c, u32 op, u64 e, dealer_t *D)
     D->bA[0] = w[6]; D->bA[1] = w[7]; D->bA[2] = D->beta - w[6] - w[7];
 }
 
+/* daBit of test e of an equality grid.  In a grid the masked index of a row is opened
+ * once and serves the comparisons with all columns (see eq_grid_rs), so a test needs no
+ * edaBit of its own, only the daBit of its conversion: 131 bits.  The eight tests
+ * 8g..8g+7 share the three blocks 3g, 3g+1, 3g+2 of stream 4: test j takes slot j%3 of
+ * block 3g + j/3; slot q holds the arithmetic components in words 2q and 2q+1 and the
+ * bit and its first two Boolean components in bits 3q, 3q+1, 3q+2 of word 6. */
+static void dabit_grid(const orc_ctx *c, u32 op, u64 e, dealer_t *D)
+{
+    u64 g = e >> 3, j = e & 7, blk = 3 * g + j / 3, q = j % 3;
+    u32 out[16];
+    u64 w[8];
+    orc_chacha_block(c->key[KEY_DEALER], (u32)blk, (u32)(blk >> 32), op, 4, PRF_ROUNDS, out);
+    for (int i = 0; i < 8; i++) w[i] = (u64)out[2 * i] | ((u64)out[2 * i + 1] << 32);
+    D->beta = (w[6] >> (3 * q)) & 1;
+    D->bB[0] = (w[6] >> (3 * q + 1)) & 1; D->bB[1] = (w[6] >> (3 * q + 2)) & 1;
+    D->bB[2] = D->beta ^ D->bB[0] ^ D->bB[1];
+    D->bA[0] = w[2 * q]; D->bA[1] = w[2 * q + 1]; D->bA[2] = D->beta - w[2 * q] - w[2 * q + 1];
+}
+
+void orc_dabit_grid(const orc_ctx *c, uint32_t op, uint64_t e, uint64_t out[7])
+{
+    dealer_t D;
+    dabit_grid(c, op, e, &D);
+    for (int j = 0; j < 3; j++) { out[j] = D.bB[j]; out[3 + j] = D.bA[j]; }
+    out[6] = D.beta;
+}
+
 void orc_dealer(const orc_ctx *c, uint32_t op, uint64_t e, uint64_t out[14])
 {
     dealer_t D;
@@ -446,11 +473,18 @@ void orc_ge_a(orc_ctx *c, const uint64_t *x, const uint64_t *y, size_t n, uint64
 }
 
 /* ------------------------------------------------------------------------- */
-/* Equality grid: the first two lines of the array-access protocol (Sec. V-A),
- * also used for the per-sample leaf flags of the learning protocol (Sec. V-B).
- * Rows are samples i < n, columns k < w; E[k][i] = [u[i] - base == k], optionally
- * ANDed with a shared bit g[k] common to all rows, then converted to arithmetic.
- * Element index (and position in EA) is k*n8 + i with n8 = n padded to 8. */
+/* Equality grid: the first two lines of the array-access protocol (Sec. V-A: the index u
+ * is compared with every position 0..|W|-1), also used for the per-sample leaf flags of
+ * the learning protocol (Sec. V-B).  Rows are samples i < n, columns k < w;
+ * E[k][i] = [u[i] - base == k], optionally ANDed with a shared bit g[k] common to all
+ * rows, then converted to arithmetic.  Element index (and position in EA) is k*n8 + i with
+ * n8 = n padded to 8.
+ * All comparisons of a row are with PUBLIC constants, so one masked opening serves them
+ * all: the row has one edaBit r_i (dealer block i of stream 0), c_i = u_i + r_i is opened
+ * once, and u_i - base - k = 0 iff r_i = c_i - base - k, which is tested bit by bit on the
+ * shared bits of r_i with fresh masks per test (stream 1, word of the element).  Per row
+ * l bits for the opening, per test l-1 bits for the AND rounds [+1 for the AND with g]
+ * and 1 for the conversion, whose daBit is the test's own (dabit_grid). */
 /* A row subset (rows != NULL) computes only the listed samples, with the element
  * indices of the full problem; results are stored compactly, row r of the list at
  * position k*pad8(nrows) + r.  This lets a test check sampled outputs of a problem
@@ -471,7 +505,8 @@ static void eq_grid_rs(orc_ctx *c, u32 op, const sh *u, u64 base, size_t w, size
             u64 v[3], A[3], t[3], a[3]; dealer_t D;
             sh_get(u, r, v);                           /* u is stored per listed row */
             v[0] -= base + k;                          /* public operand: component 1 only */
-            dealer(c, op, e, &D);
+            dealer(c, op, i, &D);                      /* the edaBit of the ROW: c_i - base - k = u_i - base - k + r_i */
+            dabit_grid(c, op, e, &D);                  /* the daBit of the test */
             eq_el(c, op, e, v, &D, A, t);
             if (g) {
                 u64 gb[3], al[3];
@@ -482,7 +517,9 @@ static void eq_grid_rs(orc_ctx *c, u32 op, const sh *u, u64 base, size_t w, size
             b2a_el(t, &D, a);
             sh_set(EA, k * s8 + r, a);
         }
-    wire_eq(c, (u64)w * nr);
+    wire(c, +1, nr, 64);                               /* one opening per row */
+    for (int k = 0; k < 6; k++) wire(c, -1, (u64)w * nr, 32u >> k);
+    c->rounds += EQ_ROUNDS;
     if (g) wire_and1(c, (u64)w * nr);
     wire_b2a(c, (u64)w * nr);
 }

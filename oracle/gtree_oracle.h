@@ -74,6 +74,8 @@ void orc_zero_sharing(const orc_ctx *, uint32_t op, uint32_t stream, uint64_t e,
                       uint64_t alpha[3]);
 /* dealer material of element e: out[0..2]=r comps, [3..5]=rho comps (Boolean),
  * [6..8]=beta Boolean comps, [9..11]=beta arithmetic comps, [12]=r, [13]=beta */
+/* daBit of test e of an equality grid: out = Boolean components [0..2], arithmetic components [3..5], the bit [6] */
+void orc_dabit_grid(const orc_ctx *c, uint32_t op, uint64_t e, uint64_t out[7]);
 void orc_dealer(const orc_ctx *, uint32_t op, uint64_t e, uint64_t out[14]);
 
 /* ---- sharing ------------------------------------------------------------- */

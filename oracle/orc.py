@@ -63,6 +63,7 @@ def _load():
         "orc_prf_word": (u64, [vp, i, u32, u32, u64]),
         "orc_zero_sharing": (None, [vp, u32, u32, u64, i, _u64p]),
         "orc_dealer": (None, [vp, u32, u64, _u64p]),
+        "orc_dabit_grid": (None, [vp, u32, u64, _u64p]),
         "orc_share_a": (None, [vp, _u64p, sz, _u64p]),
         "orc_reconstruct_a": (None, [_u64p, sz, _u64p]),
         "orc_reconstruct_b": (None, [_u64p, sz, _u64p]),
@@ -176,6 +177,11 @@ class Oracle:
         self.L.orc_dealer(self.ctx, op, e, _p(a))
         return dict(rA=a[0:3].copy(), rho=a[3:6].copy(), bB=a[6:9].copy(), bA=a[9:12].copy(),
                     r=int(a[12]), beta=int(a[13]))
+
+    def dabit_grid(self, op, e):
+        a = np.zeros(7, dtype=np.uint64)
+        self.L.orc_dabit_grid(self.ctx, op, e, _p(a))
+        return dict(bB=a[0:3].copy(), bA=a[3:6].copy(), beta=int(a[6]))
 
     # -- sharing -----------------------------------------------------------
     def share(self, plain):

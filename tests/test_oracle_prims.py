@@ -161,10 +161,11 @@ def test_oaa_rounds_log_l_plus_3(seed):
     o.oaa(W, u)
     rounds, wire = o.stats()
     assert rounds == 9
-    # per row: w equality tests (127 bits + 1 bit conversion each) and one 64-bit reshare;
+    # per row: ONE opening of the masked index (64 bits) for all w comparisons, per comparison the
+    # 63 bits of the AND rounds and 1 bit of conversion, and one 64-bit reshare of the inner product;
     # the paper's unfused select costs (4l-1) bits per array element instead
-    assert int(wire[1].sum()) * 8 == 8 * (16 * 128 + 64)
-    assert 8 * (16 * 128 + 64) < 8 * 16 * (4 * 64 - 1)
+    assert int(wire[1].sum()) * 8 == 8 * (64 + 16 * 64 + 64)
+    assert 8 * (64 + 16 * 64 + 64) < 8 * 16 * (4 * 64 - 1)
 
 
 @pytest.mark.parametrize("tau", [4, 10, 16])
@@ -234,4 +235,30 @@ def test_array_access_as_printed_costs_4l_minus_1_bits(seed, w, n):
     o.stats_reset()
     z2 = o.oaa(sW, su)
     assert np.array_equal(Oracle.rec(z2), want)
-    assert int(o.wire_bits()[0].sum()) == w * n * 128 + n * 64 < w * n * 255 + 1
+    assert int(o.wire_bits()[0].sum()) == n * 64 + w * n * 64 + n * 64 < w * n * 255 + 1
+
+
+def test_grid_opens_one_masked_index_per_row(seed):
+    """In an equality grid the comparisons of a row are all with public constants, so the row's
+    masked index is opened once: the array access must still return W[u] for every u (also
+    outside the array), its messages must be 64 bits per row + 63 + 1 per test + the reshare,
+    and the daBits of the eight tests of a group come from three dealer blocks whose Boolean
+    and arithmetic components share the same bit."""
+    o = Oracle(seed)
+    for e in (0, 1, 2, 3, 7, 8, 1000003):
+        d = o.dabit_grid(5, e)
+        assert int(d["bB"][0] ^ d["bB"][1] ^ d["bB"][2]) == d["beta"] and d["beta"] in (0, 1)
+        assert (int(d["bA"][0]) + int(d["bA"][1]) + int(d["bA"][2])) & M64 == d["beta"]
+    # tests 0..2 share a block and differ; tests of different groups use different blocks
+    assert len({int(o.dabit_grid(5, e)["bA"][0]) for e in range(16)}) == 16
+    rng = np.random.default_rng(8)
+    w, n = 11, 29
+    Wp = rng.integers(0, M64, size=w, dtype=np.uint64)
+    u = np.concatenate([np.arange(w + 3), rng.integers(0, w, size=n - w - 3)]).astype(np.uint64)
+    sW, su = o.share(Wp), o.share(u)
+    o.stats_reset()
+    z = o.oaa(sW, su)
+    assert np.array_equal(Oracle.rec(z), np.array([Wp[int(i)] if int(i) < w else 0 for i in u], dtype=np.uint64))
+    bits = o.wire_bits()
+    assert int(bits[0, 1]) == n * 64 + w * n * 1                  # to the successor: opening per row, conversion bit per test
+    assert int(bits[0, 2]) == w * n * 63 + n * 64                 # to the predecessor: AND rounds per test, reshare per row

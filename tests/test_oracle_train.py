@@ -209,9 +209,10 @@ def test_learning_protocol_as_printed_matches_plaintext_and_cost_formula(seed):
     CW = d * K + K
     for h in range(H + 1):
         nh = 1 << h
-        if h > 0:
-            fused += N * (nh // 2) * 128 + N * l + N * d * 128 + N * l
-        fused += nh * (2 * l - 1) + N * nh * (2 * l + 1) + nh * (K if h == H else CW) * l
+        if h > 0:       # two array accesses: opening per sample, 63 + 1 bits per test, reshare per sample
+            fused += (N * l + N * (nh // 2) * l + N * l) + (N * l + N * d * l + N * l)
+        # leaf flags (per node), leaf grid (opening per sample; 63 + AND 1 + conversion 1 per test), count reshare
+        fused += nh * (2 * l - 1) + N * l + N * nh * (l + 1) + nh * (K if h == H else CW) * l
     assert int(o.wire_bits()[0].sum()) - int(o2.wire_bits()[0].sum()) == lit - fused
     run_oracle_train(seed, wl.c2_train(N=80, d=7, H=3), literal=True)
 
@@ -221,7 +222,8 @@ def test_partition_by_products_matches_plaintext_cart(seed):
     split decisions, node types, tree and labels equal the plaintext CART level by level; M
     equals the paper's recurrence for every sample in a real leaf (and goes left below a node
     that stopped being one); the partition costs N*d*l + N*l bits plus n_{h-1}*d equality tests
-    with conversion instead of N*(n_{h-1} + d)*2l + 2*N*l."""
+    with conversion instead of N*(n_{h-1} + d)*l + 4*N*l (two array accesses, each with one
+    opening and one reshare per sample and l bits per test)."""
     w = wl.c1_train()
     N, d, K, H, l = w["N"], w["d"], w["K"], w["H"], 64
     o, ref, _ = run_oracle_train(seed, w, by_products=True)
@@ -230,7 +232,7 @@ def test_partition_by_products_matches_plaintext_cart(seed):
     saved = 0
     for h in range(1, H + 1):
         npv = 1 << (h - 1)
-        saved += (N * (npv + d) * 2 * l + 2 * N * l) - (npv * d * 2 * l + N * d * l + N * l)
+        saved += (N * (npv + d) * l + 4 * N * l) - (npv * d * 2 * l + N * d * l + N * l)
     assert int(o2.wire_bits()[0].sum()) - int(o.wire_bits()[0].sum()) == saved
     assert o.stats()[0] == o2.stats()[0] - H * (18 - 10)           # two array accesses of 9 rounds against 7 + 1 + 1 + 1
     run_oracle_train(seed, wl.c2_train(), H=5, by_products=True)          # has nodes that stop early
