@@ -19,11 +19,12 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12   # 32-bit vector ALU lane-ops, Tops/s: CUs x SIMDs x lanes x clock
-# Algorithmic 32-bit ALU ops per equality test, three parties together: one dealer ChaCha8 block
-# (400 ops: the edaBit and daBit of the test, offline material that the paper's timings exclude but
-# that this simulation derives inside the kernel) + 3 mask blocks per 8 tests (150: the zero
+# Algorithmic 32-bit ALU ops per equality test of a grid, three parties together.  A ChaCha8 block
+# is 400 ops.  Dealer: 3 blocks per 8 tests (150: the daBits of the tests, offline material that the
+# paper's timings exclude but that this simulation derives inside the kernel; the edaBit is one
+# block per ROW of the grid, 400/w per test, left out) + 3 mask blocks per 8 tests (150: the zero
 # sharings of the AND rounds, online) + protocol steps 3 x 50 on packed fields (online)
-EQ_ALU_OPS_DEALER, EQ_ALU_OPS_ONLINE = 400, 300
+EQ_ALU_OPS_DEALER, EQ_ALU_OPS_ONLINE = 150, 300
 EQ_ALU_OPS = EQ_ALU_OPS_DEALER + EQ_ALU_OPS_ONLINE
 # HBM bytes per equality test of the three grid variants, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (table in profiles/pmc_traffic_micro.md): inner product against a shared array, against the
@@ -323,7 +324,7 @@ def main():
             "eqgrid": {"bound": "alu", "achieved": EQ_ALU_OPS * n_eq * k / (eq_ms / 1e3) / 1e12, "peak": LANE_OPS_PEAK,
                        "unit": "Tops/s", "traffic": eq_bytes_step * k / max(eq_l, 1),
                        "note": "the equality-test kernels together (three grid variants of training and the one-launch inference: most of the step); %d 32-bit ALU ops per "
-                               "test for the three parties, of which %d are the dealer's PRF block (offline material of the test: "
+                               "test for the three parties, of which %d are the dealer's PRF blocks (the daBits, offline material of the test: "
                                "the paper's timings exclude its generation, this simulation derives it in the kernel) and %d are "
                                "online work (mask words 150, protocol 150): counting online ops only the figure is %.2f of the "
                                "peak; peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz nominal (the shader clock under this load "

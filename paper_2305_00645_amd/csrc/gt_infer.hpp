@@ -59,10 +59,9 @@ __device__ __forceinline__ u64 sum_over_column_groups(u64 v)
     return v;
 }
 
-// State of one workgroup: LDS rows as in k_eqgrid (rows 0-2: r arithmetic components,
-// then the opening's messages, then the mask words; rows 3-5: r Boolean components, then
-// the messages of the AND rounds, conversions and reshares; rows 6-8: beta arithmetic
-// components, between two steps party p's PRF scratch in row 6+p).
+// State of one workgroup: LDS rows as in k_eqgrid (rows 0-2: the mask words; rows 3-5: the
+// messages of the openings, AND rounds, conversions and reshares; rows 6-8: beta
+// arithmetic components, between two steps party p's PRF scratch in row 6+p).
 template <int LGI>
 struct InferWg {
     static constexpr u32 IT = 1u << LGI, LPI = GT_LANES >> LGI, CS = 8 * LPI;   // instances per tile, lanes per instance, columns per step
@@ -85,82 +84,55 @@ struct InferWg {
     {
         const Sh one = pub(p, 1);
         u64 acc = 0, acc2 = 0;
+        // the instance's edaBit and the one opening of the access: c = u + r - base is public
+        // afterwards; the lanes of one instance replay the same message, one of them counts
+        u64 cpub; Sh rho;
+        {
+            const Dealer D = dealer_of(K, p, op, i);
+            rho = D.rho;
+            const u64 snd = u.o + D.rA.o;
+            cpub = snd + (u.n + D.rA.n) + LW.open1(snd, (valid && cg == 0) ? 64u : 0u) - base;
+        }
         for (u32 k0 = 0; k0 < w; k0 += CS) {
-            // the dealer's 512 blocks of the step, spread over the 192 lanes
-#pragma unroll 1
-            for (int j = 0; j < 3; j++) {
-                const int el = j * 192 + tid;
-                if (el < GT_TILE_EL) {
-                    const u32 ln = el & (GT_LANES - 1), sl = (u32)el >> 6;
-                    const u64 e = (u64)(k0 + (ln >> LGI) * 8 + sl) * N8 + tile0 + (ln & (IT - 1));
-                    u64 D[8];
-                    chacha8(K.dlr, e, op, 0, D);
-                    const u64 beta = D[5] & 1;
-                    s_mat[0][el] = D[1]; s_mat[1][el] = D[2]; s_mat[2][el] = D[0] - D[1] - D[2];
-                    s_mat[3][el] = D[3]; s_mat[4][el] = D[4]; s_mat[5][el] = D[0] ^ D[3] ^ D[4];
-                    s_mat[6][el] = D[6]; s_mat[7][el] = D[7]; s_mat[8][el] = beta - D[6] - D[7];
-                    const u32 b0 = (u32)(D[5] >> 1) & 1, b1 = (u32)(D[5] >> 2) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
-                    atomicOr(&s_bitw[par][ln], (b0 << sl) | (b1 << (8 + sl)) | (b2 << (16 + sl)));
-                }
-            }
-            // mask words under the own key: this lane evaluates the block of column
-            // k0 + lane / (IT/8), instances 8 * (lane mod IT/8) .. +7 of the tile
+            // This lane evaluates, for column k0 + lane / (IT/8) and instances
+            // 8 * (lane mod IT/8) .. +7 of the tile, the block of mask words under the own
+            // key and the party-th of the group's three daBit blocks
             u64 A[8];
             {
                 const u32 cc = (u32)lane >> (LGI - 3), gg = (u32)lane & (IT / 8 - 1);
-                chacha8(K.own, (((u64)(k0 + cc) * N8 + tile0) >> 3) + gg, op, 1, A);
+                const u64 g = (((u64)(k0 + cc) * N8 + tile0) >> 3) + gg;
+                u64 D[8];
+                chacha8(K.dlr, 3 * g + p, op, 4, D);
+                const u32 sl = cc & 7, ln0 = (cc >> 3) * IT + gg * 8;
+#pragma unroll
+                for (int q = 0; q < 3; q++) {
+                    const u32 j = 3 * p + q;
+                    if (j < 8) {
+                        const u32 ln = ln0 + j, el = sl * GT_LANES + ln;
+                        const u64 beta = (D[6] >> (3 * q)) & 1;
+                        s_mat[6][el] = D[2 * q]; s_mat[7][el] = D[2 * q + 1]; s_mat[8][el] = beta - D[2 * q] - D[2 * q + 1];
+                        const u32 b0 = (u32)(D[6] >> (3 * q + 1)) & 1, b1 = (u32)(D[6] >> (3 * q + 2)) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
+                        atomicOr(&s_bitw[par][ln], (b0 << sl) | (b1 << (8 + sl)) | (b2 << (16 + sl)));
+                    }
+                }
+                chacha8(K.own, g, op, 1, A);
             }
+#pragma unroll
+            for (int s = 0; s < 8; s++) s_mat[p][8 * lane + s] = A[s];           // block (cc, gg): words of 8 instances
             __syncthreads();
-            u64 snd[8], rcv[8], mn[8];
+            if (p == 0) s_bitw[par ^ 1][lane] = 0;
             u32 nl = 0;
+            Sh t[8];
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const u32 col = k0 + cg * 8 + s;
                 nl += (valid && col < w) ? 1u : 0u;
-                const int el = s * GT_LANES + lane;
-                const Sh nsub = pub(p, 0 - (base + col));
-                snd[s] = u.o + nsub.o + s_mat[p][el];      // columns beyond w, instances beyond NI: any value serves
-                mn[s] = u.n + nsub.n + s_mat[pn][el];
-            }
-            if (p == 0) s_bitw[par ^ 1][lane] = 0;
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = snd[s];   // the opening, 64 bits per test
-            LW.nopen += 64u * nl;
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < 8; s++) rcv[s] = s_mat[pp][s * GT_LANES + lane];
-            Sh t[8];
-            if (p == 0) {
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const int el = s * GT_LANES + lane;
-                    t[s].o = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
-                    t[s].n = s_mat[4][el];
-                }
-            } else if (p == 2) {
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const int el = s * GT_LANES + lane;
-                    t[s].n = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
-                    t[s].o = s_mat[5][el];
-                }
-            } else {
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const int el = s * GT_LANES + lane;
-                    t[s].o = s_mat[4][el];
-                    t[s].n = s_mat[5][el];
-                }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < 8; s++) s_mat[p][8 * lane + s] = A[s];           // block (cc, gg): words of 8 instances
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < 8; s++) {
                 const u32 idx = (cg * 8 + s) * IT + inst;
                 A[s] = s_mat[p][idx] ^ s_mat[pn][idx];
+                // t = rho with the complement of (c - base - col) xored into component 0
+                const u64 nx = ~(cpub - col);                // columns beyond w, instances beyond NI: any value serves
+                t[s].o = p == 0 ? rho.o ^ nx : rho.o;
+                t[s].n = p == 2 ? rho.n ^ nx : rho.n;
             }
             u32 To8, Tn8;
             eq_rounds8_packed(LW, t, A, nl, To8, Tn8);

@@ -505,20 +505,46 @@ __device__ __forceinline__ u32 mask63_packed(const u64 (&A)[8])
 }
 
 // Offline and pairwise-key material is produced once per workgroup and handed out
-// through LDS.  The dealer's block of an element yields the components of all three
-// parties, so the 512 blocks of a step are spread over the 192 lanes (the dealer is a
-// role of its own, not one of the parties); each party's wavefront then reads only its
-// two components.  The mask word under key k_j is evaluated by party j's wavefront and
-// also read by party j-1, the other holder of k_j; it reuses the rows of the edaBit's
-// arithmetic components, which are dead once the masked value has been opened.
+// through LDS; a dealer block yields the components of all three parties (the dealer is a
+// role of its own, not one of the parties), each party's wavefront then reads only its
+// two components.
+//  - Per work item: the edaBits of the lane's 8 samples (one per ROW of the grid: all
+//    comparisons of a row are with public constants, so its masked index is opened once);
+//    the three wavefronts split the 8 blocks, the opening goes through LDS, afterwards
+//    every lane keeps the public c and its two Boolean components of r in registers.
+//  - Per step (one column for the lane's 8 samples): the daBits of the 8 tests come from
+//    three dealer blocks (stream 4, blocks 3g..3g+2 of the group g = e/8; test j in slot
+//    j%3 of block 3g + j/3): party p's wavefront evaluates block 3g+p, one block per
+//    lane; the mask word under key k_j is evaluated by party j's wavefront and also read
+//    by party j-1, the other holder of k_j.
 #define GT_TILE_EL (8 * GT_LANES)
+
+// the three daBits of one dealer block into the rows of the arithmetic components (rows
+// 6-8) and the packed bit words of lane ln: slot q serves test j = 3b + q of the group
+__device__ __forceinline__ void deal_dabits(u64 (*s_mat)[GT_TILE_EL], u32 *bitw, const u64 (&D)[8], u32 b, u32 ln)
+{
+    u32 bits = 0;
+#pragma unroll
+    for (int q = 0; q < 3; q++) {
+        const u32 j = 3 * b + q;
+        if (j < 8) {
+            const u32 el = j * GT_LANES + ln;
+            const u64 beta = (D[6] >> (3 * q)) & 1;
+            s_mat[6][el] = D[2 * q]; s_mat[7][el] = D[2 * q + 1]; s_mat[8][el] = beta - D[2 * q] - D[2 * q + 1];
+            const u32 b0 = (u32)(D[6] >> (3 * q + 1)) & 1, b1 = (u32)(D[6] >> (3 * q + 2)) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
+            bits |= (b0 << j) | (b1 << (8 + j)) | (b2 << (16 + j));
+        }
+    }
+    atomicOr(&bitw[ln], bits);
+}
 
 template <int MODE, bool HAS_G, int NDOT>
 __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
 {
-    // rows 0-2: r arithmetic components, then the messages of the opening, then the mask
-    // words under k_0..k_2; rows 3-5: r Boolean components, then the messages of the AND
-    // rounds and of the bit conversion; rows 6-8: beta arithmetic components
+    // rows 0-2: the mask words under k_0..k_2; rows 3-5: the messages of the AND rounds, of
+    // the bit conversion and of the reshared inner products; rows 6-8: beta arithmetic
+    // components.  At the start of a work item rows 0-5 carry the edaBit components of the
+    // lane's samples and the opening.
     __shared__ u64 s_mat[9][GT_TILE_EL];
     // beta Boolean components, packed per lane: bit 8j+s = component j of the lane's test s.
     // The dealer's lanes OR their bits in; two copies alternate between steps so that
@@ -526,11 +552,8 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
     __shared__ u32 s_bitw[2][GT_LANES];
     __shared__ u64 s_cnt[6];
     const int p = party_of_wave(), lane = threadIdx.x, tid = p * GT_LANES + lane, pn = p == 2 ? 0 : p + 1, pp = p == 0 ? 2 : p - 1;
-    // messages of the AND rounds and of the bit conversion pass through the rows of the
-    // Boolean edaBit components, which are dead once t has been formed; so do the
-    // reshared inner products at the end of a work item
     LWire LW; LW.init(&s_mat[3][0], s_cnt);
-    static_assert(GT_LWIRE_WORDS <= 3 * GT_TILE_EL, "LDS wire does not fit the rows it reuses");
+    static_assert(GT_LWIRE_WORDS <= 3 * GT_TILE_EL, "LDS wire does not fit the rows it uses");
     const PartyKeys K = load_party_keys(a.c.keys, p);
     const u32 op = a.c.op;
     const u64 ngrp = a.N8 / 8;
@@ -554,6 +577,39 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
         const u64 grp = (tile << lgs) + (lane & lgm), i0 = grp * 8;
         const bool actg = grp < ngrp;
         const u64 nvg = actg ? a.N : 0;
+        // ---- the row's part: edaBits of the 8 samples, masked indices, one opening
+        u64 cpub[8], rho_o[8], rho_n[8];
+        {
+#pragma unroll 1
+            for (int s = p; s < 8; s += 3) {            // this party's share of the 8 dealer blocks of the lane
+                u64 D[8];
+                chacha8(K.dlr, i0 + s, op, 0, D);
+                const int el = s * GT_LANES + lane;
+                s_mat[0][el] = D[1]; s_mat[1][el] = D[2]; s_mat[2][el] = D[0] - D[1] - D[2];
+                s_mat[3][el] = D[3]; s_mat[4][el] = D[4]; s_mat[5][el] = D[0] ^ D[3] ^ D[4];
+            }
+            u64 snd[8], mn[8];
+            ld8(own_of(a.u, p), i0, nvg, snd); ld8(nxt_of(a.u, p), i0, nvg, mn);
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const int el = s * GT_LANES + lane;
+                snd[s] += s_mat[p][el];                 // samples beyond N: any value serves
+                mn[s] += s_mat[pn][el];
+                rho_o[s] = s_mat[3 + p][el]; rho_n[s] = s_mat[3 + pn][el];
+            }
+            __syncthreads();
+            // the opening, 64 bits per sample: party p's message takes the place of row p.  The column
+            // ranges of one tile (and the four column lanes of the leaf grid) replay the same opening;
+            // it is counted once.
+#pragma unroll
+            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = snd[s];
+            if (kbeg == 0 && ro == 0) LW.nopen += 64u * live8(i0, nvg);
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < 8; s++) cpub[s] = snd[s] + mn[s] + s_mat[pp][s * GT_LANES + lane] - a.base;
+            __syncthreads();
+        }
         u64 acc[8], acc2[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) { acc[s] = 0; acc2[s] = 0; }
@@ -563,76 +619,28 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
             const u64 nv = act ? a.N : 0;              // samples of this lane that exist
             const u32 nl = live8(i0, nv);              // how many of the lane's eight tests exist
             const u64 e0 = (u64)k * a.N8 + i0;
-#pragma unroll 1
-            for (int j = 0; j < 3; j++) {
-                const int el = j * 192 + tid;
-                if (el < GT_TILE_EL) {
-                    const u32 ln = el & (GT_LANES - 1);
-                    const u64 e = (u64)(k0 + (ln >> lgs)) * a.N8 + ((tile << lgs) + (ln & lgm)) * 8 + (el >> 6);
-                    u64 D[8];
-                    chacha8(K.dlr, e, op, 0, D);
-                    const u64 beta = D[5] & 1;
-                    s_mat[0][el] = D[1]; s_mat[1][el] = D[2]; s_mat[2][el] = D[0] - D[1] - D[2];
-                    s_mat[3][el] = D[3]; s_mat[4][el] = D[4]; s_mat[5][el] = D[0] ^ D[3] ^ D[4];
-                    s_mat[6][el] = D[6]; s_mat[7][el] = D[7]; s_mat[8][el] = beta - D[6] - D[7];
-                    const u32 b0 = (u32)(D[5] >> 1) & 1, b1 = (u32)(D[5] >> 2) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
-                    const u32 sh = (u32)el >> 6;
-                    atomicOr(&s_bitw[par][ln], (b0 << sh) | (b1 << (8 + sh)) | (b2 << (16 + sh)));
-                }
-            }
             u64 A[8];
+            {
+                u64 D[8];
+                chacha8(K.dlr, 3 * (e0 >> 3) + p, op, 4, D);       // daBits of the tests 3p, 3p+1, 3p+2 of the lane
+                deal_dabits(s_mat, s_bitw[par], D, (u32)p, (u32)lane);
+            }
             chacha8(K.own, e0 >> 3, op, 1, A);         // mask words under this party's own key
-            __syncthreads();
-            u64 snd[8], rcv[8], mn[8];
-            const Sh nsub = pub(p, 0 - (a.base + k));  // minus the public column index
-            ld8(own_of(a.u, p), i0, nv, snd); ld8(nxt_of(a.u, p), i0, nv, mn);
-#pragma unroll
-            for (int s = 0; s < 8; s++) {
-                const int el = s * GT_LANES + lane;
-                snd[s] = snd[s] + nsub.o + s_mat[p][el];   // samples beyond N: any value serves
-                mn[s] = mn[s] + nsub.n + s_mat[pn][el];
-            }
-            if (p == 0) s_bitw[par ^ 1][lane] = 0;     // the next step's bit words
-            // opening of the masked values, 64 bits each: party p's message takes the place
-            // of row p once every party has read the components it needs
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = snd[s];
-            LW.nopen += 64u * nl;
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < 8; s++) rcv[s] = s_mat[pp][s * GT_LANES + lane];
-            // t = rho with the complement of the opened value xored into component 0,
-            // which party 0 holds as its own and party 2 as its next component
-            Sh t[8];
-            if (p == 0) {
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const int el = s * GT_LANES + lane;
-                    t[s].o = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
-                    t[s].n = s_mat[4][el];
-                }
-            } else if (p == 2) {
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const int el = s * GT_LANES + lane;
-                    t[s].n = ~(s_mat[3][el] ^ (snd[s] + mn[s] + rcv[s]));
-                    t[s].o = s_mat[5][el];
-                }
-            } else {
-#pragma unroll
-                for (int s = 0; s < 8; s++) {
-                    const int el = s * GT_LANES + lane;
-                    t[s].o = s_mat[4][el];
-                    t[s].n = s_mat[5][el];
-                }
-            }
-            __syncthreads();
 #pragma unroll
             for (int s = 0; s < 8; s++) s_mat[p][s * GT_LANES + lane] = A[s];
             __syncthreads();
+            if (p == 0) s_bitw[par ^ 1][lane] = 0;     // the next step's bit words
 #pragma unroll
             for (int s = 0; s < 8; s++) A[s] ^= s_mat[pn][s * GT_LANES + lane];
+            // t = rho with the complement of (c - base - k) xored into component 0, which
+            // party 0 holds as its own and party 2 as its next component
+            Sh t[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) {
+                const u64 nx = ~(cpub[s] - k);
+                t[s].o = p == 0 ? rho_o[s] ^ nx : rho_o[s];
+                t[s].n = p == 2 ? rho_n[s] ^ nx : rho_n[s];
+            }
             u32 To8, Tn8;
             eq_rounds8_packed(LW, t, A, nl, To8, Tn8); // six AND rounds, 63 bits
             if (HAS_G) {                               // and with the column's shared bit

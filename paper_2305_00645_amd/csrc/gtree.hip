@@ -153,6 +153,13 @@ static void acct_eq(gt_ctx *c, u64 n)
     for (int k = 0; k < 6; k++) wire_add(c, -1, n, 32u >> k);
     c->acc.rounds += 7;
 }
+// equality grid: the masked index is opened once per row, the AND rounds run per test
+static void acct_eq_grid(gt_ctx *c, u64 rows, u64 n)
+{
+    wire_add(c, +1, rows, 64);
+    for (int k = 0; k < 6; k++) wire_add(c, -1, n, 32u >> k);
+    c->acc.rounds += 7;
+}
 static void acct_ge(gt_ctx *c, u64 n)
 {
     wire_add(c, +1, n, 64);
@@ -438,7 +445,7 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a, u64 *e
         GTCHK(rc);
         if (a.dacc) GTCHK(launch(c, GT_KC_SMALL, k_dot_fin, dim3(tiles8(a.N8)), GT_BLOCK, a));
     }
-    acct_eq(c, nel);
+    acct_eq_grid(c, a.N, nel);
     if (has_g) acct_and1(c, nel);
     acct_b2a(c, nel);
     if (mode != GM_STORE) acct_reshare(c, a.N, ndot);
@@ -1106,11 +1113,11 @@ static int infer_one_launch(gt_ctx *c, P6 feat, P6 thr, P6 leaf, bool has_thr, u
     for (u32 t = 0; t < ntrees; t++) {
         for (u32 n = 0; n < H; n++) {
             const u64 nel = ((u64)1 << n) * NI;
-            acct_eq(c, nel); acct_b2a(c, nel); acct_reshare(c, NI, has_thr ? 2 : 1);
-            acct_eq(c, (u64)d * NI); acct_b2a(c, (u64)d * NI); acct_reshare(c, NI, 1);
+            acct_eq_grid(c, NI, nel); acct_b2a(c, nel); acct_reshare(c, NI, has_thr ? 2 : 1);
+            acct_eq_grid(c, NI, (u64)d * NI); acct_b2a(c, (u64)d * NI); acct_reshare(c, NI, 1);
             if (has_thr) { acct_ge(c, NI); acct_b2a(c, NI); }
         }
-        acct_eq(c, ((u64)1 << H) * NI); acct_b2a(c, ((u64)1 << H) * NI); acct_reshare(c, NI, 1);
+        acct_eq_grid(c, NI, ((u64)1 << H) * NI); acct_b2a(c, ((u64)1 << H) * NI); acct_reshare(c, NI, 1);
     }
     return rc;
 }
