@@ -31,7 +31,7 @@ EQ_ALU_OPS = EQ_ALU_OPS_DEALER + EQ_ALU_OPS_ONLINE
 # sample's own row, leaf one-hot written as limb tiles
 # (the one-launch inference reads every feature of an instance once per level: 10 levels x 48 B x 64
 # features over 2687 tests per instance at C5)
-EQ_HBM_BYTES = {"eqgrid": 7.5, "eqgrid_rows": 81.6, "eqgrid_store": 52.1, "infer": 14.2}
+EQ_HBM_BYTES = {"eqgrid": 7.4, "eqgrid_rows": 55.4, "eqgrid_store": 48.4, "infer": 13.9}
 SHADER_CLOCK_MEASURED_GHZ = 2.1  # under the equality grid's load (profiles/pmc_sq_micro.md); the peak below uses the nominal 2.4
 
 
@@ -331,7 +331,7 @@ def main():
                                "reads %.1f GHz); traffic = HBM bytes per launch = per-variant counter bytes per test "
                                "(profiles/pmc_traffic_micro.md) x this run's tests per variant; the >=50%% HBM target of the "
                                "workload description is not met and cannot be by this kernel: its messages stay in LDS and it "
-                               "is bound by the PRF (VALU issue share 0.76-0.81, profiles/pmc_sq_micro.md), see eqgrid_hbm_view"
+                               "is bound by the PRF (VALU issue share 0.77-0.83, profiles/pmc_sq_micro.md), see eqgrid_hbm_view"
                                % (EQ_ALU_OPS, EQ_ALU_OPS_DEALER, EQ_ALU_OPS_ONLINE,
                                   EQ_ALU_OPS_ONLINE * n_eq * k / (eq_ms / 1e3) / 1e12 / LANE_OPS_PEAK, SHADER_CLOCK_MEASURED_GHZ),
                        "avg_launch_ms": eq_ms / max(eq_l, 1), "launches_per_step": eq_l // k,
