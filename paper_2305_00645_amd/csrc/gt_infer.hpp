@@ -103,12 +103,15 @@ struct InferWg {
                 const u64 g = (((u64)(k0 + cc) * N8 + tile0) >> 3) + gg;
                 u64 D[8];
                 chacha8(K.dlr, 3 * g + p, op, 4, D);
+                // the 8 tests of a block go to 8 neighbouring lanes: positions in a row of LDS
+                // are swizzled (low three bits of the lane xor the next three) so that neither
+                // the producers' stores nor the consumers' loads pile up on a few banks
                 const u32 sl = cc & 7, ln0 = (cc >> 3) * IT + gg * 8;
 #pragma unroll
                 for (int q = 0; q < 3; q++) {
                     const u32 j = 3 * p + q;
                     if (j < 8) {
-                        const u32 ln = ln0 + j, el = sl * GT_LANES + ln;
+                        const u32 ln = ln0 + j, el = sl * GT_LANES + (ln ^ ((ln >> 3) & 7));
                         const u64 beta = (D[6] >> (3 * q)) & 1;
                         s_mat[6][el] = D[2 * q]; s_mat[7][el] = D[2 * q + 1]; s_mat[8][el] = beta - D[2 * q] - D[2 * q + 1];
                         const u32 b0 = (u32)(D[6] >> (3 * q + 1)) & 1, b1 = (u32)(D[6] >> (3 * q + 2)) & 1, b2 = ((u32)beta ^ b0 ^ b1) & 1;
@@ -118,7 +121,7 @@ struct InferWg {
                 chacha8(K.own, g, op, 1, A);
             }
 #pragma unroll
-            for (int s = 0; s < 8; s++) s_mat[p][8 * lane + s] = A[s];           // block (cc, gg): words of 8 instances
+            for (int s = 0; s < 8; s++) s_mat[p][8 * lane + (s ^ (lane & 7))] = A[s];   // block (cc, gg): words of 8 instances
             __syncthreads();
             if (p == 0) s_bitw[par ^ 1][lane] = 0;
             u32 nl = 0;
@@ -127,7 +130,7 @@ struct InferWg {
             for (int s = 0; s < 8; s++) {
                 const u32 col = k0 + cg * 8 + s;
                 nl += (valid && col < w) ? 1u : 0u;
-                const u32 idx = (cg * 8 + s) * IT + inst;
+                const u32 li = (cg * 8 + s) * IT + inst, idx = li ^ ((li >> 3) & 7);
                 A[s] = s_mat[p][idx] ^ s_mat[pn][idx];
                 // t = rho with the complement of (c - base - col) xored into component 0
                 const u64 nx = ~(cpub - col);                // columns beyond w, instances beyond NI: any value serves
@@ -145,7 +148,7 @@ struct InferWg {
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const u32 col = k0 + cg * 8 + s;
-                const int el = s * GT_LANES + lane;
+                const int el = s * GT_LANES + (lane ^ ((lane >> 3) & 7));
                 const Sh bA = { s_mat[6 + p][el], s_mat[6 + pn][el] };
                 Sh E;
                 E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
