@@ -220,15 +220,18 @@ def main():
         g.train_create(st["X"], st["Y"], N, d, H)
         return g, st
 
-    def step(g, st, t):
+    def step(g, st, t, pc=None):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         g.train_reset(st["X"], st["Y"])                                   # a0
         torch.cuda.synchronize(); t1 = time.perf_counter()
         g.train_import(h, st["M"], st["Tprev"], st["F"], st["C"], st["gamma"])   # set-up of the level's state (copies)
         torch.cuda.synchronize(); t1b = time.perf_counter()
+        c0 = g.prof()["count"][0] if pc is not None else 0.0
         g.train_level(h)                                                  # a1-a7
         torch.cuda.synchronize(); t2 = time.perf_counter()
+        if pc is not None:                                                # the level's own contraction, apart from the label level's
+            pc["level_count_ms"] = pc.get("level_count_ms", 0.0) + g.prof()["count"][0] - c0
         tree = g.train_finish()                                           # a1, a2, a8 at level H
         torch.cuda.synchronize(); t3 = time.perf_counter()
         R = g.infer_batch(st["tree"], st["I"], NI, d)                     # b1-b5
@@ -295,8 +298,9 @@ def main():
         g, st = setup(True)
         step(g, st, None)
         g.stats_reset()
+        pc = {}
         for _ in range(k):
-            step(g, st, None)
+            step(g, st, None, pc)
         prof = g.prof()
         g.close(); del g, st
         torch.cuda.empty_cache()
@@ -344,7 +348,13 @@ def main():
                       "unit": "TOP/s", "traffic": None,
                       "note": "ring MAC = 36 int8 limb products on the matrix cores = 72 int8 ops; int8 dense peak 5.0 POP/s; "
                               "%d ring MACs/step" % macs,
-                      "avg_launch_ms": cnt_ms / max(cnt_l, 1), "launches_per_step": cnt_l // k},
+                      "avg_launch_ms": cnt_ms / max(cnt_l, 1), "launches_per_step": cnt_l // k,
+                      "level_launch": {"ms": pc["level_count_ms"] / k, "ring_macs": 6 * N * (1 << h) * CW,
+                                       "achieved": 72.0 * 6 * N * (1 << h) * CW / (pc["level_count_ms"] / k / 1e3) / 1e12,
+                                       "frac": 72.0 * 6 * N * (1 << h) * CW / (pc["level_count_ms"] / k / 1e3) / 1e12 / 5000.0,
+                                       "note": "the contraction of the split-scoring level alone (128 nodes x 260 columns): "
+                                               "the figure above averages it with the label level's, whose 4 class columns "
+                                               "fill a quarter of a 16-wide tile"}},
         }
         for v in kern.values():
             v["frac"] = v["achieved"] / v["peak"]

@@ -47,3 +47,39 @@ def test_static_array_access_equals_gt_oaa(seed):
         gb.oaa_static(gb.share_a(np.arange(4, dtype=np.uint64)), ub, gb.new(big))
     assert e.value.code == gtree.GT_EINVAL
     ga.close(); gb.close()
+
+
+def test_static_array_access_replayed_from_a_hip_graph(seed):
+    """gt_oaa_static is what a caller under HIP graph capture can use: captured once on the
+    context's stream, replayed three times with eager work of the same program and device
+    synchronisations in between, every replay must leave the shares of the eager call (same
+    operation id, hence the same randomness) in the caller's output."""
+    import torch
+    from oracle import Oracle
+    from paper_2305_00645_amd import gtree
+    gtree.load()
+    rng = np.random.default_rng(21)
+    w, n = 150, 3001                                     # columns split over workgroups: the scratch array is used
+    Wp = rng.integers(0, M64, size=w, dtype=np.uint64)
+    u = rng.integers(0, w + 2, size=n).astype(np.uint64)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        g, e, o = gtree.GTree(seed, stream=st), gtree.GTree(seed, stream=st), Oracle(seed)
+        Wg, ug, zg = g.share_a(Wp), g.share_a(u), g.new(n)
+        We, ue = e.share_a(Wp), e.share_a(u)
+        ze = e.oaa(We, ue)
+        st.synchronize()
+        want = ze.planes()
+        assert np.array_equal(ze.components(), o.oaa(o.share(Wp), o.share(u)))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            g.oaa_static(Wg, ug, zg)
+        for replay in range(3):
+            zg.t.zero_()
+            e.mult(We, We)                               # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(zg.planes(), want), replay
+        del graph
+        g.close(); e.close()
