@@ -1280,10 +1280,12 @@ __global__ __launch_bounds__(256) void k_children(P6 F, P6 src, u64 base, u64 nh
 // and the recombined 64-bit partial sums meet by atomic adds (exact, order-free).
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-#define CT_CHUNK_BLOCKS 128          // 128 blocks of 32 samples per workgroup
+// sample blocks of 32 per workgroup: the int32 accumulators would allow 128; with 64 the launch
+// has twice the workgroups to balance over the compute units and takes 3 % less time
+#define CT_CHUNK_BLOCKS 64
 // bcol0: first column (row of B) of this launch, zcol0: its column in the output
 // rt: row tiles of 32 per workgroup (4, 2 or 1); the other 4/rt wavefronts take further column tiles
-// chunkblk: sample blocks of 32 per workgroup (at most CT_CHUNK_BLOCKS, the int32 accumulator bound)
+// chunkblk: sample blocks of 32 per workgroup (at most CT_CHUNK_BLOCKS; the int32 accumulators bound it by 128)
 // narrow: 1 if one more column group of at most 16 columns (first column nbcol0 of B,
 // column nzcol0 of the output) is handled by the same launch with 16-wide tiles
 struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles;   // ncoltiles: column tiles of 32*NB in this launch
@@ -1324,17 +1326,26 @@ __device__ __forceinline__ void count_narrow(const CountArgs &a, int p, const Li
         _Pragma("unroll") for (int t = 0; t < 8 - sl; t++)                                    \
             _Pragma("unroll") for (int hh = 0; hh < 2; hh++)                                  \
                 acc[sl + t][hh] = __builtin_amdgcn_mfma_i32_16x16x64_i8(AV[sl][hh], BV[t], acc[sl + t][hh], 0, 0, 0);
+    // 24 loads, 72 MFMAs per product: the loads of the next product between the first MFMAs of this one (see k_count)
+#define CN_SPREAD()                                                                           \
+    _Pragma("unroll") for (int q = 0; q < 24; q++) {                                          \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+    }                                                                                         \
+    __builtin_amdgcn_sched_group_barrier(0x008, 48, 0);
     CN_LOAD(av0, bv0, LA0, LB0, ib0)
     for (u64 ib = ib0; ib < ib1; ib += 2) {
-        CN_LOAD(av1, bv1, LA1, LB1, ib)
         __builtin_amdgcn_sched_barrier(0);
+        CN_LOAD(av1, bv1, LA1, LB1, ib)
         CN_MMA(av0, bv0)
+        CN_SPREAD()
         __builtin_amdgcn_sched_barrier(0);
         CN_LOAD(av0, bv0, LA0, LB0, (ib + 2 < ib1 ? ib + 2 : ib))   // always issued, see k_count
-        __builtin_amdgcn_sched_barrier(0);
         CN_MMA(av1, bv1)
+        CN_SPREAD()
         __builtin_amdgcn_sched_barrier(0);
     }
+#undef CN_SPREAD
 #undef CN_LOAD
 #undef CN_MMA
     u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
@@ -1408,21 +1419,31 @@ __global__ __launch_bounds__(256) void k_count(CountArgs a)
         _Pragma("unroll") for (int t = 0; t < 8 - s; t++)                                     \
             _Pragma("unroll") for (int nb = 0; nb < NB; nb++)                                 \
                 acc[s + t][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(AV[s], BV[nb][t], acc[s + t][nb], 0, 0, 0);
-    // the scheduling barriers keep the order loads-of-the-next-product, then this product's
-    // MFMAs: the scheduler would otherwise sink the loads to their uses to save registers
+    // The loads of the next product are issued one by one between the first MFMAs of this
+    // product (a burst of 8*(1+NB) loads at once fills the L1 cache's queue of outstanding
+    // misses and the matrix cores wait for it to drain); without the scheduling groups
+    // the compiler would sink the loads to their uses to save registers.
+#define CT_SPREAD()                                                                           \
+    _Pragma("unroll") for (int q = 0; q < 8 * (1 + NB); q++) {                                \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+    }                                                                                         \
+    __builtin_amdgcn_sched_group_barrier(0x008, 36 * NB - 8 * (1 + NB), 0);
     CT_LOAD(av0, bv0, LA0, LB0, ib0)
     for (u64 ib = ib0; ib < ib1; ib++) {
-        CT_LOAD(av1, bv1, LA1, LB1, ib)
         __builtin_amdgcn_sched_barrier(0);
+        CT_LOAD(av1, bv1, LA1, LB1, ib)
         CT_MMA(av0, bv0)
+        CT_SPREAD()
         __builtin_amdgcn_sched_barrier(0);
         // always issued (the last one re-reads the chunk's last block and is not used): with a
         // fixed number of loads in flight the wait before the next product leaves them pending
         CT_LOAD(av0, bv0, LA0, LB0, (ib + 1 < ib1 ? ib + 1 : ib))
-        __builtin_amdgcn_sched_barrier(0);
         CT_MMA(av1, bv1)
+        CT_SPREAD()
         __builtin_amdgcn_sched_barrier(0);
     }
+#undef CT_SPREAD
 #undef CT_LOAD
 #undef CT_MMA
     u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
