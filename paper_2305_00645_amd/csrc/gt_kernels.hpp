@@ -222,8 +222,14 @@ __device__ __forceinline__ u64 load_limbs1(const LimbMat &m, u64 row, u64 i)
     return (y ^ GT_BIAS) - GT_BIAS;
 }
 
-// the per-party operands: L as (own+next, own), B as (own, next)
+// The operands of the contraction z_p = x_p (y_p + y_{p+1}) + x_{p+1} y_p (the three-term
+// product of Sec. II-B with the sum moved to the factor that is written once):
+// B, the columns made at set-up, per party as (own+next, own); L, the leaf one-hot made anew at
+// every level, one matrix per COMPONENT: component j is what party j holds as its own and
+// party j-1 as its next part - the two copies are equal by construction, party j's
+// wavefront writes the one that both holders read.
 struct LimbSet { LimbMat m[3][2]; };
+struct LimbTri { LimbMat m[3]; };
 
 // ---------------------------------------------------------------------------------
 // Elementwise product (Sec. II-B), 8 consecutive elements per lane.
@@ -276,7 +282,7 @@ __global__ __launch_bounds__(192) void k_mult(MultArgs a)
 
 // One-time products of the learning protocol (Sec. V-B): column col = k*K + c,
 // element e = col*N8 + i, z = XT[k][i] * YT[c][i] for i < N, written as limb tiles
-// (own component into B.m[p][0], next into B.m[p][1]).  A step covers 16 groups of 8
+// (own + next component into B.m[p][0], own into B.m[p][1]).  A step covers 16 groups of 8
 // samples of four adjacent columns (blockIdx.y = column quad): the four 32-byte pieces
 // that one wavefront writes per sample block and limb make up a whole 128-byte line
 // of the tile layout.
@@ -320,9 +326,9 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
             W.reshare<8>(snd, rcv, 64u * live8(i0, nv));
             if (act) {
 #pragma unroll
-                for (int s = 0; s < 8; s++) if (i0 + s >= a.N) { snd[s] = 0; rcv[s] = 0; }
-                store_limbs8(a.B.m[p][0], col, i0, snd);
-                store_limbs8(a.B.m[p][1], col, i0, rcv);
+                for (int s = 0; s < 8; s++) { if (i0 + s >= a.N) { snd[s] = 0; rcv[s] = 0; } rcv[s] += snd[s]; }
+                store_limbs8(a.B.m[p][0], col, i0, rcv);
+                store_limbs8(a.B.m[p][1], col, i0, snd);
             }
         }
     }
@@ -340,24 +346,24 @@ __global__ __launch_bounds__(256) void k_y_limbs(P6 YT, LimbSet B, u64 N, u64 N8
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const bool live = i0 + s < N;
-                xo[s] = live ? YT.o[p][c * N8 + i0 + s] : 0; xn[s] = live ? YT.n[p][c * N8 + i0 + s] : 0;
+                xo[s] = live ? YT.o[p][c * N8 + i0 + s] : 0; xn[s] = live ? xo[s] + YT.n[p][c * N8 + i0 + s] : 0;
             }
-            store_limbs8(B.m[p][0], rowbase + c, i0, xo);
-            store_limbs8(B.m[p][1], rowbase + c, i0, xn);
+            store_limbs8(B.m[p][0], rowbase + c, i0, xn);
+            store_limbs8(B.m[p][1], rowbase + c, i0, xo);
         }
     }
 }
 
 // per-sample leaf one-hot back to 64-bit words for export: out[r*N8 + i]
-__global__ __launch_bounds__(256) void k_l_export(LimbSet L, P6 out, u64 nh, u64 N, u64 N8)
+__global__ __launch_bounds__(256) void k_l_export(LimbTri L, P6 out, u64 nh, u64 N, u64 N8)
 {
     const u64 total = nh * N8;
     for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (u64)gridDim.x * blockDim.x) {
         const u64 r = t / N8, i = t % N8;
         for (int p = 0; p < 3; p++) {
-            u64 sum = 0, own = 0;
-            if (i < N) { sum = load_limbs1(L.m[p][0], r, i); own = load_limbs1(L.m[p][1], r, i); }
-            out.o[p][t] = own; out.n[p][t] = sum - own;
+            u64 own = 0, nxt = 0;
+            if (i < N) { own = load_limbs1(L.m[p], r, i); nxt = load_limbs1(L.m[p == 2 ? 0 : p + 1], r, i); }
+            out.o[p][t] = own; out.n[p][t] = nxt;
         }
     }
 }
@@ -381,7 +387,7 @@ struct GridArgs {
     P6 g, out, out2, W1, W2, XT, prev;
     u64 w1off, w2off;
     int epi;
-    LimbSet L;      // GM_STORE: limb tiles of (own+next, own), row = column k
+    LimbTri L;      // GM_STORE: limb tiles of the components, row = column k
     u32 nkc, kchunk;// column ranges per tile and their length
     int lgs;        // GM_STORE: log2 of the lanes that share a column in one step (6 or 4)
     u64 *dacc;      // [2][3][N8] partial inner products when nkc > 1
@@ -662,7 +668,7 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 Wk = ld(a.W1, p, a.w1off + k);
                 if (NDOT == 2) Wk2 = ld(a.W2, p, a.w2off + k);
             }
-            u64 Es[8], Eo[8], xo[8], xn[8];
+            u64 Eo[8], xo[8], xn[8];
             if (MODE == GM_ROWS) { ld8(own_of(a.XT, p) + (u64)k * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + (u64)k * a.N8, i0, nv, xn); }
 #pragma unroll
             for (int s = 0; s < 8; s++) {
@@ -672,13 +678,12 @@ __global__ __launch_bounds__(192, 3) void k_eqgrid(GridArgs a)
                 E.o = ((f >> s) & 1) ? one.o - bA.o : bA.o;
                 E.n = ((f >> s) & 1) ? one.n - bA.n : bA.n;
                 const bool live = i0 + s < nv;
-                if (MODE == GM_STORE) { Es[s] = live ? E.o + E.n : 0; Eo[s] = live ? E.o : 0; }
+                if (MODE == GM_STORE) Eo[s] = live ? E.o : 0;
                 if (MODE == GM_COMMON) { acc[s] += prod3(E, Wk); if (NDOT == 2) acc2[s] += prod3(E, Wk2); }
                 if (MODE == GM_ROWS) { const Sh x = { xo[s], xn[s] }; acc[s] += prod3(E, x); }
             }
             if (MODE == GM_STORE && act) {
-                store_limbs8(a.L.m[p][0], k, i0, Es);
-                store_limbs8(a.L.m[p][1], k, i0, Eo);
+                store_limbs8(a.L.m[p], k, i0, Eo);
             }
             par ^= 1;
             __syncthreads();                           // the material in LDS is overwritten next
@@ -1159,7 +1164,8 @@ __global__ __launch_bounds__(192) void k_count_literal(LitCountArgs a)
             if (row == 0) cv = v ? x : pub(p, 1) - x;
             else {
                 const u64 col = k * a.K + (row - 1);
-                const Sh xy = { load_limbs1(a.B.m[p][0], col, i), load_limbs1(a.B.m[p][1], col, i) };
+                const u64 xyo = load_limbs1(a.B.m[p][1], col, i);
+                const Sh xy = { xyo, load_limbs1(a.B.m[p][0], col, i) - xyo };
                 cv = v ? xy : ld(a.YT, p, (row - 1) * a.N8 + i) - xy;
             }
             s = ld(a.LB, p, r * a.N8 + i);
@@ -1268,7 +1274,7 @@ __global__ __launch_bounds__(256) void k_children(P6 F, P6 src, u64 base, u64 nh
 
 // ---------------------------------------------------------------------------------
 // Statistics counting as a contraction in Z_2^64 (Sec. V-B):
-//   Z_p[r][col] = sum_i (L_p + L_{p+1})[r][i] * B_p[col][i] + L_p[r][i] * B_{p+1}[col][i]
+//   Z_p[r][col] = sum_i L_p[r][i] * (B_p + B_{p+1})[col][i] + L_{p+1}[r][i] * B_p[col][i]
 // with L the per-sample leaf one-hot and B the sample-contiguous columns (XY products,
 // then the K class indicators).  Both operands are uniformly random 64-bit shares, so
 // this is a dense integer GEMM; it runs on the matrix cores in signed 8-bit limbs:
@@ -1288,78 +1294,95 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // chunkblk: sample blocks of 32 per workgroup (at most CT_CHUNK_BLOCKS; the int32 accumulators bound it by 128)
 // narrow: 1 if one more column group of at most 16 columns (first column nbcol0 of B,
 // column nzcol0 of the output) is handled by the same launch with 16-wide tiles
-struct CountArgs { LimbSet L, B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles;   // ncoltiles: column tiles of 32*NB in this launch
+struct CountArgs { LimbTri L; LimbSet B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles;   // ncoltiles: column tiles of 32*NB in this launch
                    u32 narrow; u64 nbcol0; u32 nzcol0; };
 
-// A remainder of at most 16 columns: 32 rows x 16 columns per wavefront with
-// v_mfma_i32_16x16x64_i8 (lane l holds row or column l%16 and the 16 samples
-// 16*(l/16).. of a pair of sample blocks; result C[4*(l/16)+v][l%16]).  It runs inside
-// the launch of the wide groups, as one more column group of each sample chunk, so that
-// its rows of L are found in the L2 cache that the wide groups of the chunk have filled.
-__device__ __forceinline__ void count_narrow(const CountArgs &a, int p, const LimbMat &LA0, const LimbMat &LA1,
-                                             const LimbMat &LB0, const LimbMat &LB1, u64 r0, u64 ib0, u64 ib1, int lane)
+// A remainder of at most 16 columns (the class totals): 16 rows x 16 columns per wavefront
+// with v_mfma_i32_16x16x64_i8 (lane l holds row or column l%16 and the 16 samples
+// 16*(l/16).. of a pair of sample blocks; result C[4*(l/16)+v][l%16]), for ALL THREE
+// parties at once: with so few columns the products are limited by the rate at which L
+// arrives, and the three component matrices of L, fetched once, serve all six products
+//   Z_p += L_p x (B_p + B_{p+1}),  Z_p += L_{p+1} x B_p,   p = 0, 1, 2
+// (each party's sums still come from the two components that party holds).  It runs inside
+// the launch of the wide groups, as one more column group of each sample chunk.
+__device__ __forceinline__ void count_narrow(const CountArgs &a, u64 r0, u64 ib0, u64 ib1, int lane)
 {
-    const u32 lr = lane & 15, kq = lane >> 4;
-    v4i acc[8][2];
+    const u32 lr = lane & 15, kq = lane >> 4, half = (kq & 1) * 16, nreal = a.ncol - a.nzcol0;
+    v4i acc[3][8];
 #pragma unroll
-    for (int u = 0; u < 8; u++)
+    for (int j = 0; j < 3; j++)
 #pragma unroll
-        for (int hh = 0; hh < 2; hh++) acc[u][hh] = v4i{ 0, 0, 0, 0 };
-    const u64 rA0 = r0 + lr, rA1 = r0 + 16 + lr;     // below the padded row count of L, a multiple of 32
+        for (int u = 0; u < 8; u++) acc[j][u] = v4i{ 0, 0, 0, 0 };
+    v4i A[3][8], Bq[2][8];
     // the lane's sample block of a pair; the second block of an odd tail does not belong
     // to this chunk: its lanes load the first block again and multiply zeros
-    const u32 half = (kq & 1) * 16;
-    v4i av0[8][2], bv0[8], av1[8][2], bv1[8];
-#define CN_LOAD(AV, BV, LA, LB, IB)                                                           \
+#define CN_LOAD_A(J, IB)                                                                      \
+    {                                                                                         \
+        const u64 ibl = (IB) + (kq >> 1) >= ib1 ? (IB) : (IB) + (kq >> 1);                    \
+        _Pragma("unroll") for (int sl = 0; sl < 8; sl++)                                      \
+            A[J][sl] = *(const v4i *)(a.L.m[J].base + limb_addr(a.L.m[J], ibl, sl, r0 + lr) + half); \
+    }
+    // product Q: party Q/2, its (own+next) columns for Q even, its own columns for Q odd; the
+    // tile's columns beyond the last real one are not fetched
+#define CN_LOAD_B(BV, Q, IB)                                                                  \
     {                                                                                         \
         const bool tail = (IB) + (kq >> 1) >= ib1;                                            \
         const u64 ibl = tail ? (IB) : (IB) + (kq >> 1);                                       \
+        const LimbMat &LB_ = a.B.m[(Q) >> 1][(Q) & 1];                                        \
         _Pragma("unroll") for (int sl = 0; sl < 8; sl++) {                                    \
-            AV[sl][0] = *(const v4i *)(LA.base + limb_addr(LA, ibl, sl, rA0) + half);         \
-            AV[sl][1] = *(const v4i *)(LA.base + limb_addr(LA, ibl, sl, rA1) + half);         \
-            BV[sl] = *(const v4i *)(LB.base + limb_addr(LB, ibl, sl, a.nbcol0 + lr) + half);  \
-            if (tail) BV[sl] = v4i{ 0, 0, 0, 0 };                                             \
+            BV[sl] = v4i{ 0, 0, 0, 0 };                                                       \
+            if (!tail && lr < nreal) BV[sl] = *(const v4i *)(LB_.base + limb_addr(LB_, ibl, sl, a.nbcol0 + lr) + half); \
         }                                                                                     \
     }
-#define CN_MMA(AV, BV)                                                                        \
+    // L component of product Q: the party's own for Q even, its next for Q odd
+#define CN_MMA(Q, BV)                                                                         \
     _Pragma("unroll") for (int sl = 0; sl < 8; sl++)                                          \
         _Pragma("unroll") for (int t = 0; t < 8 - sl; t++)                                    \
-            _Pragma("unroll") for (int hh = 0; hh < 2; hh++)                                  \
-                acc[sl + t][hh] = __builtin_amdgcn_mfma_i32_16x16x64_i8(AV[sl][hh], BV[t], acc[sl + t][hh], 0, 0, 0);
-    // 24 loads, 72 MFMAs per product: the loads of the next product between the first MFMAs of this one (see k_count)
-#define CN_SPREAD()                                                                           \
-    _Pragma("unroll") for (int q = 0; q < 24; q++) {                                          \
+            acc[(Q) >> 1][sl + t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[(((Q) >> 1) + ((Q) & 1)) % 3][sl], BV[t], acc[(Q) >> 1][sl + t], 0, 0, 0);
+#define CN_SPREAD(NLOADS)                                                                     \
+    _Pragma("unroll") for (int q_ = 0; q_ < (NLOADS); q_++) {                                 \
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                    \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
     }                                                                                         \
-    __builtin_amdgcn_sched_group_barrier(0x008, 48, 0);
-    CN_LOAD(av0, bv0, LA0, LB0, ib0)
+    __builtin_amdgcn_sched_group_barrier(0x008, 36 - (NLOADS), 0);                            \
+    __builtin_amdgcn_sched_barrier(0);
+    // One pair of sample blocks = six products of 36 MFMAs, in the order 0, 5, 1, 2, 3, 4: the two
+    // products that use component 0 of L first, then those of component 1, then of component 2.
+    // A component that has served its two products is fetched for the NEXT pair while the other
+    // two are multiplied (no second set of registers for L); the columns of a product are
+    // fetched during the product before it.  All loads go between the MFMAs one by one.
+    CN_LOAD_A(0, ib0)
+    CN_LOAD_A(1, ib0)
+    CN_LOAD_B(Bq[0], 0, ib0)
     for (u64 ib = ib0; ib < ib1; ib += 2) {
+        // the loads for the pair after the last are issued all the same (they read the chunk's
+        // last pair again and are not used): the number of loads in flight stays fixed
+        const u64 ibn = ib + 2 < ib1 ? ib + 2 : ib;
         __builtin_amdgcn_sched_barrier(0);
-        CN_LOAD(av1, bv1, LA1, LB1, ib)
-        CN_MMA(av0, bv0)
-        CN_SPREAD()
-        __builtin_amdgcn_sched_barrier(0);
-        CN_LOAD(av0, bv0, LA0, LB0, (ib + 2 < ib1 ? ib + 2 : ib))   // always issued, see k_count
-        CN_MMA(av1, bv1)
-        CN_SPREAD()
-        __builtin_amdgcn_sched_barrier(0);
+        CN_LOAD_B(Bq[1], 5, ib) CN_LOAD_A(2, ib)  CN_MMA(0, Bq[0]) CN_SPREAD(16)
+        CN_LOAD_B(Bq[0], 1, ib)                   CN_MMA(5, Bq[1]) CN_SPREAD(8)
+        CN_LOAD_B(Bq[1], 2, ib) CN_LOAD_A(0, ibn) CN_MMA(1, Bq[0]) CN_SPREAD(16)
+        CN_LOAD_B(Bq[0], 3, ib)                   CN_MMA(2, Bq[1]) CN_SPREAD(8)
+        CN_LOAD_B(Bq[1], 4, ib) CN_LOAD_A(1, ibn) CN_MMA(3, Bq[0]) CN_SPREAD(16)
+        CN_LOAD_B(Bq[0], 0, ibn)                  CN_MMA(4, Bq[1]) CN_SPREAD(8)
     }
-#undef CN_SPREAD
-#undef CN_LOAD
+#undef CN_LOAD_A
+#undef CN_LOAD_B
 #undef CN_MMA
-    u64 *Z = a.Zacc + (u64)p * a.nh * a.ncol;
+#undef CN_SPREAD
 #pragma unroll
-    for (int hh = 0; hh < 2; hh++)
+    for (int j = 0; j < 3; j++) {
+        u64 *Z = a.Zacc + (u64)j * a.nh * a.ncol;
 #pragma unroll
         for (int v = 0; v < 4; v++) {
-            const u64 r = r0 + hh * 16 + 4 * kq + v;
+            const u64 r = r0 + 4 * kq + v;
             const u64 c = a.nzcol0 + lr;
             u64 z = 0;
 #pragma unroll
-            for (int u = 0; u < 8; u++) z += (u64)(long long)acc[u][hh][v] << (8 * u);
+            for (int u = 0; u < 8; u++) z += (u64)(long long)acc[j][u][v] << (8 * u);
             if (r < a.nh && c < a.ncol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)z);
         }
+    }
 }
 
 // Workgroup = 4 wavefronts = 128 rows x (32*NB) columns; NB = 2 for full groups of 64
@@ -1371,27 +1394,30 @@ template <int NB>
 __global__ __launch_bounds__(256) void k_count(CountArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int p = blockIdx.z / a.nrowgrp, rg = blockIdx.z % a.nrowgrp;
-    const u32 wr = wave % a.rt, wc = wave / a.rt, cper = 4 / a.rt;   // this wavefront's row / column tile
-    const u64 r0 = ((u64)rg * a.rt + wr) * 32;
-    if (r0 >= a.nh) return;                                   // whole wavefront, no barrier in this kernel
     // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The column
     // groups of one sample chunk read the same rows of L, so they are given
     // consecutive slots of the same XCD: id = slot*8 + xcd, chunk = (slot / ncg)*8 + xcd.
     const u32 ncg = a.ncg + a.narrow, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
     const u32 cg = slot % ncg, chunk = (slot / ncg) * 8 + xcd;
-    if (chunk >= a.nchunk) return;
+    if (chunk >= a.nchunk) return;                            // whole workgroup, no barrier in this kernel
     const u64 ib0 = (u64)chunk * a.chunkblk;
     const u64 ib1 = ib0 + a.chunkblk < a.nblk ? ib0 + a.chunkblk : a.nblk;
-    // product 0: (L_p + L_{p+1}) x B_p, product 1: L_p x B_{p+1}
-    const LimbMat LA0 = p == 0 ? a.L.m[0][0] : (p == 1 ? a.L.m[1][0] : a.L.m[2][0]);
-    const LimbMat LA1 = p == 0 ? a.L.m[0][1] : (p == 1 ? a.L.m[1][1] : a.L.m[2][1]);
-    const LimbMat LB0 = p == 0 ? a.B.m[0][0] : (p == 1 ? a.B.m[1][0] : a.B.m[2][0]);
-    const LimbMat LB1 = p == 0 ? a.B.m[0][1] : (p == 1 ? a.B.m[1][1] : a.B.m[2][1]);
-    if (a.narrow && cg == a.ncg) {                            // the narrow column group of this chunk
-        if (wc == 0) count_narrow(a, p, LA0, LA1, LB0, LB1, r0, ib0, ib1, lane);
+    if (a.narrow && cg == a.ncg) {
+        // the narrow column group of this chunk: its 3*nrowgrp workgroups of 4 wavefronts share
+        // out the row tiles of 16 (each tile for all three parties)
+        const u64 rn = ((u64)blockIdx.z * 4 + wave) * 16;
+        if (rn < a.nh) count_narrow(a, rn, ib0, ib1, lane);
         return;
     }
+    const int p = blockIdx.z / a.nrowgrp, rg = blockIdx.z % a.nrowgrp;
+    const u32 wr = wave % a.rt, wc = wave / a.rt, cper = 4 / a.rt;   // this wavefront's row / column tile
+    const u64 r0 = ((u64)rg * a.rt + wr) * 32;
+    if (r0 >= a.nh) return;                                   // whole wavefront
+    // product 0: L_p x (B_p + B_{p+1}), product 1: L_{p+1} x B_p
+    const LimbMat LA0 = p == 0 ? a.L.m[0] : (p == 1 ? a.L.m[1] : a.L.m[2]);
+    const LimbMat LA1 = p == 0 ? a.L.m[1] : (p == 1 ? a.L.m[2] : a.L.m[0]);
+    const LimbMat LB0 = p == 0 ? a.B.m[0][0] : (p == 1 ? a.B.m[1][0] : a.B.m[2][0]);
+    const LimbMat LB1 = p == 0 ? a.B.m[0][1] : (p == 1 ? a.B.m[1][1] : a.B.m[2][1]);
     const u64 ctile = (u64)cg * cper + wc;                   // column tile of 32*NB
     if (ctile >= a.ncoltiles) return;                         // whole wavefront
     const u64 c0 = a.bcol0 + ctile * (32 * NB);

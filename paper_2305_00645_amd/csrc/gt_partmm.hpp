@@ -4,7 +4,7 @@
 //   M[i]     <- 2 M[i] + sum_k sel[k][i] * X[k][i] + 1   (op+1, zero sharing of stream 0, word i, reshare)
 // fused in one launch: a workgroup = the three parties' wavefronts works on a block of 32
 // samples; each wavefront computes its party's three-term product
-//   (L_p + L_{p+1}) OH_p + L_p OH_{p+1}
+//   L_p (OH_p + OH_{p+1}) + L_{p+1} OH_p
 // as an int8-limb GEMM (64 columns x 32 samples per pass, contraction over the nodes r of
 // both terms), adds the zero sharing, sends its component to the predecessor through LDS
 // and accumulates the row inner product with X; sel never reaches device memory.
@@ -18,7 +18,7 @@
 #pragma once
 #include "gt_kernels.hpp"
 
-// OH as limb bytes: OHL[((p*2 + w)*8 + s)*dpad + k)*rpad + r] = limb s of component (w ? next : own)
+// OH as limb bytes: OHL[((p*2 + w)*8 + s)*dpad + k)*rpad + r] = limb s of (w ? own : own + next)
 // of party p's OH[r][k]; zero for r >= np or k >= d.
 __global__ __launch_bounds__(256) void k_oh_limbs(P6 OH, unsigned char *OHL, u32 np, u32 d, u32 rpad, u32 dpad)
 {
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void k_oh_limbs(P6 OH, unsigned char *OHL, u32
     for (u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (u64)gridDim.x * blockDim.x) {
         const u32 pw = (u32)(t / per), k = (u32)((t % per) / rpad), r = (u32)(t % rpad), p = pw >> 1, w = pw & 1;
         u64 x = 0;
-        if (r < np && k < d) x = (w ? OH.n[p] : OH.o[p])[(u64)r * d + k];
+        if (r < np && k < d) x = OH.o[p][(u64)r * d + k] + (w ? 0 : OH.n[p][(u64)r * d + k]);
         const u64 y = (x + GT_BIAS) ^ GT_BIAS;
 #pragma unroll
         for (int s = 0; s < 8; s++) OHL[(((u64)pw * 8 + s) * dpad + k) * rpad + r] = (unsigned char)(y >> (8 * s));
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void k_oh_limbs(P6 OH, unsigned char *OHL, u32
 
 struct PartMmArgs {
     KCommon c;                 // c.op: the column-selection op; c.op + 1: the row inner product
-    LimbSet L;                 // leaf one-hot of the previous level: m[p][0] = own+next, m[p][1] = own
+    LimbTri L;                 // leaf one-hot of the previous level, one matrix per component
     const unsigned char *OHL;
     P6 XT, M;
     u64 N, N8, nblk;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(192, 1) void k_part_mm(PartMmArgs a)
                 for (int t = 0; t < 2; t++)
 #pragma unroll
                     for (int v = 0; v < 16; v++) acc[u][t][v] = 0;
-            // chunks of 32 node rows: first those of (own+next) x OH_own, then those of own x OH_next.
+            // chunks of 32 node rows: first those of L_p x (OH own+next), then those of L_{p+1} x OH own.
             // The eight limb tiles of the next chunk are in flight while this one is transposed and
             // multiplied (the last iteration loads its own chunk again, unused, so that the number of
             // loads in flight at every wait is the same).  Two passes of the epilogue's zero-sharing
@@ -100,7 +100,8 @@ __global__ __launch_bounds__(192, 1) void k_part_mm(PartMmArgs a)
 #define PM_LOAD(X, CH)                                                                               \
             {                                                                                        \
                 const u32 w_ = (CH) / nrc, rc_ = (CH) % nrc;                                         \
-                const LimbMat LM_ = p == 0 ? a.L.m[0][w_] : (p == 1 ? a.L.m[1][w_] : a.L.m[2][w_]);  \
+                const u32 j_ = (u32)p + w_ >= 3 ? 0 : (u32)p + w_;                                   \
+                const LimbMat LM_ = j_ == 0 ? a.L.m[0] : (j_ == 1 ? a.L.m[1] : a.L.m[2]);            \
                 _Pragma("unroll") for (int s = 0; s < 8; s++)                                        \
                     X[s] = *(const v4i *)(LM_.base + limb_addr(LM_, ib, s, (u64)rc_ * 32) + (lane >> 1) * 32 + (lane & 1) * 16); \
             }

@@ -91,7 +91,7 @@ struct gt_train {
     bool fresh_import;               // state was imported and no level has run since: nothing to export for "last"
     TreeSlot *slot;
     DSh XT, YT;                      // [k][i], [c][i]: sample-contiguous copies of the inputs
-    unsigned char *LQ, *BQ;          // limb tiles: leaf one-hot (own+next, own), columns (own, next)
+    unsigned char *LQ, *BQ;          // limb tiles: leaf one-hot (one matrix per component), columns (own+next, own) per party
     size_t nblk, Lrows, Brows;       // sample blocks of 32, row strides of the limb planes
     DSh M, T, F, C, Cn, gamma, Gn, isLeaf, SD, split;
     DSh S, Q, quo, rem, val[2], idx[2], tval, best, lab;
@@ -529,7 +529,13 @@ static LimbSet limbs_of(unsigned char *base, size_t nblk, size_t rows)
     for (int p = 0; p < 3; p++) for (int m = 0; m < 2; m++) { L.m[p][m].base = base + (size_t)(2 * p + m) * per; L.m[p][m].rows = rows; }
     return L;
 }
-static LimbSet limbs_L(const gt_train *t) { return limbs_of(t->LQ, t->nblk, t->Lrows); }
+static LimbTri limbs_L(const gt_train *t)
+{
+    LimbTri L;
+    const size_t per = t->nblk * 8 * t->Lrows * 32;
+    for (int j = 0; j < 3; j++) { L.m[j].base = t->LQ + (size_t)j * per; L.m[j].rows = t->Lrows; }
+    return L;
+}
 static LimbSet limbs_B(const gt_train *t) { return limbs_of(t->BQ, t->nblk, t->Brows); }
 
 extern "C" int gt_train_destroy(gt_train *t) { if (!t) return GT_EINVAL; (void)hipDeviceSynchronize(); train_free(t); return GT_OK; }
@@ -599,7 +605,7 @@ extern "C" int gt_train_create(gt_ctx *c, const gt_shares *X, const gt_shares *Y
     t->nblk = (N + 31) / 32;
     t->Lrows = std::max<size_t>(32, (nmax + 31) / 32 * 32);
     t->Brows = (CW + 63) / 64 * 64 + 64;
-    const size_t lq = 6 * t->nblk * 8 * t->Lrows * 32, bq = 6 * t->nblk * 8 * t->Brows * 32;
+    const size_t lq = 3 * t->nblk * 8 * t->Lrows * 32, bq = 6 * t->nblk * 8 * t->Brows * 32;
     if (rc == GT_OK && hipMalloc(&t->LQ, lq) != hipSuccess) rc = GT_ENOMEM;
     if (rc == GT_OK && hipMalloc(&t->BQ, bq) != hipSuccess) rc = GT_ENOMEM;
     if (rc == GT_OK && (hipMemsetAsync(t->LQ, 0, lq, s) != hipSuccess || hipMemsetAsync(t->BQ, 0, bq, s) != hipSuccess)) rc = GT_EHIP;
