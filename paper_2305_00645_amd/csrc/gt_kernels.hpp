@@ -1292,10 +1292,10 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // bcol0: first column (row of B) of this launch, zcol0: its column in the output
 // rt: row tiles of 32 per workgroup (4, 2 or 1); the other 4/rt wavefronts take further column tiles
 // chunkblk: sample blocks of 32 per workgroup (at most CT_CHUNK_BLOCKS; the int32 accumulators bound it by 128)
-// narrow: 1 if one more column group of at most 16 columns (first column nbcol0 of B,
-// column nzcol0 of the output) is handled by the same launch with 16-wide tiles
+// nns: slots per chunk (0 = none) for one more column group of at most 16 columns (first column
+// nbcol0 of B, column nzcol0 of the output), handled by the same launch with 16-wide tiles
 struct CountArgs { LimbTri L; LimbSet B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles;   // ncoltiles: column tiles of 32*NB in this launch
-                   u32 narrow; u64 nbcol0; u32 nzcol0; };
+                   u32 nns; u64 nbcol0; u32 nzcol0; };
 
 // A remainder of at most 16 columns (the class totals): 16 rows x 16 columns per wavefront
 // with v_mfma_i32_16x16x64_i8 (lane l holds row or column l%16 and the 16 samples
@@ -1394,22 +1394,25 @@ template <int NB>
 __global__ __launch_bounds__(256) void k_count(CountArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The column
-    // groups of one sample chunk read the same rows of L, so they are given
-    // consecutive slots of the same XCD: id = slot*8 + xcd, chunk = (slot / ncg)*8 + xcd.
-    const u32 ncg = a.ncg + a.narrow, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
-    const u32 cg = slot % ncg, chunk = (slot / ncg) * 8 + xcd;
+    // Workgroups go round-robin to the 8 XCDs, each with its own L2.  The column groups of
+    // one sample chunk, of all three parties, read the same rows of the three components of
+    // L, so they are given consecutive slots of the same XCD: id = slot*8 + xcd; per chunk
+    // 3*ncg wide slots (party-major) and nns narrow ones.
+    const u32 per = 3 * a.ncg + a.nns, id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const u32 sl = slot % per, chunk = (slot / per) * 8 + xcd;
     if (chunk >= a.nchunk) return;                            // whole workgroup, no barrier in this kernel
     const u64 ib0 = (u64)chunk * a.chunkblk;
     const u64 ib1 = ib0 + a.chunkblk < a.nblk ? ib0 + a.chunkblk : a.nblk;
-    if (a.narrow && cg == a.ncg) {
-        // the narrow column group of this chunk: its 3*nrowgrp workgroups of 4 wavefronts share
-        // out the row tiles of 16 (each tile for all three parties)
-        const u64 rn = ((u64)blockIdx.z * 4 + wave) * 16;
+    const u32 rg = blockIdx.z;
+    if (sl >= 3 * a.ncg) {
+        // a narrow slot of this chunk: its workgroups of 4 wavefronts share out the row tiles
+        // of 16 (each tile for all three parties)
+        const u64 rn = ((u64)((sl - 3 * a.ncg) * a.nrowgrp + rg) * 4 + wave) * 16;
         if (rn < a.nh) count_narrow(a, rn, ib0, ib1, lane);
         return;
     }
-    const int p = blockIdx.z / a.nrowgrp, rg = blockIdx.z % a.nrowgrp;
+    const int p = sl / a.ncg;
+    const u32 cg = sl % a.ncg;
     const u32 wr = wave % a.rt, wc = wave / a.rt, cper = 4 / a.rt;   // this wavefront's row / column tile
     const u64 r0 = ((u64)rg * a.rt + wr) * 32;
     if (r0 >= a.nh) return;                                   // whole wavefront

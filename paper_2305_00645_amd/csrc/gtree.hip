@@ -695,7 +695,9 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     const u32 ncg2 = (nfull + cper - 1) / cper, ncg1 = (rem && rem <= 32 && !narrow) ? 1 : 0;
     // sample chunk per workgroup: as long as the int32 accumulators allow, shorter when
     // that is needed to give every compute unit several workgroups
-    const u64 wgs_per_chunk = (u64)(ncg2 + ncg1 + narrow) * 3 * a.nrowgrp;
+    // narrow slots per chunk: a workgroup of the narrow group covers 64 rows (4 tiles of 16, all parties)
+    const u32 nns = narrow ? (u32)((nh + 64ull * a.nrowgrp - 1) / (64ull * a.nrowgrp)) : 0;
+    const u64 wgs_per_chunk = (u64)(3 * (ncg2 + ncg1) + nns) * a.nrowgrp;
     u64 want_chunks = ((u64)c->resident + wgs_per_chunk - 1) / wgs_per_chunk;
     u64 cb = (t->nblk + want_chunks - 1) / want_chunks;
     cb = std::max<u64>(8, std::min<u64>(CT_CHUNK_BLOCKS, cb));
@@ -703,13 +705,13 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     a.nchunk = (u32)((t->nblk + cb - 1) / cb);
     if (nfull || narrow) {
         a.ncg = ncg2; a.ncoltiles = nfull; a.bcol0 = colbase; a.zcol0 = 0;
-        a.narrow = narrow; a.nbcol0 = colbase + (u64)nfull * 64; a.nzcol0 = nfull * 64;
-        GTCHK(launch(c, GT_KC_COUNT, k_count<2>, dim3(((a.nchunk + 7) / 8) * (a.ncg + narrow) * 8, 1, 3 * a.nrowgrp), B256, a));
+        a.nns = nns; a.nbcol0 = colbase + (u64)nfull * 64; a.nzcol0 = nfull * 64;
+        GTCHK(launch(c, GT_KC_COUNT, k_count<2>, dim3(((a.nchunk + 7) / 8) * (3 * a.ncg + nns) * 8, 1, a.nrowgrp), B256, a));
     }
     if (ncg1) {
-        a.narrow = 0;
+        a.nns = 0;
         a.ncg = 1; a.ncoltiles = 1; a.bcol0 = colbase + (u64)nfull * 64; a.zcol0 = nfull * 64;
-        GTCHK(launch(c, GT_KC_COUNT, k_count<1>, dim3(((a.nchunk + 7) / 8) * 8, 1, 3 * a.nrowgrp), B256, a));
+        GTCHK(launch(c, GT_KC_COUNT, k_count<1>, dim3(((a.nchunk + 7) / 8) * 3 * 8, 1, a.nrowgrp), B256, a));
     }
     CountFinArgs f{}; f.c = kc(c, op); f.Zacc = t->Zacc; f.C = t->C.v; f.n = nh * ncol; f.ncol = ncol; f.CW = t->CW; f.colbase = colbase;
     GTCHK(launch(c, GT_KC_SMALL, k_count_fin, dim3(tiles(f.n)), GT_BLOCK, f));
