@@ -31,7 +31,7 @@ EQ_ALU_OPS = EQ_ALU_OPS_DEALER + EQ_ALU_OPS_ONLINE
 # sample's own row, leaf one-hot written as limb tiles
 # (the one-launch inference reads every feature of an instance once per level: 10 levels x 48 B x 64
 # features over 2687 tests per instance at C5)
-EQ_HBM_BYTES = {"eqgrid": 7.4, "eqgrid_rows": 55.4, "eqgrid_store": 48.4, "infer": 13.9}
+EQ_HBM_BYTES = {"eqgrid": 7.4, "eqgrid_rows": 55.4, "eqgrid_store": 24.4, "infer": 15.1}
 SHADER_CLOCK_MEASURED_GHZ = 2.1  # under the equality grid's load (profiles/pmc_sq_micro.md); the peak below uses the nominal 2.4
 
 
@@ -342,7 +342,7 @@ def main():
                        "eq_tests_per_s": n_eq * k / (eq_ms / 1e3), "variants": per_variant},
             "eqgrid_hbm_view": {"bound": "hbm", "achieved": eq_bytes_step * k / (eq_ms / 1e3) / 1e9,
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": eq_bytes_step * k / max(eq_l, 1),
-                                "note": "per-variant HBM bytes per test x tests/s: the protocol messages (200 B per test) pass "
+                                "note": "per-variant HBM bytes per test x tests/s: the protocol messages (24 B per test: 63 + 1 bits from each party) pass "
                                         "through LDS, HBM sees the operands and results only, so this is not the binding limit"},
             "count": {"bound": "mfma", "achieved": 72.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": 5000.0,
                       "unit": "TOP/s", "traffic": None,
