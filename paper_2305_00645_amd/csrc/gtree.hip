@@ -400,6 +400,10 @@ extern "C" int gt_ge_a(gt_ctx *c, const gt_shares *x, const gt_shares *y, size_t
     return T.finish(rc);
 }
 
+// work items (tile, column range) per resident workgroup slot that the column split aims at: every range
+// replays the row's edaBits and opening, so few long ranges beat many short ones (measured: 2 is best
+// for the census-shaped and the 10^6-sample workloads alike; 4 costs 6 % of the former's training time)
+#define GT_GRID_WANT 2
 // the equality grid with its accounting
 static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a, u64 *ext = nullptr, size_t ext_words = 0)
 {
@@ -412,7 +416,7 @@ static int do_grid(gt_ctx *c, int mode, bool has_g, int ndot, GridArgs a, u64 *e
         a.lgs = (mode == GM_STORE && a.w % 4 == 0) ? 4 : 6;
         const u64 kstep = GT_LANES >> a.lgs, nsteps = (a.w + kstep - 1) / kstep;
         // enough work items (tile, column range) to keep every resident workgroup slot busy for several rounds
-        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = 4ull * c->resident;
+        const u64 ntile = (a.N8 / 8 + (GT_LANES >> (6 - a.lgs)) - 1) >> a.lgs, want = (u64)GT_GRID_WANT * c->resident;
         u64 nkc = std::min<u64>(nsteps, std::max<u64>(1, (want + ntile - 1) / ntile));
         a.kchunk = (u32)(((nsteps + nkc - 1) / nkc) * kstep);
         a.nkc = (a.w + a.kchunk - 1) / a.kchunk;
