@@ -302,6 +302,9 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
     // again and again for one tile of samples (cache hits) and each value of X once
     for (u64 tile = blockIdx.x; tile < nt; tile += gridDim.x) {
         const u64 g = tile * 16 + (lane & 15), i0 = g * 8;
+        // the lane's class column of Y stays in registers while the class does not change from one
+        // column quad to the next (never, when K divides 4 or 4 divides K)
+        u64 yo[8] = { 0, 0, 0, 0, 0, 0, 0, 0 }, yn[8] = { 0, 0, 0, 0, 0, 0, 0, 0 }, cyc = ~(u64)0;
         for (u64 q = blockIdx.y; q < nq; q += gridDim.y) {
             const u64 colq = q * 4 + (lane >> 4);
             const bool act = colq < a.ncol && g < ngrp;
@@ -312,9 +315,12 @@ __global__ __launch_bounds__(192, 2) void k_xy(XyArgs a)
             chacha8(K.own, blk, a.c.op, 0, ao);
 #pragma unroll
             for (int s = 0; s < 8; s++) s_prf[p][s * GT_LANES + lane] = ao[s];
-            u64 xo[8], xn[8], yo[8], yn[8];
+            u64 xo[8], xn[8];
             ld8(own_of(a.XT, p) + kx * a.N8, i0, nv, xo); ld8(nxt_of(a.XT, p) + kx * a.N8, i0, nv, xn);
-            ld8(own_of(a.YT, p) + cy * a.N8, i0, nv, yo); ld8(nxt_of(a.YT, p) + cy * a.N8, i0, nv, yn);
+            if (act && cy != cyc) {
+                ld8(own_of(a.YT, p) + cy * a.N8, i0, nv, yo); ld8(nxt_of(a.YT, p) + cy * a.N8, i0, nv, yn);
+                cyc = cy;
+            }
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const Sh x = { xo[s], xn[s] }, y = { yo[s], yn[s] };
