@@ -134,7 +134,10 @@ int gt_mult(gt_ctx *ctx, const gt_shares *x, const gt_shares *y, size_t n, const
 int gt_eq_a(gt_ctx *ctx, const gt_shares *x, const uint64_t *y_pub_dev, size_t n, const gt_shares *z);
 /* z = arithmetic 0/1 sharing of [x >= y]; requires |x - y| < 2^63 as signed numbers */
 int gt_ge_a(gt_ctx *ctx, const gt_shares *x, const gt_shares *y, size_t n, const gt_shares *z);
-/* z[i] = W[u[i]], 0 when u[i] is outside [0, w); linear scan over all w entries */
+/* z[i] = W[u[i]], 0 when u[i] is outside [0, w); linear scan over all w entries.  The w
+ * equality tests of a row compare one shared index with public constants: the index is
+ * masked and opened once per row (64 bits), every entry then costs its AND rounds and its
+ * conversion (63 + 1 bits), the selected entry one reshare (64 bits); 9 rounds. */
 int gt_oaa(gt_ctx *ctx, const gt_shares *W, size_t w, const gt_shares *u, size_t n, const gt_shares *z);
 /* gt_oaa for callers that cannot allocate device memory (code under HIP graph capture,
  * serving loops, harnesses that forbid it): same arguments, same shares, same operation
@@ -183,7 +186,7 @@ int gt_train_set_heuristic(gt_train *tr, int by_reconstruction);
  * leaf one-hot (a variant beyond the paper's listing, which makes two array accesses per
  * sample): OH[r][k] = [T_{h-1}[r] = k] (n_{h-1}*d equality tests, sample-independent),
  * sel[k][i] = sum_r L[r][i] OH[r][k], Dval[i] = sum_k sel[k][i] X[i][k], M <- 2M + Dval + 1.
- * Per party N*d*64 + N*64 bits instead of N*(n_{h-1} + d)*128 + 2*N*64, 10 rounds instead
+ * Per party N*d*64 + N*64 bits instead of N*(n_{h-1} + d)*64 + 4*N*64, 10 rounds instead
  * of 18.  Same tree and statistics; M equals the paper's for every sample in a real leaf (a
  * sample below a node that stopped being one keeps going left).  The level before must have
  * run in this object (GT_ESTATE after gt_train_import).  Depth at most 13.  The first call
