@@ -368,6 +368,8 @@ def main():
 
     if not args.no_paper_shapes:
         out["paper_shape_workloads"] = paper_shapes(np, torch, gtree, wl)
+        # the second half of the metric's name: 10^4 instances through a depth-7 tree with thresholds
+        out["depth7_inference_instances_per_s"] = out["paper_shape_workloads"]["c4_infer_depth7"]["instances_per_s"]
 
     if args.cpu_samples > 0:
         from oracle import Oracle, orc
