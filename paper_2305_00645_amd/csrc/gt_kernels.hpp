@@ -1303,90 +1303,92 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 struct CountArgs { LimbTri L; LimbSet B; u64 nblk; u32 nh, ncol; u64 bcol0; u32 zcol0; u64 *Zacc; u32 nchunk, nrowgrp, ncg, rt, chunkblk, ncoltiles;   // ncoltiles: column tiles of 32*NB in this launch
                    u32 nns; u64 nbcol0; u32 nzcol0; };
 
-// A remainder of at most 16 columns (the class totals): 16 rows x 16 columns per wavefront
-// with v_mfma_i32_16x16x64_i8 (lane l holds row or column l%16 and the 16 samples
+// A remainder of at most 16 columns (the class totals): 16 rows per wavefront with
+// v_mfma_i32_16x16x64_i8 (lane l holds row or column l%16 and the 16 samples
 // 16*(l/16).. of a pair of sample blocks; result C[4*(l/16)+v][l%16]), for ALL THREE
-// parties at once: with so few columns the products are limited by the rate at which L
-// arrives, and the three component matrices of L, fetched once, serve all six products
-//   Z_p += L_p x (B_p + B_{p+1}),  Z_p += L_{p+1} x B_p,   p = 0, 1, 2
-// (each party's sums still come from the two components that party holds).  It runs inside
-// the launch of the wide groups, as one more column group of each sample chunk.
+// parties at once.  With so few columns the products are limited by the rate at which L
+// arrives, so every component L_j of L is fetched once and multiplied by one tile that
+// holds both operands it meets in the three-term products,
+//   columns 0-7:  up to 8 columns of (B_j + B_{j+1})   ->  Z_j     (L_j is party j's own part)
+//   columns 8-15: the same columns of B_{j-1}          ->  Z_{j-1} (and party j-1's next part)
+// (each party's sums still come from the two components that party holds); more than 8
+// columns take a second pass.  It runs inside the launch of the wide groups, as one more
+// column group of each sample chunk.
 __device__ __forceinline__ void count_narrow(const CountArgs &a, u64 r0, u64 ib0, u64 ib1, int lane)
 {
     const u32 lr = lane & 15, kq = lane >> 4, half = (kq & 1) * 16, nreal = a.ncol - a.nzcol0;
-    v4i acc[3][8];
+    for (u32 c0 = 0; c0 < nreal; c0 += 8) {
+        const u32 nc = nreal - c0 < 8 ? nreal - c0 : 8;
+        const bool bcol = (lr & 7) < nc;                 // this lane's column of the tile exists
+        const u64 brow = a.nbcol0 + c0 + (lr & 7);
+        v4i acc[3][8];
 #pragma unroll
-    for (int j = 0; j < 3; j++)
+        for (int j = 0; j < 3; j++)
 #pragma unroll
-        for (int u = 0; u < 8; u++) acc[j][u] = v4i{ 0, 0, 0, 0 };
-    v4i A[3][8], Bq[2][8];
-    // the lane's sample block of a pair; the second block of an odd tail does not belong
-    // to this chunk: its lanes load the first block again and multiply zeros
+            for (int u = 0; u < 8; u++) acc[j][u] = v4i{ 0, 0, 0, 0 };
+        v4i A[3][8], B[3][8];
+        // the lane's sample block of a pair; the second block of an odd tail does not belong
+        // to this chunk: its lanes load the first block again and multiply zeros
 #define CN_LOAD_A(J, IB)                                                                      \
-    {                                                                                         \
-        const u64 ibl = (IB) + (kq >> 1) >= ib1 ? (IB) : (IB) + (kq >> 1);                    \
+        {                                                                                     \
+            const u64 ibl = (IB) + (kq >> 1) >= ib1 ? (IB) : (IB) + (kq >> 1);                \
+            _Pragma("unroll") for (int sl = 0; sl < 8; sl++)                                  \
+                A[J][sl] = *(const v4i *)(a.L.m[J].base + limb_addr(a.L.m[J], ibl, sl, r0 + lr) + half); \
+        }
+#define CN_LOAD_B(J, IB)                                                                      \
+        {                                                                                     \
+            const bool tail = (IB) + (kq >> 1) >= ib1;                                        \
+            const u64 ibl = tail ? (IB) : (IB) + (kq >> 1);                                   \
+            const LimbMat &Bs_ = a.B.m[J][0], &Bo_ = a.B.m[((J) + 2) % 3][1];                 \
+            const unsigned char *bb_ = lr < 8 ? Bs_.base : Bo_.base;                          \
+            _Pragma("unroll") for (int sl = 0; sl < 8; sl++) {                                \
+                B[J][sl] = v4i{ 0, 0, 0, 0 };                                                 \
+                if (!tail && bcol) B[J][sl] = *(const v4i *)(bb_ + limb_addr(Bs_, ibl, sl, brow) + half); \
+            }                                                                                 \
+        }
+#define CN_MMA(J)                                                                             \
         _Pragma("unroll") for (int sl = 0; sl < 8; sl++)                                      \
-            A[J][sl] = *(const v4i *)(a.L.m[J].base + limb_addr(a.L.m[J], ibl, sl, r0 + lr) + half); \
-    }
-    // product Q: party Q/2, its (own+next) columns for Q even, its own columns for Q odd; the
-    // tile's columns beyond the last real one are not fetched
-#define CN_LOAD_B(BV, Q, IB)                                                                  \
-    {                                                                                         \
-        const bool tail = (IB) + (kq >> 1) >= ib1;                                            \
-        const u64 ibl = tail ? (IB) : (IB) + (kq >> 1);                                       \
-        const LimbMat &LB_ = a.B.m[(Q) >> 1][(Q) & 1];                                        \
-        _Pragma("unroll") for (int sl = 0; sl < 8; sl++) {                                    \
-            BV[sl] = v4i{ 0, 0, 0, 0 };                                                       \
-            if (!tail && lr < nreal) BV[sl] = *(const v4i *)(LB_.base + limb_addr(LB_, ibl, sl, a.nbcol0 + lr) + half); \
+            _Pragma("unroll") for (int t = 0; t < 8 - sl; t++)                                \
+                acc[J][sl + t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[J][sl], B[J][t], acc[J][sl + t], 0, 0, 0);
+        // 16 loads between the first MFMAs of the stage, one by one (see k_count)
+#define CN_SPREAD()                                                                           \
+        _Pragma("unroll") for (int q_ = 0; q_ < 16; q_++) {                                   \
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                \
         }                                                                                     \
-    }
-    // L component of product Q: the party's own for Q even, its next for Q odd
-#define CN_MMA(Q, BV)                                                                         \
-    _Pragma("unroll") for (int sl = 0; sl < 8; sl++)                                          \
-        _Pragma("unroll") for (int t = 0; t < 8 - sl; t++)                                    \
-            acc[(Q) >> 1][sl + t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[(((Q) >> 1) + ((Q) & 1)) % 3][sl], BV[t], acc[(Q) >> 1][sl + t], 0, 0, 0);
-#define CN_SPREAD(NLOADS)                                                                     \
-    _Pragma("unroll") for (int q_ = 0; q_ < (NLOADS); q_++) {                                 \
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                    \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
-    }                                                                                         \
-    __builtin_amdgcn_sched_group_barrier(0x008, 36 - (NLOADS), 0);                            \
-    __builtin_amdgcn_sched_barrier(0);
-    // One pair of sample blocks = six products of 36 MFMAs, in the order 0, 5, 1, 2, 3, 4: the two
-    // products that use component 0 of L first, then those of component 1, then of component 2.
-    // A component that has served its two products is fetched for the NEXT pair while the other
-    // two are multiplied (no second set of registers for L); the columns of a product are
-    // fetched during the product before it.  All loads go between the MFMAs one by one.
-    CN_LOAD_A(0, ib0)
-    CN_LOAD_A(1, ib0)
-    CN_LOAD_B(Bq[0], 0, ib0)
-    for (u64 ib = ib0; ib < ib1; ib += 2) {
-        // the loads for the pair after the last are issued all the same (they read the chunk's
-        // last pair again and are not used): the number of loads in flight stays fixed
-        const u64 ibn = ib + 2 < ib1 ? ib + 2 : ib;
+        __builtin_amdgcn_sched_group_barrier(0x008, 20, 0);                                   \
         __builtin_amdgcn_sched_barrier(0);
-        CN_LOAD_B(Bq[1], 5, ib) CN_LOAD_A(2, ib)  CN_MMA(0, Bq[0]) CN_SPREAD(16)
-        CN_LOAD_B(Bq[0], 1, ib)                   CN_MMA(5, Bq[1]) CN_SPREAD(8)
-        CN_LOAD_B(Bq[1], 2, ib) CN_LOAD_A(0, ibn) CN_MMA(1, Bq[0]) CN_SPREAD(16)
-        CN_LOAD_B(Bq[0], 3, ib)                   CN_MMA(2, Bq[1]) CN_SPREAD(8)
-        CN_LOAD_B(Bq[1], 4, ib) CN_LOAD_A(1, ibn) CN_MMA(3, Bq[0]) CN_SPREAD(16)
-        CN_LOAD_B(Bq[0], 0, ibn)                  CN_MMA(4, Bq[1]) CN_SPREAD(8)
-    }
+        // One pair of sample blocks = three stages of 36 MFMAs, one per component.  While a stage
+        // multiplies, L for the stage after the next and the columns for the next are fetched.
+        CN_LOAD_A(0, ib0)
+        CN_LOAD_A(1, ib0)
+        CN_LOAD_B(0, ib0)
+        for (u64 ib = ib0; ib < ib1; ib += 2) {
+            // the loads for the pair after the last are issued all the same (they read the chunk's
+            // last pair again and are not used): the number of loads in flight stays fixed
+            const u64 ibn = ib + 2 < ib1 ? ib + 2 : ib;
+            __builtin_amdgcn_sched_barrier(0);
+            CN_LOAD_A(2, ib)  CN_LOAD_B(1, ib)  CN_MMA(0) CN_SPREAD()
+            CN_LOAD_A(0, ibn) CN_LOAD_B(2, ib)  CN_MMA(1) CN_SPREAD()
+            CN_LOAD_A(1, ibn) CN_LOAD_B(0, ibn) CN_MMA(2) CN_SPREAD()
+        }
 #undef CN_LOAD_A
 #undef CN_LOAD_B
 #undef CN_MMA
 #undef CN_SPREAD
 #pragma unroll
-    for (int j = 0; j < 3; j++) {
-        u64 *Z = a.Zacc + (u64)j * a.nh * a.ncol;
+        for (int j = 0; j < 3; j++) {
+            const int pz = lr < 8 ? j : (j + 2) % 3;     // the party whose sum this column of the tile belongs to
+            u64 *Z = a.Zacc + (u64)pz * a.nh * a.ncol;
 #pragma unroll
-        for (int v = 0; v < 4; v++) {
-            const u64 r = r0 + 4 * kq + v;
-            const u64 c = a.nzcol0 + lr;
-            u64 z = 0;
+            for (int v = 0; v < 4; v++) {
+                const u64 r = r0 + 4 * kq + v;
+                const u64 c = a.nzcol0 + c0 + (lr & 7);
+                u64 z = 0;
 #pragma unroll
-            for (int u = 0; u < 8; u++) z += (u64)(long long)acc[j][u][v] << (8 * u);
-            if (r < a.nh && c < a.ncol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)z);
+                for (int u = 0; u < 8; u++) z += (u64)(long long)acc[j][u][v] << (8 * u);
+                if (r < a.nh && bcol) atomicAdd((unsigned long long *)&Z[r * a.ncol + c], (unsigned long long)z);
+            }
         }
     }
 }
