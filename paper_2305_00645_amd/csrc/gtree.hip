@@ -693,14 +693,13 @@ static int count(gt_ctx *c, gt_train *t, u32 h, bool totals_only)
     // narrow group, one of 17 to 32 columns runs in a launch of its own with a 32-wide tile
     const u32 rem = ncol % 64, nfull = ncol / 64 + (rem > 32 ? 1 : 0);
     // (a remainder of at most 16 columns with no full group beside it - the class totals of the
-    // label level - runs on the 16-wide tiles alone: half the matrix-core work of a padded 32-wide
-    // tile, measured 2.15 ms instead of 2.56 ms at 256 nodes x 10^6 samples)
+    // label level - runs on the 16-wide tiles alone)
     const u32 narrow = (rem && rem <= 16) ? 1 : 0;
     const u32 ncg2 = (nfull + cper - 1) / cper, ncg1 = (rem && rem <= 32 && !narrow) ? 1 : 0;
-    // sample chunk per workgroup: as long as the int32 accumulators allow, shorter when
-    // that is needed to give every compute unit several workgroups
     // narrow slots per chunk: a workgroup of the narrow group covers 64 rows (4 tiles of 16, all parties)
     const u32 nns = narrow ? (u32)((nh + 64ull * a.nrowgrp - 1) / (64ull * a.nrowgrp)) : 0;
+    // sample chunk per workgroup: at most CT_CHUNK_BLOCKS blocks, shorter when that is needed to
+    // give every compute unit several workgroups
     const u64 wgs_per_chunk = (u64)(3 * (ncg2 + ncg1) + nns) * a.nrowgrp;
     u64 want_chunks = ((u64)c->resident + wgs_per_chunk - 1) / wgs_per_chunk;
     u64 cb = (t->nblk + want_chunks - 1) / want_chunks;
