@@ -347,7 +347,8 @@ def main():
             "count": {"bound": "mfma", "achieved": 72.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": 5000.0,
                       "unit": "TOP/s", "traffic": None,
                       "note": "ring MAC = 36 int8 limb products on the matrix cores = 72 int8 ops; int8 dense peak 5.0 POP/s; "
-                              "%d ring MACs/step" % macs,
+                              "%d ring MACs/step (every party's two products are computed; the leaf one-hot is stored once per "
+                              "component, the copy that both of its holders read)" % macs,
                       "avg_launch_ms": cnt_ms / max(cnt_l, 1), "launches_per_step": cnt_l // k,
                       "level_launch": {"ms": pc["level_count_ms"] / k, "ring_macs": 6 * N * (1 << h) * CW,
                                        "achieved": 72.0 * 6 * N * (1 << h) * CW / (pc["level_count_ms"] / k / 1e3) / 1e12,
