@@ -262,6 +262,19 @@ def test_train_limits_of_classes_and_precision(mods, seed):
     run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=3), tau=20)
 
 
+@pytest.mark.parametrize("N,d,K,H", [(600, 4, 16, 3), (300, 3, 12, 2), (700, 5, 2, 3), (900, 21, 3, 3), (500, 40, 2, 4)])
+def test_train_column_group_remainders(mods, seed, N, d, K, H):
+    """The statistics contraction splits its d*K+K columns into groups of 64 and a remainder that
+    takes its own path: 16 columns beside a full group (two passes of the packed 16-wide tile), 12
+    class columns alone at the label level, 12 columns with no full group at all, 2 beside a full
+    group, and a remainder of 18 (a launch of its own)."""
+    rng = np.random.default_rng(1000 * d + K)
+    X = (rng.random((N, d)) < 0.45).astype(np.uint64)
+    y = (X[:, 0].astype(np.int64) * 3 + X[:, d - 1].astype(np.int64) + rng.integers(0, 2, N)) % K
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    run_train_pair(mods, seed, dict(X=X, Y=Y, y=y, N=N, d=d, K=K, H=H), tau=12)
+
+
 def test_train_deep_tree_few_samples(mods, seed):
     """Far more nodes than samples: 2^11 leaves for 40 samples, most nodes empty."""
     rng = np.random.default_rng(98)
