@@ -193,3 +193,76 @@ def test_c4_full_inference(seed):
     assert ro == rg and np.array_equal(wo, wg)
     assert np.array_equal(o.wire_bits(), g.wire_bits_dev())
     tree.close(); g.close(); o.close()
+
+
+def test_maximum_sample_count(seed):
+    """GT_MAX_N = 2^20 samples (the bound that keeps the Gini terms below 2^40): a level and the
+    label level on 2 columns, every share against the oracle, the split and the statistics
+    against plain integer arithmetic; one sample more is refused."""
+    import torch
+    from oracle import Oracle, X_M, X_C, X_SD, X_SCORE, X_T
+    from paper_2305_00645_amd import gtree
+    N, d, K, H = 1 << 20, 2, 2, 1
+    rng = np.random.default_rng(2020)
+    X = (rng.random((N, d)) < np.array([0.5, 0.3])).astype(np.uint64)
+    y = (X[:, 1] ^ (rng.random(N) < 0.05)).astype(np.int64)          # column 1 decides the class, 5 % flipped
+    Y = np.zeros((N, K), dtype=np.uint64); Y[np.arange(N), y] = 1
+    o, g = Oracle(seed, K=K), gtree.GTree(seed, K=K)
+    xg, yg = g.share_a(X.reshape(-1)), g.share_a(Y.reshape(-1))
+    g.train_create(xg, yg, N, d, H)
+    o.train_create(o.share(X.reshape(-1)), o.share(Y.reshape(-1)), N, d, H)
+    g.train_level(0); o.train_level(0)
+    for what, name in ((X_SD, "SD"), (X_C, "C"), (X_SCORE, "score"), (X_M, "M")):
+        _same(g.train_export(what), o.train_export(what), name)
+    C = g.rec(g.train_export(X_C)).astype(np.int64)
+    want = [int(((X[:, k] == 1) & (y == c)).sum()) for k in range(d) for c in range(K)] + [int((y == c).sum()) for c in range(K)]
+    assert C.tolist() == want
+    assert g.rec(g.train_export(X_SD)).tolist() == [1]
+    fo, lo = o.train_finish()
+    tree = g.train_finish()
+    fg, lg = tree.export()
+    _same(fg, fo, "tree features"); _same(lg, lo, "tree labels")
+    _same(g.train_export(X_M), o.train_export(X_M), "M after the label level")
+    assert g.rec(lg).tolist() == [0, 1]
+    ro, wo = o.stats(); rg, wg, _ = g.stats()
+    assert ro == rg and np.array_equal(wo, wg) and np.array_equal(o.wire_bits(), g.wire_bits_dev())
+    tree.close()
+    big = g.new((N + 1) * d)
+    with pytest.raises(gtree.GtError) as e:
+        g.train_create(big, g.new((N + 1) * K), N + 1, d, H)
+    assert e.value.code == gtree.GT_EINVAL
+    g.close(); o.close()
+    torch.cuda.empty_cache()
+
+
+def test_maximum_depth(seed):
+    """GT_MAX_DEPTH = 16 decision levels: inference through a random complete tree of 2^16 - 1
+    nodes and 2^16 leaves (the last array access scans 65,536 labels per instance), every share
+    against the oracle and the labels against plaintext traversal; depth 17 is refused."""
+    import torch
+    from oracle import Oracle
+    from paper_2305_00645_amd import gtree
+    H, d, NI = 16, 5, 21
+    rng = np.random.default_rng(1616)
+    feat = rng.integers(0, d, size=(1 << H) - 1).astype(np.uint64)
+    leaf = rng.integers(0, 3, size=1 << H).astype(np.uint64)
+    I = (rng.random((NI, d)) < 0.5).astype(np.uint64)
+    o, g = Oracle(seed), gtree.GTree(seed)
+    tree = g.tree_import(g.share_a(feat), None, g.share_a(leaf), H)
+    fo, lo = o.share(feat), o.share(leaf)
+    Rg = g.infer_batch(tree, g.share_a(I.reshape(-1)), NI, d)
+    Ro = o.infer(fo, None, lo, H, o.share(I.reshape(-1)), NI, d)
+    _same(Rg, Ro, "labels")
+    T = np.concatenate([feat, leaf]).astype(np.int64)
+    idx = np.zeros(NI, dtype=np.int64)
+    for _ in range(H):
+        idx = 2 * idx + 1 + I[np.arange(NI), T[idx]].astype(np.int64)
+    assert np.array_equal(g.rec(Rg).astype(np.int64), T[idx])
+    ro, wo = o.stats(); rg, wg, _ = g.stats()
+    assert ro == rg and np.array_equal(wo, wg) and np.array_equal(o.wire_bits(), g.wire_bits_dev())
+    tree.close()
+    with pytest.raises(gtree.GtError) as e:
+        g.tree_import(g.new((1 << 17) - 1), None, g.new(1 << 17), 17)
+    assert e.value.code == gtree.GT_EINVAL
+    g.close(); o.close()
+    torch.cuda.empty_cache()
