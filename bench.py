@@ -363,6 +363,21 @@ def main():
         dom = "eqgrid" if eq_ms >= max(prof[c][0] for c in prof if c not in n_var) else max(
             (c for c in prof if c not in n_var), key=lambda c: prof[c][0])
         dom = dom if dom in kern else "eqgrid"
+        # what a plain streaming kernel of the library reaches on this machine, beside the published 8 TB/s:
+        # gt_reconstruct_a reads three words and writes one per element
+        gs = gtree.GTree(wl.PROTOCOL_SEED, tau=16, K=K)
+        sv = gs.new(1 << 26)
+        pv = torch.zeros(1 << 26, dtype=torch.int64, device="cuda:0")
+        gs.L.gt_reconstruct_a(gs.ctx, gtree._ref(sv), pv.data_ptr(), sv.n)
+        torch.cuda.synchronize(); c0 = time.perf_counter()
+        for _ in range(10):
+            gs.L.gt_reconstruct_a(gs.ctx, gtree._ref(sv), pv.data_ptr(), sv.n)
+        torch.cuda.synchronize()
+        stream_gbs = 10 * 4 * 8 * (1 << 26) / (time.perf_counter() - c0) / 1e9
+        gs.close(); del sv, pv
+        torch.cuda.empty_cache()
+        out["measured_stream_GBps"] = {"value": stream_gbs, "frac_of_hbm_peak": stream_gbs / HBM_PEAK_GBS,
+                                       "kernel": "gt_reconstruct_a on 2^26 words (3 reads + 1 write per word), 10 launches"}
         out["roofline"] = dict(kern[dom], kernel=dom)
         out["kernel_classes_ms_per_step"] = cls_ms
         out["roofline_other"] = {c: v for c, v in kern.items() if c != dom}
