@@ -317,7 +317,10 @@ def main():
         eq_ms = sum(prof[c][0] for c in n_var)
         eq_l = sum(prof[c][1] for c in n_var)
         cnt_ms, cnt_l = prof["count"]
-        macs = 3 * 2 * N * ((1 << h) * CW + (1 << (h + 1)) * K)         # ring MACs per step, all parties
+        macs_level, macs_label = 6 * N * (1 << h) * CW, 6 * N * (1 << (h + 1)) * K   # ring MACs, all parties
+        lvl_cnt_ms = pc["level_count_ms"] / k
+        lbl_cnt_ms = max(cnt_ms / k - lvl_cnt_ms, 1e-9)
+        lbl_bytes = 8.0 * N * (3 * (1 << (h + 1)) + 6 * K)            # L once per component, the K columns (own+next, own) per party
         eq_bytes_step = sum(EQ_HBM_BYTES[c] * n_var[c] for c in n_var)
         per_variant = {c: {"tests_per_step": n_var[c], "ms_per_step": prof[c][0] / k, "launches_per_step": prof[c][1] // k,
                            "tests_per_s": n_var[c] * k / (prof[c][0] / 1e3) if prof[c][0] else None,
@@ -344,18 +347,23 @@ def main():
                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": eq_bytes_step * k / max(eq_l, 1),
                                 "note": "per-variant HBM bytes per test x tests/s: the protocol messages (24 B per test: 63 + 1 bits from each party) pass "
                                         "through LDS, HBM sees the operands and results only, so this is not the binding limit"},
-            "count": {"bound": "mfma", "achieved": 72.0 * macs * k / (cnt_ms / 1e3) / 1e12, "peak": 5000.0,
-                      "unit": "TOP/s", "traffic": None,
-                      "note": "ring MAC = 36 int8 limb products on the matrix cores = 72 int8 ops; int8 dense peak 5.0 POP/s; "
-                              "%d ring MACs/step (every party's two products are computed; the leaf one-hot is stored once per "
-                              "component, the copy that both of its holders read)" % macs,
-                      "avg_launch_ms": cnt_ms / max(cnt_l, 1), "launches_per_step": cnt_l // k,
-                      "level_launch": {"ms": pc["level_count_ms"] / k, "ring_macs": 6 * N * (1 << h) * CW,
-                                       "achieved": 72.0 * 6 * N * (1 << h) * CW / (pc["level_count_ms"] / k / 1e3) / 1e12,
-                                       "frac": 72.0 * 6 * N * (1 << h) * CW / (pc["level_count_ms"] / k / 1e3) / 1e12 / 5000.0,
-                                       "note": "the contraction of the split-scoring level alone (128 nodes x 260 columns): "
-                                               "the figure above averages it with the label level's, whose 4 class columns "
-                                               "fill a quarter of a 16-wide tile"}},
+            # the two launches of the contraction have different bounds: the level's (128 nodes x 260 columns)
+            # is matrix-core work, the label level's (256 nodes x 4 class columns) streams L once
+            "count": {"bound": "mfma", "achieved": 72.0 * macs_level / (lvl_cnt_ms / 1e3) / 1e12, "peak": 5000.0,
+                      "unit": "TOP/s", "traffic": 19.0e9,
+                      "note": "the contraction of the split-scoring level: ring MAC = 36 int8 limb products on the matrix "
+                              "cores = 72 int8 ops; int8 dense peak 5.0 POP/s; %d ring MACs (every party's two products "
+                              "are computed; the leaf one-hot is stored once per component, the copy that both of its "
+                              "holders read); traffic: FETCH_SIZE + WRITE_SIZE of this launch in profiles/pmc_traffic_micro.md "
+                              "(compulsory 15.6 GB)" % macs_level,
+                      "avg_launch_ms": lvl_cnt_ms, "launches_per_step": 1},
+            "count_label_level": {"bound": "hbm", "achieved": lbl_bytes / (lbl_cnt_ms / 1e3) / 1e9, "peak": HBM_PEAK_GBS,
+                                  "unit": "GB/s", "traffic": lbl_bytes,
+                                  "note": "class totals of the label level (%d nodes x %d class columns on 16-wide tiles): "
+                                          "the three components of L and the class columns are read once "
+                                          "(algorithmic bytes); %d ring MACs = %.2f of the int8 peak"
+                                          % (1 << (h + 1), K, macs_label, 72.0 * macs_label / (lbl_cnt_ms / 1e3) / 1e12 / 5000.0),
+                                  "avg_launch_ms": lbl_cnt_ms, "launches_per_step": 1},
         }
         for v in kern.values():
             v["frac"] = v["achieved"] / v["peak"]
